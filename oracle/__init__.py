@@ -1,0 +1,369 @@
+"""CPU oracle for the INT4 fixed-point backward pass -- TEST INFRASTRUCTURE ONLY.
+
+A plain double / int64 implementation of what the GPU library computes, written
+from the paper (Kim et al., "Toward INT4 Fixed-Point Training via Exploring
+Quantization Error for Gradients"): the uniform quantizer of Eq. (1)-(4), the
+gradient clip value c_g = gamma * g_max of Sec. 3.1, the clip-out count and the
+clipping-factor update of Eq. (15)-(16) / Alg. 1, and the two integer
+contractions of the backward pass with the denormalisation of Eq. (4).
+
+Only tests, the smoke entry and the benchmark's cpu_baseline leg may import
+this package.  It shares nothing with the HIP path and imports nothing from it.
+The arithmetic lives in ``lbt_oracle.c`` (compiled with gcc on first use);
+this file marshals numpy arrays and strings the steps together in the paper's
+order.  ``diagnostics.py`` holds the error measures E(G), E(G_L), the bound
+U(G_L) and its derivative, used to pin the oracle against the paper's closed
+forms.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from dataclasses import dataclass, field
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "lbt_oracle.c")
+_LIB = os.path.join(_HERE, "liblbt_oracle.so")
+
+OK, NONFINITE, ZERO_GRAD = 0, 1, 2
+NEAREST, STOCHASTIC = 0, 1
+
+
+def build(force: bool = False) -> str:
+    """Compile lbt_oracle.c with gcc (no fused multiply-add, OpenMP)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        subprocess.check_call(
+            ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
+             "-fno-fast-math", "-Wall", "-Wextra", "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def _L():
+    global _lib
+    if _lib is None:
+        lib = C.CDLL(build())
+        i64, u64, f32, f64, i32 = C.c_int64, C.c_uint64, C.c_float, C.c_double, C.c_int
+        p = C.c_void_p
+        lib.orc_num_threads.restype = i32
+        lib.orc_philox4x32_10.argtypes = [p, p, p]
+        lib.orc_r16.argtypes = [u64, u64, u64]
+        lib.orc_r16.restype = C.c_uint32
+        lib.orc_max.argtypes = [p, i64, i32, p]
+        lib.orc_max.restype = i32
+        lib.orc_clip_value.argtypes = [f64, f32]
+        lib.orc_clip_value.restype = f32
+        lib.orc_levels.argtypes = [i32, i32]
+        lib.orc_levels.restype = i32
+        lib.orc_scale.argtypes = [f32, i32, i32]
+        lib.orc_scale.restype = f64
+        lib.orc_quantize.argtypes = [p, i64, f32, i32, i32, i32, u64, u64, p, p]
+        lib.orc_pack_nibbles.argtypes = [p, i64, p]
+        lib.orc_update_interval.argtypes = [p, f64, f64, f64, f64, i32, u64, u64]
+        lib.orc_update_interval.restype = i32
+        lib.orc_linear_dx.argtypes = [p, p, i64, i64, i64, p]
+        lib.orc_linear_dw.argtypes = [p, p, i64, i64, i64, p]
+        conv = [p, p] + [i64] * 9
+        lib.orc_conv2d_dx.argtypes = conv + [p]
+        lib.orc_conv2d_dw.argtypes = conv + [p]
+        lib.orc_conv2d_dx_at.argtypes = conv + [p, i64, p]
+        lib.orc_conv2d_dw_at.argtypes = conv + [p, i64, p]
+        lib.orc_dequant.argtypes = [p, i64, f64, f64, p]
+        _lib = lib
+    return _lib
+
+
+def _ptr(a: np.ndarray):
+    return a.ctypes.data_as(C.c_void_p)
+
+
+def _f32(a) -> np.ndarray:
+    a = np.ascontiguousarray(a)
+    assert a.dtype == np.float32, "oracle inputs are the same fp32 bits the GPU sees"
+    return a
+
+
+def _i32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def num_threads() -> int:
+    return int(_L().orc_num_threads())
+
+
+# ----------------------------------------------------------------------------
+# primitives
+# ----------------------------------------------------------------------------
+def philox4x32_10(ctr, key):
+    c = np.asarray(ctr, dtype=np.uint32).copy()
+    k = np.asarray(key, dtype=np.uint32).copy()
+    out = np.zeros(4, dtype=np.uint32)
+    _L().orc_philox4x32_10(_ptr(c), _ptr(k), _ptr(out))
+    return out
+
+
+def r16(e: int, seed: int, step: int) -> int:
+    return int(_L().orc_r16(e, seed, step))
+
+
+def tensor_max(x, use_abs: bool = True):
+    """(max |x| or max x as fp32, status)."""
+    x = _f32(x)
+    out = C.c_float(0.0)
+    st = _L().orc_max(_ptr(x), x.size, int(use_abs), C.byref(out))
+    return np.float32(out.value), int(st)
+
+
+def clip_value(gamma: float, gmax) -> np.float32:
+    return np.float32(_L().orc_clip_value(float(gamma), float(gmax)))
+
+
+def levels(bits: int, is_unsigned: bool = False) -> int:
+    return int(_L().orc_levels(bits, int(is_unsigned)))
+
+
+def scale(c, bits: int, is_unsigned: bool = False) -> float:
+    return float(_L().orc_scale(float(c), bits, int(is_unsigned)))
+
+
+def quantize(x, c, bits: int = 4, is_unsigned: bool = False, rounding: int = NEAREST,
+             seed: int = 0, step: int = 0):
+    """Eq. (1)-(4) with clip value c: (int32 codes shaped like x, clip-out count)."""
+    x = _f32(x)
+    code = np.empty(x.shape, dtype=np.int32)
+    n_out = C.c_uint64(0)
+    _L().orc_quantize(_ptr(x), x.size, float(c), bits, int(is_unsigned), rounding,
+                      seed, step, _ptr(code), C.byref(n_out))
+    return code, int(n_out.value)
+
+
+def pack_nibbles(code) -> np.ndarray:
+    code = _i32(code).reshape(-1)
+    out = np.zeros((code.size + 1) // 2, dtype=np.uint8)
+    _L().orc_pack_nibbles(_ptr(code), code.size, _ptr(out))
+    return out
+
+
+# ----------------------------------------------------------------------------
+# per-layer gradient-quantizer state (the scalars of Alg. 1)
+# ----------------------------------------------------------------------------
+@dataclass
+class GradState:
+    gamma: float = 1.0
+    alpha: float = 1e-3
+    beta: float = 1e-3
+    gamma_min: float = 1e-3
+    gamma_max: float = 1.0
+    bits: int = 4
+    status: int = OK
+    step: int = 0
+    n_total: int = 0
+    n_out: int = 0
+    gmax: np.float32 = field(default_factory=lambda: np.float32(0))
+    clip: np.float32 = field(default_factory=lambda: np.float32(0))
+    scale: np.float32 = field(default_factory=lambda: np.float32(0))
+
+
+def quantize_grad(g, st: GradState, seed: int = 0, rounding: int = NEAREST):
+    """Gradient quantizer of one layer: g_max, c_g = gamma*g_max, codes, N(G_out).
+
+    Writes gmax, clip, scale, n_total, n_out, status into ``st``; gamma and step
+    are left alone (the update is a separate call, as in Alg. 1 whose input is
+    the clip-out set of the quantization just done).  Returns int32 codes.
+    """
+    g = _f32(g)
+    gmax, status = tensor_max(g, use_abs=True)
+    st.status = status
+    st.n_total = int(g.size)
+    if status == NONFINITE:
+        return None
+    if status == ZERO_GRAD:
+        st.gmax = np.float32(0)
+        st.clip = np.float32(0)
+        st.scale = np.float32(0)
+        st.n_out = 0
+        return np.zeros(g.shape, dtype=np.int32)
+    c = clip_value(st.gamma, gmax)
+    code, n_out = quantize(g, c, st.bits, False, rounding, seed, st.step)
+    st.gmax, st.clip, st.n_out = gmax, c, n_out
+    st.scale = np.float32(scale(c, st.bits, False))
+    return code
+
+
+def update_interval(st: GradState) -> int:
+    """Alg. 1 on the counts of the last quantize_grad; returns the sign used."""
+    if st.status != OK:
+        return 0
+    g = C.c_double(st.gamma)
+    sg = _L().orc_update_interval(C.byref(g), st.alpha, st.beta, st.gamma_min, st.gamma_max,
+                                  st.bits, st.n_out, st.n_total)
+    st.gamma = float(g.value)
+    st.step += 1
+    return int(sg)
+
+
+def quantize_operand(x, c: float, is_unsigned: bool, bits: int = 4):
+    """Weights / activations: Eq. (2) or (3), nearest rounding.
+
+    c <= 0 selects the per-tensor maximum (max |x| signed, max x unsigned).
+    Returns (codes, clip value fp32, scale double, status).
+    """
+    x = _f32(x)
+    status = OK
+    if not (c > 0):
+        m, status = tensor_max(x, use_abs=not is_unsigned)
+        if status == NONFINITE:
+            return None, np.float32(0), 0.0, status
+        c = m
+        status = OK  # an all-zero operand is legal: codes 0, scale 0
+    c = np.float32(c)
+    code, _ = quantize(x, c, bits, is_unsigned, NEAREST)
+    return code, c, scale(c, bits, is_unsigned), status
+
+
+# ----------------------------------------------------------------------------
+# integer contractions
+# ----------------------------------------------------------------------------
+def linear_dx(qG, qW):
+    qG, qW = _i32(qG), _i32(qW)
+    M, N = qG.shape
+    K, N2 = qW.shape
+    assert N == N2
+    acc = np.empty((M, K), dtype=np.int64)
+    _L().orc_linear_dx(_ptr(qG), _ptr(qW), M, K, N, _ptr(acc))
+    return acc
+
+
+def linear_dw(qX, qG):
+    qX, qG = _i32(qX), _i32(qG)
+    M, K = qX.shape
+    M2, N = qG.shape
+    assert M == M2
+    acc = np.empty((K, N), dtype=np.int64)
+    _L().orc_linear_dw(_ptr(qX), _ptr(qG), M, K, N, _ptr(acc))
+    return acc
+
+
+def _conv_dims(x_shape, w_shape, stride, pad):
+    N, Cc, H, W = x_shape
+    K, C2, R, S = w_shape
+    assert Cc == C2
+    P = (H + 2 * pad - R) // stride + 1
+    Q = (W + 2 * pad - S) // stride + 1
+    return N, Cc, H, W, K, R, S, P, Q
+
+
+def conv2d_dx(qG, qW, x_shape, stride: int, pad: int):
+    qG, qW = _i32(qG), _i32(qW)
+    N, Cc, H, W, K, R, S, P, Q = _conv_dims(x_shape, qW.shape, stride, pad)
+    assert qG.shape == (N, K, P, Q)
+    acc = np.empty((N, Cc, H, W), dtype=np.int64)
+    _L().orc_conv2d_dx(_ptr(qG), _ptr(qW), N, Cc, H, W, K, R, S, stride, pad, _ptr(acc))
+    return acc
+
+
+def conv2d_dw(qG, qX, w_shape, stride: int, pad: int):
+    qG, qX = _i32(qG), _i32(qX)
+    N, Cc, H, W, K, R, S, P, Q = _conv_dims(qX.shape, w_shape, stride, pad)
+    assert qG.shape == (N, K, P, Q)
+    acc = np.empty((K, Cc, R, S), dtype=np.int64)
+    _L().orc_conv2d_dw(_ptr(qG), _ptr(qX), N, Cc, H, W, K, R, S, stride, pad, _ptr(acc))
+    return acc
+
+
+def conv2d_dx_at(qG, qW, x_shape, stride: int, pad: int, flat_idx):
+    qG, qW = _i32(qG), _i32(qW)
+    N, Cc, H, W, K, R, S, P, Q = _conv_dims(x_shape, qW.shape, stride, pad)
+    idx = np.ascontiguousarray(flat_idx, dtype=np.int64)
+    acc = np.empty(idx.size, dtype=np.int64)
+    _L().orc_conv2d_dx_at(_ptr(qG), _ptr(qW), N, Cc, H, W, K, R, S, stride, pad,
+                          _ptr(idx), idx.size, _ptr(acc))
+    return acc
+
+
+def conv2d_dw_at(qG, qX, w_shape, stride: int, pad: int, flat_idx):
+    qG, qX = _i32(qG), _i32(qX)
+    N, Cc, H, W, K, R, S, P, Q = _conv_dims(qX.shape, w_shape, stride, pad)
+    idx = np.ascontiguousarray(flat_idx, dtype=np.int64)
+    acc = np.empty(idx.size, dtype=np.int64)
+    _L().orc_conv2d_dw_at(_ptr(qG), _ptr(qX), N, Cc, H, W, K, R, S, stride, pad,
+                          _ptr(idx), idx.size, _ptr(acc))
+    return acc
+
+
+def dequant(acc, s_a: float, s_b: float) -> np.ndarray:
+    acc = np.ascontiguousarray(acc, dtype=np.int64)
+    out = np.empty(acc.shape, dtype=np.float32)
+    _L().orc_dequant(_ptr(acc), acc.size, float(s_a), float(s_b), _ptr(out))
+    return out
+
+
+# ----------------------------------------------------------------------------
+# whole-layer backward, in the order of the method
+# ----------------------------------------------------------------------------
+@dataclass
+class BackwardResult:
+    qG: np.ndarray
+    qX: np.ndarray
+    qW: np.ndarray
+    s_g: float
+    s_x: float
+    s_w: float
+    acc_dx: np.ndarray | None
+    acc_dw: np.ndarray | None
+    dX: np.ndarray | None
+    dW: np.ndarray | None
+
+
+def _operands(X, W, dY, c_x, x_unsigned, c_w, st, seed, rounding):
+    qG = quantize_grad(dY, st, seed, rounding)
+    if st.status == NONFINITE:
+        return None
+    s_g = scale(st.clip, st.bits, False)
+    qX, _, s_x, sx_status = quantize_operand(X, c_x, bool(x_unsigned), st.bits)
+    qW, _, s_w, sw_status = quantize_operand(W, c_w, False, st.bits)
+    if sx_status == NONFINITE or sw_status == NONFINITE:
+        st.status = NONFINITE
+        return None
+    return qG, qX, qW, s_g, s_x, s_w
+
+
+def backward_linear(X, W, dY, st: GradState, c_x: float = 0.0, x_unsigned: bool = False,
+                    c_w: float = 0.0, seed: int = 0, rounding: int = NEAREST,
+                    want_dx: bool = True, want_dw: bool = True):
+    """X[M,K], W[K,N], dY[M,N]: dX = Q(dY).Q(W)^T, dW = Q(X)^T.Q(dY)."""
+    ops = _operands(X, W, dY, c_x, x_unsigned, c_w, st, seed, rounding)
+    if ops is None:
+        return None
+    qG, qX, qW, s_g, s_x, s_w = ops
+    acc_dx = linear_dx(qG, qW) if want_dx else None
+    acc_dw = linear_dw(qX, qG) if want_dw else None
+    for a in (acc_dx, acc_dw):
+        assert a is None or np.abs(a).max(initial=0) < 2 ** 31
+    return BackwardResult(qG, qX, qW, s_g, s_x, s_w, acc_dx, acc_dw,
+                          dequant(acc_dx, s_g, s_w) if want_dx else None,
+                          dequant(acc_dw, s_x, s_g) if want_dw else None)
+
+
+def backward_conv2d(X, W, dY, stride: int, pad: int, st: GradState, c_x: float = 0.0,
+                    x_unsigned: bool = True, c_w: float = 0.0, seed: int = 0,
+                    rounding: int = NEAREST, want_dx: bool = True, want_dw: bool = True):
+    """X[N,C,H,W], W[K,C,R,S], dY[N,K,P,Q]: both gradients of the convolution."""
+    ops = _operands(X, W, dY, c_x, x_unsigned, c_w, st, seed, rounding)
+    if ops is None:
+        return None
+    qG, qX, qW, s_g, s_x, s_w = ops
+    acc_dx = conv2d_dx(qG, qW, X.shape, stride, pad) if want_dx else None
+    acc_dw = conv2d_dw(qG, qX, W.shape, stride, pad) if want_dw else None
+    for a in (acc_dx, acc_dw):
+        assert a is None or np.abs(a).max(initial=0) < 2 ** 31
+    return BackwardResult(qG, qX, qW, s_g, s_x, s_w, acc_dx, acc_dw,
+                          dequant(acc_dx, s_g, s_w) if want_dx else None,
+                          dequant(acc_dw, s_x, s_g) if want_dw else None)

@@ -1,0 +1,146 @@
+"""Pins for the oracle's integer contractions and dequantisation (backward pass).
+
+The sums are checked against library routines used in a different formulation:
+numpy's integer matmul, an unfold (im2col) + matmul version of the convolution
+gradients, and torch's own conv / linear gradients in fp64 on the dequantised
+operands.
+"""
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+import oracle
+from paper_2407_12637_amd import synth
+
+CONV_CASES = [
+    # N, C, H, W, K, R, S, stride, pad
+    (2, 3, 8, 8, 4, 3, 3, 1, 1),
+    (2, 4, 9, 7, 5, 3, 3, 2, 1),
+    (3, 2, 10, 10, 3, 1, 1, 2, 0),
+    (2, 3, 12, 12, 4, 7, 7, 2, 3),
+    (2, 5, 6, 6, 4, 1, 1, 1, 0),
+    (1, 2, 7, 8, 3, 3, 3, 2, 0),       # rows/cols of X the stride never reaches
+]
+
+
+def _codes(r, shape, lo, hi):
+    return r.integers(lo, hi + 1, size=shape).astype(np.int32)
+
+
+def test_linear_against_numpy_matmul():
+    r = np.random.default_rng(0)
+    M, K, N = 37, 29, 41
+    qG, qW, qX = _codes(r, (M, N), -7, 7), _codes(r, (K, N), -7, 7), _codes(r, (M, K), 0, 15)
+    assert np.array_equal(oracle.linear_dx(qG, qW), qG.astype(np.int64) @ qW.astype(np.int64).T)
+    assert np.array_equal(oracle.linear_dw(qX, qG), qX.astype(np.int64).T @ qG.astype(np.int64))
+
+
+@pytest.mark.parametrize("case", CONV_CASES)
+def test_conv_against_unfold_matmul(case):
+    N, C, H, W, K, R, S, st, pad = case
+    r = np.random.default_rng(1)
+    P, Q = (H + 2 * pad - R) // st + 1, (W + 2 * pad - S) // st + 1
+    qG = _codes(r, (N, K, P, Q), -7, 7)
+    qW = _codes(r, (K, C, R, S), -7, 7)
+    qX = _codes(r, (N, C, H, W), 0, 15)
+    # dW: columns of X (im2col) times dY, summed over the batch -- exact in fp64
+    cols = F.unfold(torch.from_numpy(qX).double(), (R, S), padding=pad, stride=st)  # [N,CRS,PQ]
+    g = torch.from_numpy(qG).double().reshape(N, K, P * Q)
+    dw = torch.einsum("nkl,njl->kj", g, cols).reshape(K, C, R, S)
+    assert np.array_equal(oracle.conv2d_dw(qG, qX, (K, C, R, S), st, pad),
+                          dw.numpy().astype(np.int64))
+    # dX: W^T times dY gives gradient columns; fold scatters them back (col2im)
+    wmat = torch.from_numpy(qW).double().reshape(K, C * R * S)
+    dcols = torch.einsum("kj,nkl->njl", wmat, g)
+    dx = F.fold(dcols, (H, W), (R, S), padding=pad, stride=st)
+    assert np.array_equal(oracle.conv2d_dx(qG, qW, (N, C, H, W), st, pad),
+                          dx.numpy().astype(np.int64))
+
+
+@pytest.mark.parametrize("case", CONV_CASES)
+def test_conv_against_torch_gradients(case):
+    N, C, H, W, K, R, S, st, pad = case
+    r = synth.rng(2, 92, 0, 0)
+    X, Wt = synth.relu_normal(r, (N, C, H, W)), synth.kaiming_normal(r, (K, C, R, S))
+    P, Q = (H + 2 * pad - R) // st + 1, (W + 2 * pad - S) // st + 1
+    dY = synth.grad_cfg1(r, (N, K, P, Q))
+    state = oracle.GradState(gamma=0.3)
+    res = oracle.backward_conv2d(X, Wt, dY, st, pad, state, x_unsigned=True)
+    # dequantised operands through torch's conv gradients, fp64
+    xq = torch.from_numpy(res.qX * res.s_x).double()
+    wq = torch.from_numpy(res.qW * res.s_w).double()
+    gq = torch.from_numpy(res.qG * res.s_g).double()
+    dx = torch.nn.grad.conv2d_input((N, C, H, W), wq, gq, stride=st, padding=pad)
+    dw = torch.nn.grad.conv2d_weight(xq, (K, C, R, S), gq, stride=st, padding=pad)
+    # atol only absorbs fp64 cancellation noise where the exact integer sum is 0
+    np.testing.assert_allclose(res.dX, dx.numpy(), rtol=2e-7, atol=1e-12 * np.abs(res.dX).max())
+    np.testing.assert_allclose(res.dW, dw.numpy(), rtol=2e-7, atol=1e-12 * np.abs(res.dW).max())
+
+
+def test_linear_against_torch_gradients():
+    L = synth.linear_case()
+    r = synth.rng(0, 1, 0, 0)
+    X, W = synth.normal(r, (L.M, L.K)), synth.normal(r, (L.K, L.N), 0.02)
+    dY = synth.grad_cfg1(r, (L.M, L.N))
+    st = oracle.GradState(gamma=0.2)
+    res = oracle.backward_linear(X, W, dY, st, x_unsigned=False)
+    xq = torch.from_numpy(res.qX * res.s_x).double().requires_grad_()
+    wq = torch.from_numpy(res.qW * res.s_w).double().requires_grad_()
+    gq = torch.from_numpy(res.qG * res.s_g).double()
+    (xq @ wq).backward(gq)                    # Y = X W  =>  dX = dY W^T, dW = X^T dY
+    np.testing.assert_allclose(res.dX, xq.grad.numpy(), rtol=2e-7, atol=1e-12 * np.abs(res.dX).max())
+    np.testing.assert_allclose(res.dW, wq.grad.numpy(), rtol=2e-7, atol=1e-12 * np.abs(res.dW).max())
+    assert np.abs(res.acc_dx).max() > 0 and np.abs(res.acc_dw).max() > 0
+
+
+def test_sampled_sums_equal_full_sums():
+    r = np.random.default_rng(3)
+    for N, C, H, W, K, R, S, st, pad in CONV_CASES:
+        P, Q = (H + 2 * pad - R) // st + 1, (W + 2 * pad - S) // st + 1
+        qG = _codes(r, (N, K, P, Q), -7, 7)
+        qW = _codes(r, (K, C, R, S), -7, 7)
+        qX = _codes(r, (N, C, H, W), 0, 15)
+        full_dx = oracle.conv2d_dx(qG, qW, (N, C, H, W), st, pad).reshape(-1)
+        full_dw = oracle.conv2d_dw(qG, qX, (K, C, R, S), st, pad).reshape(-1)
+        ix = np.arange(full_dx.size)
+        iw = np.arange(full_dw.size)
+        assert np.array_equal(oracle.conv2d_dx_at(qG, qW, (N, C, H, W), st, pad, ix), full_dx)
+        assert np.array_equal(oracle.conv2d_dw_at(qG, qX, (K, C, R, S), st, pad, iw), full_dw)
+
+
+def test_linear_is_a_1x1_conv():
+    r = np.random.default_rng(4)
+    M, K, N = 12, 9, 7
+    qG, qX = _codes(r, (M, N), -7, 7), _codes(r, (M, K), -7, 7)
+    qW = _codes(r, (K, N), -7, 7)                   # linear layout [in, out]
+    qWc = np.ascontiguousarray(qW.T).reshape(N, K, 1, 1)  # conv layout [out, in, 1, 1]
+    dx = oracle.conv2d_dx(qG.reshape(M, N, 1, 1), qWc, (M, K, 1, 1), 1, 0).reshape(M, K)
+    dw = oracle.conv2d_dw(qG.reshape(M, N, 1, 1), qX.reshape(M, K, 1, 1), (N, K, 1, 1), 1, 0)
+    assert np.array_equal(dx, oracle.linear_dx(qG, qW))
+    assert np.array_equal(dw.reshape(N, K).T, oracle.linear_dw(qX, qG))
+
+
+def test_all_ones_count_the_taps():
+    N, C, H, W, K, R, S, st, pad = 2, 3, 6, 6, 4, 3, 3, 1, 1
+    one = lambda *s: np.ones(s, dtype=np.int32)
+    dx = oracle.conv2d_dx(one(N, K, H, W), one(K, C, R, S), (N, C, H, W), st, pad)
+    assert dx[0, 0, 2, 2] == K * R * S and dx[0, 0, 0, 0] == K * 4 and dx[0, 0, 0, 3] == K * 6
+    dw = oracle.conv2d_dw(one(N, K, H, W), one(N, C, H, W), (K, C, R, S), st, pad)
+    assert dw[0, 0, 1, 1] == N * H * W and dw[0, 0, 0, 0] == N * (H - 1) * (W - 1)
+    assert np.array_equal(oracle.linear_dx(one(5, 11), one(3, 11)), np.full((5, 3), 11))
+
+
+def test_dequant_is_the_scale_product():
+    acc = np.array([[0, 1, -3], [2 ** 30, -2 ** 31 + 1, 49]], dtype=np.int64)
+    out = oracle.dequant(acc, 0.125, 3.0)
+    assert out.dtype == np.float32
+    assert np.array_equal(out, (acc * 0.375).astype(np.float32))
+
+
+def test_zero_gradient_gives_zero_outputs():
+    r = synth.rng(0, 92, 5, 0)
+    X, W = synth.normal(r, (4, 6)), synth.normal(r, (6, 5))
+    st = oracle.GradState(gamma=0.7)
+    res = oracle.backward_linear(X, W, np.zeros((4, 5), np.float32), st)
+    assert st.status == oracle.ZERO_GRAD and not res.dX.any() and not res.dW.any()
