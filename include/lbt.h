@@ -1,0 +1,178 @@
+/*
+ * lbt.h -- C ABI of the INT4 fixed-point backward pass for gfx950 (MI355X).
+ *
+ * Implements the hot path of "Toward INT4 Fixed-Point Training via Exploring
+ * Quantization Error for Gradients" (Kim et al.): per layer, the gradient
+ * quantizer whose interval is gamma * max|dY| (Sec. 3.1), with gamma moved by
+ * the clipping-factor update of Sec. 3.3 (Eq. 15-16, Alg. 1), then the two
+ * integer contractions of the backward pass on the 4-bit codes and the
+ * denormalisation of Eq. (4).
+ *
+ * Conventions for every entry point
+ *   - Returns LBT_OK (0) or a negative LBT_ERR_* code.  Nothing throws.
+ *   - Tensor pointers, state pointers and workspaces are DEVICE pointers owned
+ *     by the caller; the library never allocates, frees or retains them.
+ *     fp32 tensors must be 16-byte aligned, code buffers 4-byte aligned,
+ *     workspaces 256-byte aligned.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls only enqueue work; they do not synchronise with the host, except
+ *     lbt_state_read which waits for its copy.
+ *   - Conditions found on the device (non-finite or all-zero gradient) are
+ *     written to lbt_grad_state.status and read back with lbt_state_read.
+ *   - All tensors are dense, row-major, fp32.  Only b = 4 bits is implemented
+ *     on the device in this version; other values return LBT_ERR_UNSUPPORTED.
+ */
+#ifndef LBT_H_
+#define LBT_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LBT_OK 0
+#define LBT_ERR_NULL (-1)        /* a required pointer is NULL                     */
+#define LBT_ERR_SHAPE (-2)       /* a size is <= 0 or inconsistent                 */
+#define LBT_ERR_UNSUPPORTED (-3) /* bits != 4, size beyond a documented limit      */
+#define LBT_ERR_WORKSPACE (-4)   /* workspace smaller than lbt_workspace_bytes_*   */
+#define LBT_ERR_OVERFLOW (-5)    /* a contraction could exceed int32 accumulators  */
+#define LBT_ERR_HIP (-6)         /* a HIP runtime call failed                      */
+#define LBT_ERR_ALIGN (-7)       /* a pointer is not aligned as required           */
+
+#define LBT_STATUS_OK 0
+#define LBT_STATUS_NONFINITE 1   /* NaN or Inf seen in a tensor whose maximum was taken */
+#define LBT_STATUS_ZERO_GRAD 2   /* max|dY| == 0: codes 0, scale 0, gamma not updated   */
+
+#define LBT_ROUND_NEAREST 0      /* round half to even                              */
+#define LBT_ROUND_STOCHASTIC 1   /* floor(x_n + u), u from Philox4x32-10            */
+
+/*
+ * Per-layer state of the gradient quantizer: the scalars of Alg. 1 plus the
+ * statistics of the last quantized gradient tensor.  Lives in device memory
+ * (sizeof = 96).  It is the whole persistent state of the method: saving and
+ * restoring it (lbt_state_read / lbt_state_write) resumes a run bit for bit,
+ * since the stochastic-rounding stream is a pure function of (seed, step,
+ * element index).
+ */
+typedef struct lbt_grad_state {
+  double gamma;      /* clipping factor, Sec. 3.1; c_g = gamma * g_max              */
+  double alpha;      /* ratio of large gradients N(G_L)/N(G), Sec. 3.2              */
+  double beta;       /* step of the update, Eq. (15)                                */
+  double gamma_min;  /* gamma is clamped to [gamma_min, gamma_max] after the update */
+  double gamma_max;
+  int32_t bits;      /* b                                                           */
+  int32_t status;    /* LBT_STATUS_* of the last quantized gradient                 */
+  uint64_t step;     /* number of updates done; also the RNG's iteration word       */
+  uint64_t n_total;  /* N(G) of the last quantized gradient                         */
+  uint64_t n_out;    /* N(G_out): number of |g| > c_g (strict)                      */
+  float gmax;        /* g_max = max|G|                                              */
+  float clip;        /* c_g = (float)(gamma * (double)g_max)                        */
+  float scale;       /* s = c_g / (2^(b-1) - 1), Eq. (2)                            */
+  uint32_t reserved[3];
+} lbt_grad_state;
+
+const char* lbt_version(void);
+const char* lbt_strerror(int code);
+size_t lbt_state_sizeof(void);
+
+/* Initialise a device-resident state: gamma0 (the paper starts from the full
+ * range, gamma = 1), alpha and beta (1e-3 each in the paper's experiments,
+ * Sec. 4.1 and supplement S4), clamp range, bit-width.  step = 0. */
+int lbt_state_init(lbt_grad_state* st, double gamma0, double alpha, double beta,
+                   double gamma_min, double gamma_max, int bits, void* stream);
+/* Copy a state device -> host (waits for the stream) / host -> device. */
+int lbt_state_read(const lbt_grad_state* st, lbt_grad_state* host_out, void* stream);
+int lbt_state_write(lbt_grad_state* st, const lbt_grad_state* host_in, void* stream);
+
+/*
+ * Clipping-factor update, Eq. (15)-(16) / Alg. 1:
+ *   gamma <- clamp(gamma + beta * sign(N(G_out)/N(G) - alpha/(2^b - 1))), step <- step + 1
+ * using n_out, n_total left in *st by the last gradient quantization (which
+ * used the gamma being replaced).  sign(0) = 0.  No-op if status != OK.
+ */
+int lbt_update_interval(lbt_grad_state* st, void* stream);
+
+/*
+ * Gradient quantizer of one layer (Sec. 3.1, Eq. 1, 2, 4).
+ *   g[n] fp32  ->  codes: ceil(n/2) bytes, element 2j in the low nibble of byte
+ *   j and 2j+1 in the high nibble, two's-complement 4-bit values in [-7, 7]
+ *   (code -8 never occurs); a trailing pad nibble is 0.
+ * Computes g_max, c_g = gamma * g_max, the codes, and N(G_out); writes gmax,
+ * clip, scale, n_total, n_out, status to *st.  Does not change gamma or step.
+ * rounding = LBT_ROUND_STOCHASTIC draws 16 bits per element from
+ * Philox4x32-10 with key = seed and counter = (element/8, st->step); element
+ * e uses 16-bit lane e%8 of the four output words, low half first.
+ * ws: lbt_workspace_bytes_quantize(n) bytes.
+ */
+int lbt_quantize_grad(const float* g, int64_t n, lbt_grad_state* st, uint64_t seed,
+                      int rounding, uint8_t* codes, void* ws, size_t ws_bytes, void* stream);
+size_t lbt_workspace_bytes_quantize(int64_t n);
+
+/*
+ * Weight / activation quantizer (Eq. 2 for zero-centred inputs, Eq. 3 for
+ * inputs after a ReLU), nearest rounding, same code format as above (unsigned
+ * codes are 0..15).  c > 0 is the clipping value (learned by the caller in the
+ * paper, Sec. 3.1); c <= 0 selects the tensor's own maximum (max|x| signed,
+ * max x unsigned).  clip_scale_out (device, 2 floats, may be NULL) receives
+ * the clip value and the scale s.  ws: lbt_workspace_bytes_quantize(n).
+ */
+int lbt_quantize_operand(const float* x, int64_t n, float c, int is_unsigned, int bits,
+                         uint8_t* codes, float* clip_scale_out, void* ws, size_t ws_bytes,
+                         void* stream);
+
+/*
+ * Backward pass of a linear layer Y = X W with row-major X[M,K_in],
+ * W[K_in,N_out], dY[M,N_out]:
+ *   dX = Q(dY) . Q(W)^T   [M,K_in]      dW = Q(X)^T . Q(dY)   [K_in,N_out]
+ * dY goes through the gradient quantizer (as lbt_quantize_grad; statistics
+ * are left in *st, gamma is not changed: call lbt_update_interval afterwards);
+ * X and W through the operand quantizer with clip values c_x, c_w (<= 0: the
+ * tensor's maximum); x_unsigned selects Eq. (3) for X.  The sums run on int8
+ * matrix cores with int32 accumulators and are exact; outputs are
+ * acc * (s_a * s_b) in fp32.  dX or dW may be NULL to skip that product.
+ * Requires M*112*112 and N_out*112*112 < 2^31 (LBT_ERR_OVERFLOW otherwise).
+ */
+int lbt_backward_linear(const float* X, const float* W, const float* dY, int64_t M,
+                        int64_t K_in, int64_t N_out, float c_x, int x_unsigned, float c_w,
+                        lbt_grad_state* st, uint64_t seed, int rounding, float* dX, float* dW,
+                        void* ws, size_t ws_bytes, void* stream);
+size_t lbt_workspace_bytes_linear(int64_t M, int64_t K_in, int64_t N_out);
+
+/*
+ * Backward pass of a 2-D convolution (cross-correlation, NCHW, no dilation,
+ * no groups): X[N,C,H,Wd], W[K,C,R,S], dY[N,K,P,Q], P = (H+2*pad-R)/stride+1:
+ *   dX[n,c,h,w]  = s_g s_w * sum_{k,r,s} qG[n,k,p,q] qW[k,c,r,s],  h = p*stride-pad+r, ...
+ *   dW[k,c,r,s]  = s_x s_g * sum_{n,p,q} qG[n,k,p,q] qX[n,c,h,w]   (zero outside the image)
+ * Same quantizers, state handling and NULL-output rule as the linear call.
+ */
+int lbt_backward_conv2d(const float* X, const float* W, const float* dY, int64_t N, int64_t C,
+                        int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S, int64_t stride,
+                        int64_t pad, float c_x, int x_unsigned, float c_w, lbt_grad_state* st,
+                        uint64_t seed, int rounding, float* dX, float* dW, void* ws,
+                        size_t ws_bytes, void* stream);
+size_t lbt_workspace_bytes_conv2d(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K,
+                                  int64_t R, int64_t S, int64_t stride, int64_t pad);
+
+/*
+ * The same two calls with the raw int32 accumulators also written out
+ * (acc_dX shaped like dX, acc_dW like dW; either may be NULL).  For checking
+ * the integer sums bit for bit.
+ */
+int lbt_backward_linear_acc(const float* X, const float* W, const float* dY, int64_t M,
+                            int64_t K_in, int64_t N_out, float c_x, int x_unsigned, float c_w,
+                            lbt_grad_state* st, uint64_t seed, int rounding, float* dX,
+                            float* dW, int32_t* acc_dX, int32_t* acc_dW, void* ws,
+                            size_t ws_bytes, void* stream);
+int lbt_backward_conv2d_acc(const float* X, const float* W, const float* dY, int64_t N,
+                            int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S,
+                            int64_t stride, int64_t pad, float c_x, int x_unsigned, float c_w,
+                            lbt_grad_state* st, uint64_t seed, int rounding, float* dX,
+                            float* dW, int32_t* acc_dX, int32_t* acc_dW, void* ws,
+                            size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LBT_H_ */

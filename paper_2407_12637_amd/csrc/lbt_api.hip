@@ -1,0 +1,258 @@
+// C ABI of liblbt.so: argument validation, workspace carving, kernel sequencing.
+// Every call only enqueues work on the caller's stream (lbt_state_read excepted).
+#include "lbt_internal.h"
+
+using namespace lbt;
+
+namespace {
+
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+inline size_t pad256(size_t b) { return (b + 255) / 256 * 256; }
+
+struct ConvWorkspace {
+  size_t off_scalars, off_g_npqk, off_g_kpqn, off_x_chwn, off_w_crsk, total;
+};
+
+ConvWorkspace conv_workspace(const ConvGeom& g) {
+  ConvWorkspace w{};
+  size_t o = 0;
+  w.off_scalars = o;
+  o += 256;
+  w.off_g_npqk = o;
+  o += pad256((size_t)g.N * g.P * g.Q * g.Kp / 2);
+  w.off_g_kpqn = o;
+  o += pad256((size_t)g.K * g.P * g.Q * g.Np / 2);
+  w.off_x_chwn = o;
+  o += pad256((size_t)g.C * g.H * g.W * g.Np / 2);
+  w.off_w_crsk = o;
+  o += pad256((size_t)g.C * g.R * g.S * g.Kp / 2);
+  w.total = o;
+  return w;
+}
+
+int make_geom(int64_t N, int64_t C, int64_t H, int64_t W, int64_t K, int64_t R, int64_t S,
+              int64_t stride, int64_t pad, ConvGeom* out) {
+  if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || K <= 0 || R <= 0 || S <= 0 || stride <= 0 || pad < 0)
+    return LBT_ERR_SHAPE;
+  if (H + 2 * pad < R || W + 2 * pad < S) return LBT_ERR_SHAPE;
+  const int64_t P = (H + 2 * pad - R) / stride + 1, Q = (W + 2 * pad - S) / stride + 1;
+  const int64_t lim = 0x7fffffffll;
+  if (N * C * H * W > lim || N * K * P * Q > lim || K * C * R * S > lim) return LBT_ERR_UNSUPPORTED;
+  ConvGeom g;
+  g.N = (int)N; g.C = (int)C; g.H = (int)H; g.W = (int)W; g.K = (int)K; g.R = (int)R; g.S = (int)S;
+  g.P = (int)P; g.Q = (int)Q; g.stride = (int)stride; g.pad = (int)pad;
+  g.Np = (int)round_up(N, kGranule);
+  g.Kp = (int)round_up(K, kGranule);
+  *out = g;
+  return LBT_OK;
+}
+
+// w_is_ck: W is stored [C][K] (linear layer, [in][out]) instead of [K][C][R][S].
+int backward_common(const float* X, const float* W, const float* dY, const ConvGeom& g,
+                    bool w_is_ck, float c_x, int x_unsigned, float c_w, lbt_grad_state* st,
+                    uint64_t seed, int rounding, float* dX, float* dW, int32_t* acc_dX,
+                    int32_t* acc_dW, void* ws, size_t ws_bytes, void* stream) {
+  if (!W || !dY || !st || !ws) return LBT_ERR_NULL;
+  if (dW && !X) return LBT_ERR_NULL;
+  if ((acc_dX && !dX) || (acc_dW && !dW)) return LBT_ERR_NULL;
+  if (rounding != LBT_ROUND_NEAREST && rounding != LBT_ROUND_STOCHASTIC) return LBT_ERR_UNSUPPORTED;
+  if (!aligned(dY, 16) || !aligned(W, 16) || (X && !aligned(X, 16)) || !aligned(ws, 256) ||
+      (dX && !aligned(dX, 16)) || (dW && !aligned(dW, 16)) || !aligned(st, 8))
+    return LBT_ERR_ALIGN;
+  const ConvWorkspace lay = conv_workspace(g);
+  if (ws_bytes < lay.total) return LBT_ERR_WORKSPACE;
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  uint8_t* base = static_cast<uint8_t*>(ws);
+  OperandScalars* sc = reinterpret_cast<OperandScalars*>(base + lay.off_scalars);
+  uint8_t* g_npqk = base + lay.off_g_npqk;
+  uint8_t* g_kpqn = base + lay.off_g_kpqn;
+  uint8_t* x_chwn = base + lay.off_x_chwn;
+  uint8_t* w_crsk = base + lay.off_w_crsk;
+
+  const int64_t n_dy = (int64_t)g.N * g.K * g.P * g.Q;
+  const int64_t n_x = (int64_t)g.N * g.C * g.H * g.W;
+  const int64_t n_w = (int64_t)g.K * g.C * g.R * g.S;
+  int rc;
+  if ((rc = launch_begin(st, sc, s))) return rc;
+  if ((rc = launch_absmax(dY, n_dy, 1, reinterpret_cast<uint32_t*>(&st->gmax), s))) return rc;
+  if (dW && !(c_x > 0.0f))
+    if ((rc = launch_absmax(X, n_x, x_unsigned ? 0 : 1, &sc->xmax_bits, s))) return rc;
+  if (dX && !(c_w > 0.0f))
+    if ((rc = launch_absmax(W, n_w, 1, &sc->wmax_bits, s))) return rc;
+  if ((rc = launch_grad_prepare(st, n_dy, s))) return rc;
+  if ((rc = launch_operand_prepare(sc, st, c_x, c_w, s))) return rc;
+  if ((rc = launch_quantize_relayout_grad(dY, g.N, g.K, (int64_t)g.P * g.Q, st, seed, rounding,
+                                          dX ? g_npqk : nullptr, dW ? g_kpqn : nullptr, s)))
+    return rc;
+  if (dW) {
+    if ((rc = launch_quantize_relayout_operand(X, g.N, g.C, (int64_t)g.H * g.W, &sc->c_x,
+                                               x_unsigned, nullptr, x_chwn, s)))
+      return rc;
+  }
+  if (dX) {
+    if (w_is_ck)
+      rc = launch_quantize_relayout_operand(W, g.C, g.K, 1, &sc->c_w, 0, w_crsk, nullptr, s);
+    else
+      rc = launch_quantize_relayout_operand(W, g.K, g.C, (int64_t)g.R * g.S, &sc->c_w, 0, nullptr,
+                                            w_crsk, s);
+    if (rc) return rc;
+    rc = w_is_ck ? launch_linear_dx(g, w_crsk, g_npqk, st, sc, dX, acc_dX, s)
+                 : launch_conv_dx(g, w_crsk, g_npqk, st, sc, dX, acc_dX, s);
+    if (rc) return rc;
+  }
+  if (dW) {
+    rc = w_is_ck ? launch_linear_dw(g, g_kpqn, x_chwn, st, sc, x_unsigned, dW, acc_dW, s)
+                 : launch_conv_dw(g, g_kpqn, x_chwn, st, sc, x_unsigned, dW, acc_dW, s);
+    if (rc) return rc;
+  }
+  return LBT_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* lbt_version(void) { return "lbt-gfx950 0.1"; }
+
+const char* lbt_strerror(int code) {
+  switch (code) {
+    case LBT_OK: return "ok";
+    case LBT_ERR_NULL: return "null pointer";
+    case LBT_ERR_SHAPE: return "bad shape";
+    case LBT_ERR_UNSUPPORTED: return "unsupported configuration";
+    case LBT_ERR_WORKSPACE: return "workspace too small";
+    case LBT_ERR_OVERFLOW: return "contraction may overflow int32";
+    case LBT_ERR_HIP: return "HIP runtime error";
+    case LBT_ERR_ALIGN: return "misaligned pointer";
+    default: return "unknown error";
+  }
+}
+
+size_t lbt_state_sizeof(void) { return sizeof(lbt_grad_state); }
+
+int lbt_state_init(lbt_grad_state* st, double gamma0, double alpha, double beta, double gamma_min,
+                   double gamma_max, int bits, void* stream) {
+  if (!st) return LBT_ERR_NULL;
+  if (!aligned(st, 8)) return LBT_ERR_ALIGN;
+  if (bits != 4) return LBT_ERR_UNSUPPORTED;
+  if (!(gamma_min > 0.0) || !(gamma_max >= gamma_min) || !(gamma0 >= gamma_min) ||
+      !(gamma0 <= gamma_max) || !(alpha > 0.0) || !(beta >= 0.0))
+    return LBT_ERR_SHAPE;
+  lbt_grad_state v{};
+  v.gamma = gamma0; v.alpha = alpha; v.beta = beta;
+  v.gamma_min = gamma_min; v.gamma_max = gamma_max;
+  v.bits = bits;
+  return launch_state_init(st, v, reinterpret_cast<hipStream_t>(stream));
+}
+
+int lbt_state_read(const lbt_grad_state* st, lbt_grad_state* host_out, void* stream) {
+  if (!st || !host_out) return LBT_ERR_NULL;
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  LBT_HIP_CHECK(hipMemcpyAsync(host_out, st, sizeof(lbt_grad_state), hipMemcpyDeviceToHost, s));
+  LBT_HIP_CHECK(hipStreamSynchronize(s));
+  return LBT_OK;
+}
+
+int lbt_state_write(lbt_grad_state* st, const lbt_grad_state* host_in, void* stream) {
+  if (!st || !host_in) return LBT_ERR_NULL;
+  if (host_in->bits != 4) return LBT_ERR_UNSUPPORTED;
+  return launch_state_init(st, *host_in, reinterpret_cast<hipStream_t>(stream));
+}
+
+int lbt_update_interval(lbt_grad_state* st, void* stream) {
+  if (!st) return LBT_ERR_NULL;
+  return launch_update_interval(st, reinterpret_cast<hipStream_t>(stream));
+}
+
+size_t lbt_workspace_bytes_quantize(int64_t n) {
+  (void)n;
+  return 256;
+}
+
+int lbt_quantize_grad(const float* g, int64_t n, lbt_grad_state* st, uint64_t seed, int rounding,
+                      uint8_t* codes, void* ws, size_t ws_bytes, void* stream) {
+  if (!g || !st || !codes || !ws) return LBT_ERR_NULL;
+  if (n <= 0) return LBT_ERR_SHAPE;
+  if (rounding != LBT_ROUND_NEAREST && rounding != LBT_ROUND_STOCHASTIC) return LBT_ERR_UNSUPPORTED;
+  if (!aligned(g, 16) || !aligned(codes, 4) || !aligned(st, 8) || !aligned(ws, 256))
+    return LBT_ERR_ALIGN;
+  if (ws_bytes < lbt_workspace_bytes_quantize(n)) return LBT_ERR_WORKSPACE;
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  int rc;
+  if ((rc = launch_begin(st, nullptr, s))) return rc;
+  if ((rc = launch_absmax(g, n, 1, reinterpret_cast<uint32_t*>(&st->gmax), s))) return rc;
+  if ((rc = launch_grad_prepare(st, n, s))) return rc;
+  return launch_quantize_flat_grad(g, n, st, seed, rounding, codes, s);
+}
+
+int lbt_quantize_operand(const float* x, int64_t n, float c, int is_unsigned, int bits,
+                         uint8_t* codes, float* clip_scale_out, void* ws, size_t ws_bytes,
+                         void* stream) {
+  if (!x || !codes || !ws) return LBT_ERR_NULL;
+  if (n <= 0) return LBT_ERR_SHAPE;
+  if (bits != 4) return LBT_ERR_UNSUPPORTED;
+  if (!aligned(x, 16) || !aligned(codes, 4) || !aligned(ws, 256)) return LBT_ERR_ALIGN;
+  if (ws_bytes < lbt_workspace_bytes_quantize(n)) return LBT_ERR_WORKSPACE;
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  OperandScalars* sc = static_cast<OperandScalars*>(ws);
+  int rc;
+  if ((rc = launch_begin(nullptr, sc, s))) return rc;
+  if (!(c > 0.0f))
+    if ((rc = launch_absmax(x, n, is_unsigned ? 0 : 1, &sc->xmax_bits, s))) return rc;
+  if ((rc = launch_operand_prepare(sc, nullptr, c, 1.0f, s))) return rc;
+  return launch_quantize_flat_operand(x, n, &sc->c_x, is_unsigned, codes, clip_scale_out, s);
+}
+
+size_t lbt_workspace_bytes_conv2d(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R,
+                                  int64_t S, int64_t stride, int64_t pad) {
+  ConvGeom g;
+  if (make_geom(N, C, H, Wd, K, R, S, stride, pad, &g) != LBT_OK) return 0;
+  return conv_workspace(g).total;
+}
+
+size_t lbt_workspace_bytes_linear(int64_t M, int64_t K_in, int64_t N_out) {
+  return lbt_workspace_bytes_conv2d(M, K_in, 1, 1, N_out, 1, 1, 1, 0);
+}
+
+int lbt_backward_conv2d_acc(const float* X, const float* W, const float* dY, int64_t N, int64_t C,
+                            int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S, int64_t stride,
+                            int64_t pad, float c_x, int x_unsigned, float c_w, lbt_grad_state* st,
+                            uint64_t seed, int rounding, float* dX, float* dW, int32_t* acc_dX,
+                            int32_t* acc_dW, void* ws, size_t ws_bytes, void* stream) {
+  ConvGeom g;
+  int rc = make_geom(N, C, H, Wd, K, R, S, stride, pad, &g);
+  if (rc) return rc;
+  return backward_common(X, W, dY, g, false, c_x, x_unsigned, c_w, st, seed, rounding, dX, dW,
+                         acc_dX, acc_dW, ws, ws_bytes, stream);
+}
+
+int lbt_backward_conv2d(const float* X, const float* W, const float* dY, int64_t N, int64_t C,
+                        int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S, int64_t stride,
+                        int64_t pad, float c_x, int x_unsigned, float c_w, lbt_grad_state* st,
+                        uint64_t seed, int rounding, float* dX, float* dW, void* ws, size_t ws_bytes,
+                        void* stream) {
+  return lbt_backward_conv2d_acc(X, W, dY, N, C, H, Wd, K, R, S, stride, pad, c_x, x_unsigned, c_w,
+                                 st, seed, rounding, dX, dW, nullptr, nullptr, ws, ws_bytes, stream);
+}
+
+int lbt_backward_linear_acc(const float* X, const float* W, const float* dY, int64_t M, int64_t K_in,
+                            int64_t N_out, float c_x, int x_unsigned, float c_w, lbt_grad_state* st,
+                            uint64_t seed, int rounding, float* dX, float* dW, int32_t* acc_dX,
+                            int32_t* acc_dW, void* ws, size_t ws_bytes, void* stream) {
+  // a linear layer is a 1x1 convolution on a 1x1 image: N = M, C = K_in, K = N_out
+  ConvGeom g;
+  int rc = make_geom(M, K_in, 1, 1, N_out, 1, 1, 1, 0, &g);
+  if (rc) return rc;
+  return backward_common(X, W, dY, g, true, c_x, x_unsigned, c_w, st, seed, rounding, dX, dW,
+                         acc_dX, acc_dW, ws, ws_bytes, stream);
+}
+
+int lbt_backward_linear(const float* X, const float* W, const float* dY, int64_t M, int64_t K_in,
+                        int64_t N_out, float c_x, int x_unsigned, float c_w, lbt_grad_state* st,
+                        uint64_t seed, int rounding, float* dX, float* dW, void* ws, size_t ws_bytes,
+                        void* stream) {
+  return lbt_backward_linear_acc(X, W, dY, M, K_in, N_out, c_x, x_unsigned, c_w, st, seed, rounding,
+                                 dX, dW, nullptr, nullptr, ws, ws_bytes, stream);
+}
+
+}  // extern "C"

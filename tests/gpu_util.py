@@ -1,0 +1,95 @@
+"""Helpers for the GPU parity tests: move numpy inputs to the device, call the C ABI
+through the binding, bring results back.  No arithmetic of the method lives here."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from paper_2407_12637_amd import binding as lbt
+
+DEV = "cuda"
+
+
+def dev(a: np.ndarray) -> torch.Tensor:
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def unpack_nibbles(packed: np.ndarray, n: int, signed: bool) -> np.ndarray:
+    """Decode the ABI's flat code format (test-side decoder, independent of both paths)."""
+    lo = (packed & 0xF).astype(np.int32)
+    hi = (packed >> 4).astype(np.int32)
+    out = np.stack([lo, hi], 1).reshape(-1)[:n]
+    return np.where(out >= 8, out - 16, out) if signed else out
+
+
+def quantize_grad(g: np.ndarray, st, seed=0, rounding=0):
+    n = g.size
+    codes = torch.full(((n + 1) // 2,), 0xEE, dtype=torch.uint8, device=DEV)
+    ws = torch.empty(lbt.lbt_workspace_bytes_quantize(n), dtype=torch.uint8, device=DEV)
+    lbt.lbt_quantize_grad(dev(g.reshape(-1)), st, seed, rounding, codes, ws)
+    return codes.cpu().numpy()
+
+
+def quantize_operand(x: np.ndarray, c: float, unsigned: bool):
+    n = x.size
+    codes = torch.full(((n + 1) // 2,), 0xEE, dtype=torch.uint8, device=DEV)
+    cs = torch.zeros(2, dtype=torch.float32, device=DEV)
+    ws = torch.empty(lbt.lbt_workspace_bytes_quantize(n), dtype=torch.uint8, device=DEV)
+    lbt.lbt_quantize_operand(dev(x.reshape(-1)), c, unsigned, 4, codes, cs, ws)
+    return codes.cpu().numpy(), cs.cpu().numpy()
+
+
+class Result:
+    pass
+
+
+def backward_linear(X, W, dY, st, c_x=0.0, x_unsigned=False, c_w=0.0, seed=0, rounding=0,
+                    want_dx=True, want_dw=True):
+    M, K = X.shape
+    N = W.shape[1]
+    ws = torch.empty(lbt.lbt_workspace_bytes_linear(M, K, N), dtype=torch.uint8, device=DEV)
+    r = Result()
+    dX = torch.full((M, K), float("nan"), device=DEV) if want_dx else None
+    dW = torch.full((K, N), float("nan"), device=DEV) if want_dw else None
+    aX = torch.full((M, K), -1, dtype=torch.int32, device=DEV) if want_dx else None
+    aW = torch.full((K, N), -1, dtype=torch.int32, device=DEV) if want_dw else None
+    lbt.lbt_backward_linear_acc(dev(X), dev(W), dev(dY), M, K, N, c_x, x_unsigned, c_w, st, seed,
+                                rounding, dX, dW, aX, aW, ws)
+    r.dX, r.dW, r.acc_dx, r.acc_dw = [None if t is None else t.cpu().numpy()
+                                      for t in (dX, dW, aX, aW)]
+    return r
+
+
+def backward_conv2d(X, W, dY, stride, pad, st, c_x=0.0, x_unsigned=True, c_w=0.0, seed=0,
+                    rounding=0, want_dx=True, want_dw=True, with_acc=True):
+    N, Cc, H, Wd = X.shape
+    K, _, R, S = W.shape
+    ws = torch.empty(lbt.lbt_workspace_bytes_conv2d(N, Cc, H, Wd, K, R, S, stride, pad),
+                     dtype=torch.uint8, device=DEV)
+    r = Result()
+    dX = torch.full(X.shape, float("nan"), device=DEV) if want_dx else None
+    dW = torch.full(W.shape, float("nan"), device=DEV) if want_dw else None
+    aX = torch.full(X.shape, -1, dtype=torch.int32, device=DEV) if want_dx and with_acc else None
+    aW = torch.full(W.shape, -1, dtype=torch.int32, device=DEV) if want_dw and with_acc else None
+    lbt.lbt_backward_conv2d_acc(dev(X), dev(W), dev(dY), N, Cc, H, Wd, K, R, S, stride, pad, c_x,
+                                x_unsigned, c_w, st, seed, rounding, dX, dW, aX, aW, ws)
+    r.dX, r.dW, r.acc_dx, r.acc_dw = [None if t is None else t.cpu().numpy()
+                                      for t in (dX, dW, aX, aW)]
+    return r
+
+
+def assert_state_equal(h, o):
+    """Device state (binding.GradState) vs oracle.GradState, bit for bit."""
+    assert h.status == o.status, (h.status, o.status)
+    assert h.n_total == o.n_total
+    if o.status == 1:
+        return
+    assert h.n_out == o.n_out, (h.n_out, o.n_out)
+    assert h.gamma == o.gamma and h.step == o.step
+    assert np.float32(h.gmax) == o.gmax, (h.gmax, o.gmax)
+    assert np.float32(h.clip) == o.clip and np.float32(h.scale) == o.scale
+
+
+def assert_outputs_close(got, want):
+    """fp32 outputs: 1e-5 relative (the accumulators themselves are compared exactly)."""
+    np.testing.assert_allclose(got, want, rtol=1e-5, atol=0)

@@ -1,0 +1,84 @@
+"""CPU-side checks of the boundary: the library loads and exports every symbol the
+header declares, the binding's struct mirrors the C struct, and host-side
+validation rejects bad arguments without touching a GPU."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "lbt.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2407_12637_amd import binding, build
+    if not os.path.exists(build.LIB):
+        build.build(force=True)
+    return binding.load()
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(lbt_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_symbols_exported(lib):
+    names = _declared_functions()
+    assert {"lbt_update_interval", "lbt_quantize_grad", "lbt_backward_linear",
+            "lbt_backward_conv2d"} <= set(names)
+    for name in names:
+        assert hasattr(lib, name), name
+
+
+def test_binding_declares_every_symbol():
+    from paper_2407_12637_amd import binding
+    assert sorted(binding.SIGNATURES) == _declared_functions()
+
+
+def test_state_struct_size(lib):
+    from paper_2407_12637_amd import binding
+    assert lib.lbt_state_sizeof() == C.sizeof(binding.GradState) == 96
+    assert binding.GradState.gmax.offset == 72 and binding.GradState.step.offset == 48
+
+
+def test_strerror_and_version(lib):
+    assert lib.lbt_strerror(0) == b"ok"
+    assert b"workspace" in lib.lbt_strerror(-4)
+    assert lib.lbt_version().startswith(b"lbt-gfx950")
+
+
+def test_host_validation_rejects_without_gpu(lib):
+    # these return before any HIP call
+    assert lib.lbt_update_interval(None, None) == -1
+    assert lib.lbt_quantize_grad(None, 8, None, 0, 0, None, None, 0, None) == -1
+    assert lib.lbt_state_init(C.c_void_p(256), 1.0, 1e-3, 1e-3, 1e-3, 1.0, 5, None) == -3
+    assert lib.lbt_state_init(C.c_void_p(256), 2.0, 1e-3, 1e-3, 1e-3, 1.0, 4, None) == -2
+    p = C.c_void_p(4096)
+    assert lib.lbt_quantize_grad(p, 0, p, 0, 0, p, p, 256, None) == -2          # n <= 0
+    assert lib.lbt_quantize_grad(p, 8, p, 0, 7, p, p, 256, None) == -3          # rounding mode
+    assert lib.lbt_quantize_grad(C.c_void_p(4100), 8, p, 0, 0, p, p, 256, None) == -7
+    assert lib.lbt_quantize_grad(p, 8, p, 0, 0, p, p, 16, None) == -4           # workspace
+    # conv shape checks
+    assert lib.lbt_workspace_bytes_conv2d(1, 1, 2, 2, 1, 3, 3, 1, 0) == 0       # kernel > image
+    need = lib.lbt_workspace_bytes_conv2d(4, 16, 12, 12, 32, 3, 3, 1, 1)
+    assert need > 0 and need % 256 == 0
+    rc = lib.lbt_backward_conv2d(p, p, p, 4, 16, 12, 12, 32, 3, 3, 1, 1, 0.0, 1, 0.0, p, 0, 0,
+                                 p, p, p, need - 1, None)
+    assert rc == -4
+    rc = lib.lbt_backward_conv2d(p, p, p, 4, 16, 12, 12, 32, 3, 3, 0, 1, 0.0, 1, 0.0, p, 0, 0,
+                                 p, p, p, need, None)
+    assert rc == -2
+    assert lib.lbt_workspace_bytes_linear(256, 512, 512) > 0
+
+
+def test_workspace_formula(lib):
+    # scalars + four code tensors, each padded to 256 bytes
+    N, Cc, H, W, K, R, S, st, pad = 64, 256, 14, 14, 256, 3, 3, 1, 1
+    P = Q = 14
+    pad256 = lambda b: (b + 255) // 256 * 256
+    want = 256 + pad256(N * P * Q * K // 2) + pad256(K * P * Q * N // 2) \
+        + pad256(Cc * H * W * N // 2) + pad256(Cc * R * S * K // 2)
+    assert lib.lbt_workspace_bytes_conv2d(N, Cc, H, W, K, R, S, st, pad) == want

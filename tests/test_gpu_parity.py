@@ -1,0 +1,244 @@
+"""GPU parity: the HIP path behind the C ABI against the CPU oracle, on the same
+seeded inputs.  Codes, statistics, gamma and int32 accumulators must match bit for
+bit; dequantised fp32 outputs within 1e-5 relative."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2407_12637_amd import binding as lbt
+from paper_2407_12637_amd import synth
+
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+# -- gradient quantizer ------------------------------------------------------------
+@pytest.mark.parametrize("n", [1, 2, 7, 8, 9, 1000, 65537, (1 << 20) + 3, 3 * 1024 * 1024])
+@pytest.mark.parametrize("rounding", [0, 1])
+def test_quantize_grad_codes_and_stats(n, rounding):
+    _say("quantize_grad", n, rounding)
+    r = synth.rng(0, 10, n % 97, synth.T_DY)
+    for dist, gamma in ((synth.grad_cfg4, 1.0), (synth.grad_cfg4, 0.03), (synth.dense_grad, 0.5)):
+        g = dist(r, (n,))
+        ost = oracle.GradState(gamma=gamma, step=3)
+        want = oracle.quantize_grad(g, ost, seed=0xABCDEF0123, rounding=rounding)
+        st = lbt.new_state(gamma0=gamma)
+        h = lbt.lbt_state_read(st)
+        h.step = 3
+        lbt.lbt_state_write(st, h)
+        packed = gu.quantize_grad(g, st, seed=0xABCDEF0123, rounding=rounding)
+        gu.assert_state_equal(lbt.lbt_state_read(st), ost)
+        assert np.array_equal(packed, oracle.pack_nibbles(want))
+        assert np.array_equal(gu.unpack_nibbles(packed, n, True), want)
+
+
+def test_quantize_grad_degenerate():
+    st = lbt.new_state(gamma0=0.5)
+    packed = gu.quantize_grad(np.zeros(1001, np.float32), st)
+    h = lbt.lbt_state_read(st)
+    assert h.status == lbt.STATUS_ZERO_GRAD and not packed.any() and h.scale == 0 and h.clip == 0
+    lbt.lbt_update_interval(st)
+    h = lbt.lbt_state_read(st)
+    assert h.gamma == 0.5 and h.step == 0
+    for bad in (np.nan, np.inf, -np.inf):
+        g = np.ones(777, np.float32)
+        g[500] = bad
+        gu.quantize_grad(g, st)
+        assert lbt.lbt_state_read(st).status == lbt.STATUS_NONFINITE
+    # the state recovers on the next finite tensor
+    gu.quantize_grad(np.ones(16, np.float32), st)
+    assert lbt.lbt_state_read(st).status == lbt.STATUS_OK
+
+
+def test_quantize_is_deterministic():
+    r = synth.rng(0, 11, 0, synth.T_DY)
+    g = synth.grad_cfg4(r, (1 << 21,))
+    st = lbt.new_state(gamma0=0.02)
+    a = gu.quantize_grad(g, st, seed=9, rounding=1)
+    na = lbt.lbt_state_read(st).n_out
+    b = gu.quantize_grad(g, st, seed=9, rounding=1)
+    assert np.array_equal(a, b) and lbt.lbt_state_read(st).n_out == na
+
+
+# -- interval update -----------------------------------------------------------------
+def test_interval_trace_linear_case():
+    # configuration 1: gamma starts at 1, ten fresh gradient draws, ten updates
+    L = synth.linear_case()
+    st = lbt.new_state(gamma0=1.0)
+    ost = oracle.GradState(gamma=1.0)
+    for it in range(10):
+        g = synth.grad_cfg1(synth.rng(0, 1, 0, synth.T_DY, it), (L.M, L.N))
+        want = oracle.quantize_grad(g, ost, seed=1, rounding=1)
+        packed = gu.quantize_grad(g, st, seed=1, rounding=1)
+        assert np.array_equal(packed, oracle.pack_nibbles(want))
+        oracle.update_interval(ost)
+        lbt.lbt_update_interval(st)
+        gu.assert_state_equal(lbt.lbt_state_read(st), ost)
+    assert ost.step == 10 and ost.gamma < 1.0
+
+
+def test_interval_converges_like_oracle_and_resumes():
+    # a dense tensor drives gamma both ways; also save/restore the state mid-run
+    r = synth.rng(0, 12, 0, synth.T_DY)
+    g = synth.grad_cfg2(r, (50000,))
+    st = lbt.new_state(gamma0=0.2, beta=0.01, gamma_min=0.01)
+    ost = oracle.GradState(gamma=0.2, beta=0.01, gamma_min=0.01)
+    for it in range(30):
+        if it == 15:
+            saved = lbt.lbt_state_read(st)
+            st = lbt.new_state()
+            lbt.lbt_state_write(st, saved)
+        oracle.quantize_grad(g, ost, seed=4, rounding=1)
+        gu.quantize_grad(g, st, seed=4, rounding=1)
+        oracle.update_interval(ost)
+        lbt.lbt_update_interval(st)
+        gu.assert_state_equal(lbt.lbt_state_read(st), ost)
+
+
+# -- operand quantizer ----------------------------------------------------------------
+@pytest.mark.parametrize("unsigned", [False, True])
+@pytest.mark.parametrize("c", [0.0, 0.7])
+def test_quantize_operand(unsigned, c):
+    r = synth.rng(0, 13, int(unsigned), synth.T_X)
+    for n in (5, 4096, 100003):
+        x = synth.relu_normal(r, (n,)) if unsigned else synth.normal(r, (n,))
+        want, c_used, s, _ = oracle.quantize_operand(x, c, unsigned)
+        packed, cs = gu.quantize_operand(x, c, unsigned)
+        assert np.array_equal(gu.unpack_nibbles(packed, n, not unsigned), want)
+        assert cs[0] == c_used and cs[1] == np.float32(s)
+
+
+# -- linear backward --------------------------------------------------------------------
+def _check_backward(res, ref):
+    if ref.acc_dx is not None:
+        assert np.array_equal(res.acc_dx, ref.acc_dx), "dX int32 accumulators differ"
+        gu.assert_outputs_close(res.dX, ref.dX)
+    if ref.acc_dw is not None:
+        assert np.array_equal(res.acc_dw, ref.acc_dw), "dW int32 accumulators differ"
+        gu.assert_outputs_close(res.dW, ref.dW)
+
+
+def test_backward_linear_config1():
+    L = synth.linear_case()
+    r = synth.rng(0, 1, 0, 0)
+    X, W = synth.normal(r, (L.M, L.K)), synth.normal(r, (L.K, L.N), 0.02)
+    st = lbt.new_state(gamma0=1.0)
+    ost = oracle.GradState(gamma=1.0)
+    for it in range(10):
+        dY = synth.grad_cfg1(synth.rng(0, 1, 0, synth.T_DY, it), (L.M, L.N))
+        ref = oracle.backward_linear(X, W, dY, ost, x_unsigned=False, seed=2, rounding=1)
+        res = gu.backward_linear(X, W, dY, st, x_unsigned=False, seed=2, rounding=1)
+        _check_backward(res, ref)
+        oracle.update_interval(ost)
+        lbt.lbt_update_interval(st)
+        gu.assert_state_equal(lbt.lbt_state_read(st), ost)
+
+
+@pytest.mark.parametrize("shape", [(1, 1, 1), (3, 5, 7), (130, 70, 200), (64, 2048, 1000),
+                                   (257, 129, 33)])
+@pytest.mark.parametrize("x_unsigned", [False, True])
+def test_backward_linear_shapes(shape, x_unsigned):
+    M, K, N = shape
+    _say("linear", shape, x_unsigned)
+    r = synth.rng(0, 14, M, 0)
+    X = synth.relu_normal(r, (M, K)) if x_unsigned else synth.normal(r, (M, K))
+    W = synth.normal(r, (K, N), 0.05)
+    dY = synth.dense_grad(r, (M, N))
+    ost = oracle.GradState(gamma=0.9)
+    st = lbt.new_state(gamma0=0.9)
+    ref = oracle.backward_linear(X, W, dY, ost, x_unsigned=x_unsigned, c_w=0.08)
+    res = gu.backward_linear(X, W, dY, st, x_unsigned=x_unsigned, c_w=0.08)
+    gu.assert_state_equal(lbt.lbt_state_read(st), ost)
+    _check_backward(res, ref)
+
+
+# -- conv backward ------------------------------------------------------------------------
+CONV_CASES = [
+    # N, C, H, W, K, R, S, stride, pad
+    (2, 3, 8, 8, 4, 3, 3, 1, 1),
+    (3, 5, 9, 7, 6, 3, 3, 2, 1),
+    (3, 20, 10, 10, 24, 1, 1, 2, 0),
+    (2, 3, 20, 20, 8, 7, 7, 2, 3),
+    (5, 17, 6, 6, 33, 1, 1, 1, 0),
+    (1, 2, 7, 8, 3, 3, 3, 2, 0),
+    (16, 16, 32, 32, 16, 3, 3, 1, 1),      # CIFAR-net stage 1 at a reduced batch
+    (16, 64, 8, 8, 64, 3, 3, 1, 1),        # CIFAR-net stage 3
+    (8, 64, 14, 14, 160, 1, 1, 1, 0),      # bottleneck 1x1, several tiles
+    (4, 130, 14, 14, 140, 3, 3, 1, 1),     # ragged channel counts across tile edges
+    (20, 32, 12, 12, 48, 3, 3, 2, 1),      # batch not a multiple of 16
+]
+
+
+@pytest.mark.parametrize("case", CONV_CASES)
+@pytest.mark.parametrize("rounding", [0, 1])
+def test_backward_conv2d_cases(case, rounding):
+    N, Cc, H, W, K, R, S, stride, pad = case
+    _say("conv", case, rounding)
+    r = synth.rng(0, 15, Cc * 131 + K, 0)
+    X, Wt = synth.relu_normal(r, (N, Cc, H, W)), synth.kaiming_normal(r, (K, Cc, R, S))
+    P, Q = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1
+    for dist, gamma in ((synth.grad_cfg2, 0.3), (synth.dense_grad, 1.0)):
+        dY = dist(r, (N, K, P, Q))
+        ost = oracle.GradState(gamma=gamma, step=1)
+        st = lbt.new_state(gamma0=gamma)
+        h = lbt.lbt_state_read(st)
+        h.step = 1
+        lbt.lbt_state_write(st, h)
+        ref = oracle.backward_conv2d(X, Wt, dY, stride, pad, ost, x_unsigned=True, seed=7,
+                                     rounding=rounding)
+        res = gu.backward_conv2d(X, Wt, dY, stride, pad, st, x_unsigned=True, seed=7,
+                                 rounding=rounding)
+        gu.assert_state_equal(lbt.lbt_state_read(st), ost)
+        _check_backward(res, ref)
+
+
+def test_backward_conv2d_signed_input_and_given_clips():
+    N, Cc, H, W, K, R, S, stride, pad = 4, 24, 10, 10, 40, 3, 3, 1, 1
+    r = synth.rng(0, 16, 0, 0)
+    X, Wt = synth.normal(r, (N, Cc, H, W)), synth.kaiming_normal(r, (K, Cc, R, S))
+    dY = synth.grad_cfg5(r, (N, K, H, W))
+    ost = oracle.GradState(gamma=0.05)
+    st = lbt.new_state(gamma0=0.05)
+    ref = oracle.backward_conv2d(X, Wt, dY, stride, pad, ost, c_x=1.5, x_unsigned=False, c_w=0.1)
+    res = gu.backward_conv2d(X, Wt, dY, stride, pad, st, c_x=1.5, x_unsigned=False, c_w=0.1)
+    gu.assert_state_equal(lbt.lbt_state_read(st), ost)
+    _check_backward(res, ref)
+
+
+def test_backward_skips_and_degenerate():
+    N, Cc, H, W, K, R, S, stride, pad = 2, 8, 6, 6, 8, 3, 3, 1, 1
+    r = synth.rng(0, 17, 0, 0)
+    X, Wt = synth.relu_normal(r, (N, Cc, H, W)), synth.kaiming_normal(r, (K, Cc, R, S))
+    dY = synth.dense_grad(r, (N, K, H, W))
+    ost = oracle.GradState(gamma=0.5)
+    ref = oracle.backward_conv2d(X, Wt, dY, stride, pad, ost)
+    st = lbt.new_state(gamma0=0.5)
+    only_dw = gu.backward_conv2d(X, Wt, dY, stride, pad, st, want_dx=False)   # first layer: no dX
+    assert only_dw.dX is None and np.array_equal(only_dw.acc_dw, ref.acc_dw)
+    only_dx = gu.backward_conv2d(X, Wt, dY, stride, pad, st, want_dw=False)
+    assert only_dx.dW is None and np.array_equal(only_dx.acc_dx, ref.acc_dx)
+    zero = gu.backward_conv2d(X, Wt, np.zeros_like(dY), stride, pad, st)
+    assert lbt.lbt_state_read(st).status == lbt.STATUS_ZERO_GRAD
+    assert not zero.dX.any() and not zero.dW.any()
+    bad = dY.copy()
+    bad[0, 0, 0, 0] = np.nan
+    gu.backward_conv2d(X, Wt, bad, stride, pad, st)
+    assert lbt.lbt_state_read(st).status == lbt.STATUS_NONFINITE
+
+
+def test_backward_is_deterministic():
+    # split-K uses integer atomics: any order gives the same bits
+    N, Cc, H, W, K, R, S, stride, pad = 16, 32, 16, 16, 32, 3, 3, 1, 1
+    r = synth.rng(0, 18, 0, 0)
+    X, Wt = synth.relu_normal(r, (N, Cc, H, W)), synth.kaiming_normal(r, (K, Cc, R, S))
+    dY = synth.dense_grad(r, (N, K, H, W))
+    st = lbt.new_state(gamma0=1.0)
+    a = gu.backward_conv2d(X, Wt, dY, stride, pad, st, seed=3, rounding=1)
+    b = gu.backward_conv2d(X, Wt, dY, stride, pad, st, seed=3, rounding=1)
+    assert np.array_equal(a.dW, b.dW) and np.array_equal(a.dX, b.dX)
