@@ -1,0 +1,235 @@
+#!/usr/bin/env python3
+"""Benchmark of the INT4 quantized backward pass on one MI355X.
+
+A "step" is one pass of the whole hot path over the ResNet-50 bottleneck sweep at
+batch 64 (every bottleneck convolution of the network plus the classifier, 53
+layers): per layer the gradient quantizer (max, clip value gamma*g_max, stochastic
+rounding, clip-out count, pack), the operand quantizers for X and W, the integer dX
+and dW contractions with dequantisation, and the clipping-factor update.  Inputs
+are seeded synthetic tensors already resident in HBM: ReLU'd normal activations,
+Kaiming-normal weights, Student-t(2.5) gradients scaled by 1e-3.
+
+Prints ONE JSON line: whole-job TOPS of the two contractions over the full step
+time, the roofline position of the dominant kernel (from HIP-event timings taken by
+the library around each of its launches) and the CPU oracle timed on a bounded
+sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "INT4 backward TOPS (dX+dW) + quantize GB/s, ResNet-50 layers, % roofline"
+PEAK_HBM_GBPS = 8000.0          # MI355X HBM3E
+PEAK_INT8_TOPS = 5000.0         # MI355X dense int8 MFMA
+BYTES_PER_GRAD_ELEMENT = 4.5    # algorithmic: 4 B fp32 read + 0.5 B code written
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--rounding", choices=["stochastic", "nearest"], default="stochastic")
+    ap.add_argument("--gamma0", type=float, default=1.0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-timing", action="store_true")
+    ap.add_argument("--layer", default=None, help="run only layers whose name contains this")
+    return ap.parse_args()
+
+
+class LayerRun:
+    """Device tensors and state of one layer occurrence."""
+
+    def __init__(self, spec, idx, torch, lbt, gen, is_linear):
+        dev = "cuda"
+        self.spec, self.is_linear = spec, is_linear
+        f32 = torch.float32
+        if is_linear:
+            xs, ws, gs = (spec.M, spec.K), (spec.K, spec.N), (spec.M, spec.N)
+            fan_in = spec.K
+        else:
+            xs, ws, gs = spec.x_shape, spec.w_shape, spec.dy_shape
+            fan_in = spec.C * spec.R * spec.S
+        self.X = torch.randn(xs, generator=gen, device=dev, dtype=f32).clamp_(min=0)
+        self.W = torch.randn(ws, generator=gen, device=dev, dtype=f32).mul_((2.0 / fan_in) ** 0.5)
+        # Student-t(nu) = Z / sqrt(chi2_nu / nu), chi2_nu = 2 * Gamma(nu / 2)
+        nu = 2.5
+        z = torch.randn(gs, generator=gen, device=dev, dtype=f32)
+        chi2 = torch._standard_gamma(torch.full(gs, nu / 2, device=dev, dtype=f32), generator=gen) * 2
+        self.dY = (z / (chi2 / nu).sqrt_()).mul_(1e-3)
+        del z, chi2
+        self.dX = torch.empty(xs, device=dev, dtype=f32)
+        self.dW = torch.empty(ws, device=dev, dtype=f32)
+        self.state = None
+        self.seed = 1000 + idx
+
+    def ws_bytes(self, lbt):
+        s = self.spec
+        if self.is_linear:
+            return lbt.lbt_workspace_bytes_linear(s.M, s.K, s.N)
+        return lbt.lbt_workspace_bytes_conv2d(s.N, s.C, s.H, s.W, s.K, s.R, s.S, s.stride, s.pad)
+
+    def run(self, lbt, ws, rounding):
+        s = self.spec
+        if self.is_linear:
+            lbt.lbt_backward_linear(self.X, self.W, self.dY, s.M, s.K, s.N, 0.0, True, 0.0,
+                                    self.state, self.seed, rounding, self.dX, self.dW, ws)
+        else:
+            lbt.lbt_backward_conv2d(self.X, self.W, self.dY, s.N, s.C, s.H, s.W, s.K, s.R, s.S,
+                                    s.stride, s.pad, 0.0, True, 0.0, self.state, self.seed,
+                                    rounding, self.dX, self.dW, ws)
+        lbt.lbt_update_interval(self.state)
+
+
+def cpu_baseline(layers, rounding):
+    """Time the CPU oracle (as it stands) on a few layers of the same sweep."""
+    import numpy as np
+
+    import oracle
+    pick = ["l3.3x3.256-256@14", "l2.1x1.128-512@28", "l4.1x1.512-2048@7", "l1.3x3.64-64@56"]
+    chosen = [L for L in layers if not L.is_linear and L.spec.name in pick]
+    seen, sample = set(), []
+    for L in chosen:
+        if L.spec.name not in seen:
+            seen.add(L.spec.name)
+            sample.append(L)
+    ops, n_grad, t_total, t_quant = 0.0, 0, 0.0, 0.0
+    for L in sample:
+        s = L.spec
+        X, W, dY = (t.cpu().numpy() for t in (L.X, L.W, L.dY))
+        st = oracle.GradState(gamma=1.0)
+        t0 = time.perf_counter()
+        oracle.quantize_grad(dY, st, L.seed, rounding)
+        t1 = time.perf_counter()
+        st = oracle.GradState(gamma=1.0)
+        oracle.backward_conv2d(X, W, dY, s.stride, s.pad, st, x_unsigned=True, seed=L.seed,
+                               rounding=rounding)
+        oracle.update_interval(st)
+        t2 = time.perf_counter()
+        ops += 2.0 * s.gemm_ops
+        n_grad += dY.size
+        t_quant += t1 - t0
+        t_total += t2 - t1
+    return {
+        "value": ops / t_total / 1e12, "unit": "TOPS", "cores": oracle.num_threads(),
+        "kind": "oracle",
+        "sample": "full backward (quantize dY/X/W + dX + dW + update) of %d layers: %s; %.1f s"
+                  % (len(sample), ", ".join(L.spec.name for L in sample), t_total),
+        "quantize_GBps": n_grad * BYTES_PER_GRAD_ELEMENT / t_quant / 1e9,
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives are part of it); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    from paper_2407_12637_amd import binding as lbt
+    from paper_2407_12637_amd import synth
+
+    lbt.load()
+    torch.cuda.set_device(0)
+    rounding = lbt.ROUND_STOCHASTIC if args.rounding == "stochastic" else lbt.ROUND_NEAREST
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(0)
+
+    layers = []
+    for spec in synth.resnet50_layers(64):
+        if args.layer and args.layer not in spec.name:
+            continue
+        for _ in range(spec.count):
+            layers.append(LayerRun(spec, len(layers), torch, lbt, gen,
+                                   isinstance(spec, synth.LinearLayer)))
+    for L in layers:
+        L.state = lbt.new_state(gamma0=args.gamma0)
+    ws = torch.empty(max(L.ws_bytes(lbt) for L in layers), dtype=torch.uint8, device="cuda")
+    gemm_ops = sum(2.0 * L.spec.gemm_ops for L in layers)       # dX and dW
+    n_grad = sum(L.dY.numel() for L in layers)
+
+    def step():
+        for L in layers:
+            L.run(lbt, ws, rounding)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+
+    out = {
+        "metric": METRIC, "value": gemm_ops / (dt / args.steps) / 1e12, "unit": "TOPS",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8",
+        "data": "synthetic",
+        "config": {"workload": "ResNet-50 bottleneck sweep, batch 64, %d layers, INT4 W/A/G, "
+                               "%s rounding, gamma0=%g" % (len(layers), args.rounding, args.gamma0),
+                   "gemm_GOP_per_step": gemm_ops / 1e9, "grad_elements_per_step": n_grad},
+    }
+
+    if not args.no_kernel_timing:
+        # same steps again with the library's event timing on: per-kernel durations
+        lbt.lbt_profile_enable(True)
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        out["ms_per_step_with_kernel_timing"] = (time.perf_counter() - t0) / args.steps * 1e3
+        prof = lbt.lbt_profile_read()
+        lbt.lbt_profile_enable(False)
+        kernels = {}
+        for name, (launches, ms, work) in prof.items():
+            if not launches:
+                continue
+            k = {"launches_per_step": launches / args.steps, "ms_per_step": ms / args.steps,
+                 "avg_us": ms / launches * 1e3}
+            if "gemm" in name:
+                k["TOPS"] = work / (ms * 1e-3) / 1e12
+            elif "quantize" in name or "absmax" in name:
+                per = BYTES_PER_GRAD_ELEMENT if "quantize" in name else 4.0
+                k["GBps"] = work * per / (ms * 1e-3) / 1e9
+            kernels[name] = k
+        out["kernels"] = kernels
+        dom = max(kernels, key=lambda n: kernels[n]["ms_per_step"])
+        if "gemm" in dom:
+            ach = kernels[dom]["TOPS"]
+            out["roofline"] = {"kernel": dom, "bound": "mfma", "achieved": ach,
+                               "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
+                               "frac": ach / PEAK_INT8_TOPS, "traffic": None}
+        else:
+            ach = kernels[dom].get("GBps", 0.0)
+            out["roofline"] = {"kernel": dom, "bound": "hbm", "achieved": ach,
+                               "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBPS,
+                               "traffic": None}
+        q = kernels.get("k_quantize_relayout(grad)")
+        if q:
+            out["quantize_GBps"] = q["GBps"]
+            out["quantize_frac_of_hbm_peak"] = q["GBps"] / PEAK_HBM_GBPS
+        g = [kernels[n] for n in kernels if "gemm" in n]
+        if g:
+            tops = gemm_ops / (sum(k["ms_per_step"] for k in g) * 1e-3) / 1e12
+            out["gemm_TOPS"] = tops
+            out["gemm_frac_of_int8_peak"] = tops / PEAK_INT8_TOPS
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(layers, rounding)
+
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -172,6 +172,22 @@ int lbt_backward_conv2d_acc(const float* X, const float* W, const float* dY, int
                             float* dW, int32_t* acc_dX, int32_t* acc_dW, void* ws,
                             size_t ws_bytes, void* stream);
 
+/*
+ * Optional per-kernel timing (off by default).  While enabled, each kernel the
+ * library launches is bracketed by HIP events on the caller's stream.
+ * lbt_profile_read waits for the recorded launches and returns, per kernel
+ * class 0 .. lbt_profile_kernel_count()-1, the number of launches, their
+ * summed duration in ms and their summed algorithmic work (elements for the
+ * element-wise kernels, integer operations for the contractions, counted as
+ * 2*N*P*Q*K*C*R*S per product); it then clears the records.  Host arrays of
+ * `capacity` >= kernel count entries.  lbt_profile_enable also clears.
+ * Process-wide; not meant for concurrent use from several threads' streams.
+ */
+int lbt_profile_enable(int on);
+int lbt_profile_kernel_count(void);
+const char* lbt_profile_kernel_name(int kernel_class);
+int lbt_profile_read(int64_t* launches, double* total_ms, double* total_work, int capacity);
+
 #ifdef __cplusplus
 }
 #endif

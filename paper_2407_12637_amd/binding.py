@@ -64,6 +64,10 @@ SIGNATURES = {
                                        _int, _p, _p, _p, _p, _p, _sz, _p]),
     "lbt_backward_conv2d_acc": (_int, [_p, _p, _p] + [_i64] * 9 + [_f32, _int, _f32, _p, _u64, _int,
                                                                    _p, _p, _p, _p, _p, _sz, _p]),
+    "lbt_profile_enable": (_int, [_int]),
+    "lbt_profile_kernel_count": (_int, []),
+    "lbt_profile_kernel_name": (C.c_char_p, [_int]),
+    "lbt_profile_read": (_int, [_p, _p, _p, _int]),
 }
 
 
@@ -201,3 +205,19 @@ def lbt_backward_conv2d_acc(X, W, dY, N, Cc, H, Wd, K, R, S, stride, pad, c_x, x
                                           pad, c_x, int(x_unsigned), c_w, _dp(st), seed, rounding,
                                           _dp(dX), _dp(dW), _dp(acc_dX), _dp(acc_dW), wp, wb,
                                           _stream()), "lbt_backward_conv2d_acc")
+
+
+def lbt_profile_enable(on: bool):
+    _check(load().lbt_profile_enable(int(on)), "lbt_profile_enable")
+
+
+def lbt_profile_read():
+    """{kernel class name: (launches, total ms, total algorithmic work)} since the last read."""
+    lib = load()
+    n = lib.lbt_profile_kernel_count()
+    launches = (C.c_int64 * n)()
+    ms = (C.c_double * n)()
+    work = (C.c_double * n)()
+    _check(lib.lbt_profile_read(launches, ms, work, n), "lbt_profile_read")
+    return {lib.lbt_profile_kernel_name(i).decode(): (int(launches[i]), float(ms[i]), float(work[i]))
+            for i in range(n)}

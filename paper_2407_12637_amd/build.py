@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblbt.so")
-SOURCES = ["lbt_api.hip", "lbt_quantize.hip", "lbt_gemm.hip"]
+SOURCES = ["lbt_api.hip", "lbt_quantize.hip", "lbt_gemm.hip", "lbt_profile.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

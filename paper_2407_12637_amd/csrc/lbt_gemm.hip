@@ -264,6 +264,9 @@ static void fill_geom(GemmArgs& g, const ConvGeom& c) {
 }
 
 static int run_gemm(const GemmArgs& g, bool a_uns, bool b_uns, int splits, hipStream_t s) {
+  // algorithmic work: the convolution's multiply-adds, padding taps included
+  const double work = 2.0 * g.N * g.P * g.Q * (double)g.K * g.C * g.R * g.S;
+  ProfScope prof(g.epi == 1 ? KID_GEMM_DW : KID_GEMM_DX, work, s);
   dim3 grid((unsigned)((g.NJ + BN - 1) / BN), (unsigned)((g.M + BM - 1) / BM), (unsigned)splits);
   if (grid.y > 65535u || grid.z > 65535u) return LBT_ERR_UNSUPPORTED;
   if (a_uns && b_uns) return LBT_ERR_UNSUPPORTED;
@@ -305,12 +308,18 @@ static int run_dw(GemmArgs& g, bool a_uns, bool b_uns, long long true_k, int32_t
   splits = (g.chunks + per - 1) / per;
   g.chunks_per_split = per;
   const long long n_out = (long long)g.M * g.NJ;
-  hipLaunchKernelGGL(k_zero_i32, dim3(small_grid(n_out)), dim3(kThreads), 0, s,
-                     reinterpret_cast<int32_t*>(g.out), n_out);
+  {
+    ProfScope prof(KID_ZERO, (double)n_out, s);
+    hipLaunchKernelGGL(k_zero_i32, dim3(small_grid(n_out)), dim3(kThreads), 0, s,
+                       reinterpret_cast<int32_t*>(g.out), n_out);
+  }
   int rc = run_gemm(g, a_uns, b_uns, splits, s);
   if (rc) return rc;
-  hipLaunchKernelGGL(k_finalize_dw, dim3(small_grid(n_out)), dim3(kThreads), 0, s, g.out, acc, n_out,
-                     g.st, g.sc, x_unsigned);
+  {
+    ProfScope prof(KID_FINALIZE, (double)n_out, s);
+    hipLaunchKernelGGL(k_finalize_dw, dim3(small_grid(n_out)), dim3(kThreads), 0, s, g.out, acc,
+                       n_out, g.st, g.sc, x_unsigned);
+  }
   LBT_LAUNCH_CHECK();
   return LBT_OK;
 }
@@ -384,7 +393,6 @@ int launch_linear_dw(const ConvGeom& c, const uint8_t* g_kn, const uint8_t* x_cn
   fill_geom(g, c);
   g.A = x_cn;   // [C][Np] activation rows
   g.B = g_kn;   // [K][Np] gradient rows
-  g.C = c.K;    // the gathered tensor has K rows
   g.inner_chunks = c.Np / kGranule;
   g.chunks = g.inner_chunks;
   g.lda = (long long)g.chunks * 8;

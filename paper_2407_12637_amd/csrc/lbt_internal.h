@@ -33,6 +33,27 @@ struct OperandScalars {
   uint32_t pad[3];
 };
 
+// ---- profile.hip: optional event timing of every launch ------------------------
+enum KernelId {
+  KID_BEGIN = 0, KID_ABSMAX, KID_GRAD_PREPARE, KID_OPERAND_PREPARE, KID_FLAT_GRAD, KID_FLAT_OPERAND,
+  KID_RELAYOUT_GRAD, KID_RELAYOUT_OPERAND, KID_GEMM_DX, KID_GEMM_DW, KID_ZERO, KID_FINALIZE,
+  KID_UPDATE, KID_STATE, KID_COUNT
+};
+// Records a start event now and a stop event when it goes out of scope (after the
+// launch it brackets).  `work` is the algorithmic work of the launch: elements for
+// the element-wise kernels, integer operations (2 per multiply-add) for the GEMMs.
+class ProfScope {
+ public:
+  ProfScope(int kid, double work, hipStream_t s);
+  ~ProfScope();
+  ProfScope(const ProfScope&) = delete;
+  ProfScope& operator=(const ProfScope&) = delete;
+
+ private:
+  long long idx_;
+  hipStream_t s_;
+};
+
 // ---- quantize.hip -------------------------------------------------------------
 int launch_begin(lbt_grad_state* st, OperandScalars* sc, hipStream_t s);
 int launch_absmax(const float* x, int64_t n, int use_abs, uint32_t* max_bits, hipStream_t s);

@@ -393,12 +393,14 @@ int relayout_dispatch(const float* x, int64_t A, int64_t B, int64_t L, const flo
 }  // namespace
 
 int launch_begin(lbt_grad_state* st, OperandScalars* sc, hipStream_t s) {
+  ProfScope prof(KID_BEGIN, 0.0, s);
   hipLaunchKernelGGL(k_begin, dim3(1), dim3(1), 0, s, st, sc);
   LBT_LAUNCH_CHECK();
   return LBT_OK;
 }
 
 int launch_absmax(const float* x, int64_t n, int use_abs, uint32_t* max_bits, hipStream_t s) {
+  ProfScope prof(KID_ABSMAX, (double)n, s);
   hipLaunchKernelGGL(k_absmax, dim3(flat_grid((n / 4 + 3) / 4)), dim3(kThreads), 0, s, x,
                      (long long)n, use_abs, max_bits);
   LBT_LAUNCH_CHECK();
@@ -406,6 +408,7 @@ int launch_absmax(const float* x, int64_t n, int use_abs, uint32_t* max_bits, hi
 }
 
 int launch_grad_prepare(lbt_grad_state* st, int64_t n, hipStream_t s) {
+  ProfScope prof(KID_GRAD_PREPARE, 0.0, s);
   hipLaunchKernelGGL(k_grad_prepare, dim3(1), dim3(1), 0, s, st, (unsigned long long)n);
   LBT_LAUNCH_CHECK();
   return LBT_OK;
@@ -413,6 +416,7 @@ int launch_grad_prepare(lbt_grad_state* st, int64_t n, hipStream_t s) {
 
 int launch_operand_prepare(OperandScalars* sc, lbt_grad_state* st, float c_x, float c_w,
                            hipStream_t s) {
+  ProfScope prof(KID_OPERAND_PREPARE, 0.0, s);
   hipLaunchKernelGGL(k_operand_prepare, dim3(1), dim3(1), 0, s, sc, st, c_x, c_w);
   LBT_LAUNCH_CHECK();
   return LBT_OK;
@@ -420,6 +424,7 @@ int launch_operand_prepare(OperandScalars* sc, lbt_grad_state* st, float c_x, fl
 
 int launch_quantize_flat_grad(const float* g, int64_t n, lbt_grad_state* st, uint64_t seed,
                               int rounding, uint8_t* codes, hipStream_t s) {
+  ProfScope prof(KID_FLAT_GRAD, (double)n, s);
   const int grid = flat_grid((n + 7) / 8);
   if (rounding == LBT_ROUND_STOCHASTIC)
     hipLaunchKernelGGL(k_quantize_flat<3>, dim3(grid), dim3(kThreads), 0, s, g, (long long)n,
@@ -433,6 +438,7 @@ int launch_quantize_flat_grad(const float* g, int64_t n, lbt_grad_state* st, uin
 
 int launch_quantize_flat_operand(const float* x, int64_t n, const float* clip_ptr, int is_unsigned,
                                  uint8_t* codes, float* clip_scale_out, hipStream_t s) {
+  ProfScope prof(KID_FLAT_OPERAND, (double)n, s);
   const int grid = flat_grid((n + 7) / 8);
   if (is_unsigned)
     hipLaunchKernelGGL(k_quantize_flat<1>, dim3(grid), dim3(kThreads), 0, s, x, (long long)n,
@@ -447,6 +453,7 @@ int launch_quantize_flat_operand(const float* x, int64_t n, const float* clip_pt
 int launch_quantize_relayout_grad(const float* g, int64_t A, int64_t B, int64_t L,
                                   lbt_grad_state* st, uint64_t seed, int rounding, uint8_t* out_b,
                                   uint8_t* out_a, hipStream_t s) {
+  ProfScope prof(KID_RELAYOUT_GRAD, (double)A * (double)B * (double)L, s);
   if (rounding == LBT_ROUND_STOCHASTIC)
     return relayout_dispatch<3>(g, A, B, L, nullptr, st, seed, out_b, out_a, s);
   return relayout_dispatch<2>(g, A, B, L, nullptr, st, seed, out_b, out_a, s);
@@ -455,17 +462,20 @@ int launch_quantize_relayout_grad(const float* g, int64_t A, int64_t B, int64_t 
 int launch_quantize_relayout_operand(const float* x, int64_t A, int64_t B, int64_t L,
                                      const float* clip_ptr, int is_unsigned, uint8_t* out_b,
                                      uint8_t* out_a, hipStream_t s) {
+  ProfScope prof(KID_RELAYOUT_OPERAND, (double)A * (double)B * (double)L, s);
   if (is_unsigned) return relayout_dispatch<1>(x, A, B, L, clip_ptr, nullptr, 0, out_b, out_a, s);
   return relayout_dispatch<0>(x, A, B, L, clip_ptr, nullptr, 0, out_b, out_a, s);
 }
 
 int launch_update_interval(lbt_grad_state* st, hipStream_t s) {
+  ProfScope prof(KID_UPDATE, 0.0, s);
   hipLaunchKernelGGL(k_update_interval, dim3(1), dim3(1), 0, s, st);
   LBT_LAUNCH_CHECK();
   return LBT_OK;
 }
 
 int launch_state_init(lbt_grad_state* st, const lbt_grad_state& v, hipStream_t s) {
+  ProfScope prof(KID_STATE, 0.0, s);
   hipLaunchKernelGGL(k_state_set, dim3(1), dim3(1), 0, s, st, v);
   LBT_LAUNCH_CHECK();
   return LBT_OK;
