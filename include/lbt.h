@@ -67,10 +67,12 @@ typedef struct lbt_grad_state {
   uint64_t step;     /* number of updates done; also the RNG's iteration word       */
   uint64_t n_total;  /* N(G) of the last quantized gradient                         */
   uint64_t n_out;    /* N(G_out): number of |g| > c_g (strict)                      */
+  uint64_t sync_word; /* internal: count + arrival ticket of the running quantizer;
+                         zero between calls                                         */
   float gmax;        /* g_max = max|G|                                              */
   float clip;        /* c_g = (float)(gamma * (double)g_max)                        */
   float scale;       /* s = c_g / (2^(b-1) - 1), Eq. (2)                            */
-  uint32_t reserved[3];
+  uint32_t reserved;
 } lbt_grad_state;
 
 const char* lbt_version(void);

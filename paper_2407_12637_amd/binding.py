@@ -33,8 +33,9 @@ class GradState(C.Structure):
         ("gamma_min", C.c_double), ("gamma_max", C.c_double),
         ("bits", C.c_int32), ("status", C.c_int32),
         ("step", C.c_uint64), ("n_total", C.c_uint64), ("n_out", C.c_uint64),
+        ("sync_word", C.c_uint64),
         ("gmax", C.c_float), ("clip", C.c_float), ("scale", C.c_float),
-        ("reserved", C.c_uint32 * 3),
+        ("reserved", C.c_uint32),
     ]
 
 

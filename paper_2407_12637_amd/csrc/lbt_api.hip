@@ -10,14 +10,14 @@ inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_
 inline size_t pad256(size_t b) { return (b + 255) / 256 * 256; }
 
 struct ConvWorkspace {
-  size_t off_scalars, off_g_npqk, off_g_kpqn, off_x_chwn, off_w_crsk, total;
+  size_t off_scalars, off_g_npqk, off_g_kpqn, off_x_chwn, off_w_crsk, off_partial, total;
 };
 
-ConvWorkspace conv_workspace(const ConvGeom& g) {
+ConvWorkspace conv_workspace(const ConvGeom& g, bool is_linear) {
   ConvWorkspace w{};
   size_t o = 0;
   w.off_scalars = o;
-  o += 256;
+  o += kWsHeaderBytes;
   w.off_g_npqk = o;
   o += pad256((size_t)g.N * g.P * g.Q * g.Kp / 2);
   w.off_g_kpqn = o;
@@ -26,6 +26,11 @@ ConvWorkspace conv_workspace(const ConvGeom& g) {
   o += pad256((size_t)g.C * g.H * g.W * g.Np / 2);
   w.off_w_crsk = o;
   o += pad256((size_t)g.C * g.R * g.S * g.Kp / 2);
+  w.off_partial = o;
+  const SplitPlan plan = is_linear
+      ? plan_split_k(g.C, g.K, g.Np / kGranule)
+      : plan_split_k(g.K, g.C * g.R * g.S, g.P * g.Q * (g.Np / kGranule));
+  o += pad256(plan.partial_bytes);
   w.total = o;
   return w;
 }
@@ -59,7 +64,7 @@ int backward_common(const float* X, const float* W, const float* dY, const ConvG
   if (!aligned(dY, 16) || !aligned(W, 16) || (X && !aligned(X, 16)) || !aligned(ws, 256) ||
       (dX && !aligned(dX, 16)) || (dW && !aligned(dW, 16)) || !aligned(st, 8))
     return LBT_ERR_ALIGN;
-  const ConvWorkspace lay = conv_workspace(g);
+  const ConvWorkspace lay = conv_workspace(g, w_is_ck);
   if (ws_bytes < lay.total) return LBT_ERR_WORKSPACE;
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   uint8_t* base = static_cast<uint8_t*>(ws);
@@ -68,41 +73,46 @@ int backward_common(const float* X, const float* W, const float* dY, const ConvG
   uint8_t* g_kpqn = base + lay.off_g_kpqn;
   uint8_t* x_chwn = base + lay.off_x_chwn;
   uint8_t* w_crsk = base + lay.off_w_crsk;
+  int32_t* partial = reinterpret_cast<int32_t*>(base + lay.off_partial);
 
+  uint32_t* pmax = reinterpret_cast<uint32_t*>(base + kWsScalarsBytes);
   const int64_t n_dy = (int64_t)g.N * g.K * g.P * g.Q;
   const int64_t n_x = (int64_t)g.N * g.C * g.H * g.W;
   const int64_t n_w = (int64_t)g.K * g.C * g.R * g.S;
-  int rc;
-  if ((rc = launch_begin(st, sc, s))) return rc;
-  if ((rc = launch_absmax(dY, n_dy, 1, reinterpret_cast<uint32_t*>(&st->gmax), s))) return rc;
-  if (dW && !(c_x > 0.0f))
-    if ((rc = launch_absmax(X, n_x, x_unsigned ? 0 : 1, &sc->xmax_bits, s))) return rc;
-  if (dX && !(c_w > 0.0f))
-    if ((rc = launch_absmax(W, n_w, 1, &sc->wmax_bits, s))) return rc;
-  if ((rc = launch_grad_prepare(st, n_dy, s))) return rc;
-  if ((rc = launch_operand_prepare(sc, st, c_x, c_w, s))) return rc;
-  if ((rc = launch_quantize_relayout_grad(dY, g.N, g.K, (int64_t)g.P * g.Q, st, seed, rounding,
+  const int64_t PQ = (int64_t)g.P * g.Q, HW = (int64_t)g.H * g.W, RS = (int64_t)g.R * g.S;
+  int rc, nblocks = 0;
+  // 1. maxima of dY, and of X / W where no clip value was given, in one launch
+  const bool max_x = dW && !(c_x > 0.0f), max_w = dX && !(c_w > 0.0f);
+  if ((rc = launch_absmax3(dY, n_dy, 1, max_x ? X : nullptr, n_x, x_unsigned ? 0 : 1,
+                           max_w ? W : nullptr, n_w, 1, pmax, &nblocks, s)))
+    return rc;
+  // 2. gradient codes in the layouts the two products read
+  if ((rc = launch_quantize_relayout_grad(dY, g.N, g.K, PQ, pmax, nblocks, st, seed, rounding,
                                           dX ? g_npqk : nullptr, dW ? g_kpqn : nullptr, s)))
     return rc;
+  // 3. activation codes
   if (dW) {
-    if ((rc = launch_quantize_relayout_operand(X, g.N, g.C, (int64_t)g.H * g.W, &sc->c_x,
-                                               x_unsigned, nullptr, x_chwn, s)))
+    if ((rc = launch_quantize_relayout_operand(X, g.N, g.C, HW, c_x, pmax, nblocks, 1, x_unsigned,
+                                               &sc->c_x, &sc->bad_x, st, nullptr, x_chwn, nullptr, 0,
+                                               s)))
       return rc;
   }
+  // 4. weight codes, then the two products
   if (dX) {
     if (w_is_ck)
-      rc = launch_quantize_relayout_operand(W, g.C, g.K, 1, &sc->c_w, 0, w_crsk, nullptr, s);
+      rc = launch_quantize_relayout_operand(W, g.C, g.K, 1, c_w, pmax, nblocks, 2, 0, &sc->c_w,
+                                            &sc->bad_w, st, w_crsk, nullptr, nullptr, 0, s);
     else
-      rc = launch_quantize_relayout_operand(W, g.K, g.C, (int64_t)g.R * g.S, &sc->c_w, 0, nullptr,
-                                            w_crsk, s);
+      rc = launch_quantize_relayout_operand(W, g.K, g.C, RS, c_w, pmax, nblocks, 2, 0, &sc->c_w,
+                                            &sc->bad_w, st, nullptr, w_crsk, nullptr, 0, s);
     if (rc) return rc;
     rc = w_is_ck ? launch_linear_dx(g, w_crsk, g_npqk, st, sc, dX, acc_dX, s)
                  : launch_conv_dx(g, w_crsk, g_npqk, st, sc, dX, acc_dX, s);
     if (rc) return rc;
   }
   if (dW) {
-    rc = w_is_ck ? launch_linear_dw(g, g_kpqn, x_chwn, st, sc, x_unsigned, dW, acc_dW, s)
-                 : launch_conv_dw(g, g_kpqn, x_chwn, st, sc, x_unsigned, dW, acc_dW, s);
+    rc = w_is_ck ? launch_linear_dw(g, g_kpqn, x_chwn, st, sc, x_unsigned, dW, acc_dW, partial, s)
+                 : launch_conv_dw(g, g_kpqn, x_chwn, st, sc, x_unsigned, dW, acc_dW, partial, s);
     if (rc) return rc;
   }
   return LBT_OK;
@@ -138,7 +148,7 @@ int lbt_state_init(lbt_grad_state* st, double gamma0, double alpha, double beta,
   if (!(gamma_min > 0.0) || !(gamma_max >= gamma_min) || !(gamma0 >= gamma_min) ||
       !(gamma0 <= gamma_max) || !(alpha > 0.0) || !(beta >= 0.0))
     return LBT_ERR_SHAPE;
-  lbt_grad_state v{};
+  lbt_grad_state v{};  // sync_word = 0: no quantizer in flight
   v.gamma = gamma0; v.alpha = alpha; v.beta = beta;
   v.gamma_min = gamma_min; v.gamma_max = gamma_max;
   v.bits = bits;
@@ -156,7 +166,9 @@ int lbt_state_read(const lbt_grad_state* st, lbt_grad_state* host_out, void* str
 int lbt_state_write(lbt_grad_state* st, const lbt_grad_state* host_in, void* stream) {
   if (!st || !host_in) return LBT_ERR_NULL;
   if (host_in->bits != 4) return LBT_ERR_UNSUPPORTED;
-  return launch_state_init(st, *host_in, reinterpret_cast<hipStream_t>(stream));
+  lbt_grad_state v = *host_in;
+  v.sync_word = 0;
+  return launch_state_init(st, v, reinterpret_cast<hipStream_t>(stream));
 }
 
 int lbt_update_interval(lbt_grad_state* st, void* stream) {
@@ -166,7 +178,7 @@ int lbt_update_interval(lbt_grad_state* st, void* stream) {
 
 size_t lbt_workspace_bytes_quantize(int64_t n) {
   (void)n;
-  return 256;
+  return kWsHeaderBytes;
 }
 
 int lbt_quantize_grad(const float* g, int64_t n, lbt_grad_state* st, uint64_t seed, int rounding,
@@ -178,11 +190,10 @@ int lbt_quantize_grad(const float* g, int64_t n, lbt_grad_state* st, uint64_t se
     return LBT_ERR_ALIGN;
   if (ws_bytes < lbt_workspace_bytes_quantize(n)) return LBT_ERR_WORKSPACE;
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-  int rc;
-  if ((rc = launch_begin(st, nullptr, s))) return rc;
-  if ((rc = launch_absmax(g, n, 1, reinterpret_cast<uint32_t*>(&st->gmax), s))) return rc;
-  if ((rc = launch_grad_prepare(st, n, s))) return rc;
-  return launch_quantize_flat_grad(g, n, st, seed, rounding, codes, s);
+  uint32_t* pmax = reinterpret_cast<uint32_t*>(static_cast<uint8_t*>(ws) + kWsScalarsBytes);
+  int rc, nblocks = 0;
+  if ((rc = launch_absmax3(g, n, 1, nullptr, 0, 0, nullptr, 0, 0, pmax, &nblocks, s))) return rc;
+  return launch_quantize_flat_grad(g, n, pmax, nblocks, st, seed, rounding, codes, s);
 }
 
 int lbt_quantize_operand(const float* x, int64_t n, float c, int is_unsigned, int bits,
@@ -195,23 +206,27 @@ int lbt_quantize_operand(const float* x, int64_t n, float c, int is_unsigned, in
   if (ws_bytes < lbt_workspace_bytes_quantize(n)) return LBT_ERR_WORKSPACE;
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   OperandScalars* sc = static_cast<OperandScalars*>(ws);
-  int rc;
-  if ((rc = launch_begin(nullptr, sc, s))) return rc;
+  uint32_t* pmax = reinterpret_cast<uint32_t*>(static_cast<uint8_t*>(ws) + kWsScalarsBytes);
+  int rc, nblocks = 0;
   if (!(c > 0.0f))
-    if ((rc = launch_absmax(x, n, is_unsigned ? 0 : 1, &sc->xmax_bits, s))) return rc;
-  if ((rc = launch_operand_prepare(sc, nullptr, c, 1.0f, s))) return rc;
-  return launch_quantize_flat_operand(x, n, &sc->c_x, is_unsigned, codes, clip_scale_out, s);
+    if ((rc = launch_absmax3(nullptr, 0, 0, x, n, is_unsigned ? 0 : 1, nullptr, 0, 0, pmax, &nblocks,
+                             s)))
+      return rc;
+  return launch_quantize_flat_operand(x, n, c, pmax, nblocks, is_unsigned, codes, &sc->c_x,
+                                      clip_scale_out, s);
 }
 
 size_t lbt_workspace_bytes_conv2d(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R,
                                   int64_t S, int64_t stride, int64_t pad) {
   ConvGeom g;
   if (make_geom(N, C, H, Wd, K, R, S, stride, pad, &g) != LBT_OK) return 0;
-  return conv_workspace(g).total;
+  return conv_workspace(g, false).total;
 }
 
 size_t lbt_workspace_bytes_linear(int64_t M, int64_t K_in, int64_t N_out) {
-  return lbt_workspace_bytes_conv2d(M, K_in, 1, 1, N_out, 1, 1, 1, 0);
+  ConvGeom g;
+  if (make_geom(M, K_in, 1, 1, N_out, 1, 1, 1, 0, &g) != LBT_OK) return 0;
+  return conv_workspace(g, true).total;
 }
 
 int lbt_backward_conv2d_acc(const float* X, const float* W, const float* dY, int64_t N, int64_t C,

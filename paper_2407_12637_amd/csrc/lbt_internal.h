@@ -25,12 +25,10 @@ inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 // Scalars shared between the kernels of one backward call; lives at the start
 // of the caller's workspace.
 struct OperandScalars {
-  uint32_t xmax_bits;  // atomicMax target: bits of max x (or max|x|)
-  uint32_t wmax_bits;
-  float c_x;           // clip value actually used for X
-  float c_w;
-  uint32_t nonfinite;  // set when an operand maximum is Inf/NaN
-  uint32_t pad[3];
+  float c_x;       // clip value actually used for X
+  float c_w;       // ... for W
+  uint32_t bad_x;  // operand maximum was Inf/NaN
+  uint32_t bad_w;
 };
 
 // ---- profile.hip: optional event timing of every launch ------------------------
@@ -55,24 +53,36 @@ class ProfScope {
 };
 
 // ---- quantize.hip -------------------------------------------------------------
-int launch_begin(lbt_grad_state* st, OperandScalars* sc, hipStream_t s);
-int launch_absmax(const float* x, int64_t n, int use_abs, uint32_t* max_bits, hipStream_t s);
-int launch_grad_prepare(lbt_grad_state* st, int64_t n, hipStream_t s);
-int launch_operand_prepare(OperandScalars* sc, lbt_grad_state* st, float c_x, float c_w, hipStream_t s);
-int launch_quantize_flat_grad(const float* g, int64_t n, lbt_grad_state* st, uint64_t seed,
-                              int rounding, uint8_t* codes, hipStream_t s);
-int launch_quantize_flat_operand(const float* x, int64_t n, const float* clip_ptr, int is_unsigned,
-                                 uint8_t* codes, float* clip_scale_out, hipStream_t s);
-// Quantize T[A][B][L] (L contiguous) into GEMM layouts: out_b [A][L][Bp] with the
-// B axis innermost, out_a [B][L][Ap] with the A axis innermost (either may be null).
-// Gradient flavour reads its clip value from *st and counts clip-outs; operand
-// flavour reads the clip value from *clip_ptr.
+constexpr int kMaxPartialBlocks = 2048;  // partial-maximum slots in the workspace header
+// Workspace header: OperandScalars (256 bytes), then pmax[kMaxPartialBlocks][4] uint32.
+constexpr size_t kWsScalarsBytes = 256;
+constexpr size_t kWsHeaderBytes = kWsScalarsBytes + (size_t)kMaxPartialBlocks * 16;
+
+// One launch for the maxima of up to three tensors (null pointer = absent); partial
+// maxima go to pmax[block][tensor].  *nblocks_out = number of partial rows written.
+int launch_absmax3(const float* p0, int64_t n0, int abs0, const float* p1, int64_t n1, int abs1,
+                   const float* p2, int64_t n2, int abs2, uint32_t* pmax, int* nblocks_out,
+                   hipStream_t s);
+int launch_quantize_flat_grad(const float* g, int64_t n, const uint32_t* pmax, int nblocks,
+                              lbt_grad_state* st, uint64_t seed, int rounding, uint8_t* codes,
+                              hipStream_t s);
+int launch_quantize_flat_operand(const float* x, int64_t n, float c_given, const uint32_t* pmax,
+                                 int nblocks, int is_unsigned, uint8_t* codes, float* c_out,
+                                 float* clip_scale_out, hipStream_t s);
+// Quantize T[A][B][L] (L contiguous) into GEMM layouts of 8-byte granules (16 codes):
+// out_b [A][ceil(B/16)][L][16] and out_a [B][ceil(A/16)][L][16] (either may be null).
+// The gradient flavour takes its clip value from gamma in *st and pmax column 0 and
+// leaves the statistics in *st; the operand flavour takes c_given (> 0) or pmax column
+// pmax_col, writes the clip value to *c_out, and can clear an int32 buffer on the side.
 int launch_quantize_relayout_grad(const float* g, int64_t A, int64_t B, int64_t L,
-                                  lbt_grad_state* st, uint64_t seed, int rounding, uint8_t* out_b,
-                                  uint8_t* out_a, hipStream_t s);
-int launch_quantize_relayout_operand(const float* x, int64_t A, int64_t B, int64_t L,
-                                     const float* clip_ptr, int is_unsigned, uint8_t* out_b,
-                                     uint8_t* out_a, hipStream_t s);
+                                  const uint32_t* pmax, int nblocks, lbt_grad_state* st,
+                                  uint64_t seed, int rounding, uint8_t* out_b, uint8_t* out_a,
+                                  hipStream_t s);
+int launch_quantize_relayout_operand(const float* x, int64_t A, int64_t B, int64_t L, float c_given,
+                                     const uint32_t* pmax, int nblocks, int pmax_col,
+                                     int is_unsigned, float* c_out, uint32_t* bad_out,
+                                     lbt_grad_state* st, uint8_t* out_b, uint8_t* out_a,
+                                     int32_t* zero_ptr, int64_t zero_n, hipStream_t s);
 int launch_update_interval(lbt_grad_state* st, hipStream_t s);
 int launch_state_init(lbt_grad_state* st, const lbt_grad_state& v, hipStream_t s);
 
@@ -81,22 +91,29 @@ struct ConvGeom {
   int N, C, H, W, K, R, S, P, Q, stride, pad;
   int Np, Kp;  // N and K rounded up to kGranule
 };
-// dX: A = W codes [C][R*S][Kp], B = dY codes [N][P*Q][Kp]; out/acc [N][C][H][W].
-int launch_conv_dx(const ConvGeom& g, const uint8_t* w_crsk, const uint8_t* g_npqk,
+// How the long contraction of dW is cut over workgroups.
+struct SplitPlan {
+  int bm;                // rows of the workgroup tile (64 or 128)
+  int splits;            // number of K slices
+  int chunks_per_split;  // chunks (16 codes) per slice
+  size_t partial_bytes;  // int32 partial tiles [splits][M][NJ]; 0 when splits == 1
+};
+SplitPlan plan_split_k(int M, int NJ, int chunks);
+
+// dX: A = W codes [C][Kp/16][R*S][16], B = dY codes [N][Kp/16][P*Q][16]; out/acc [N][C][H][W].
+int launch_conv_dx(const ConvGeom& g, const uint8_t* w_codes, const uint8_t* g_codes,
                    const lbt_grad_state* st, const OperandScalars* sc, float* dX, int32_t* acc,
                    hipStream_t s);
-// dW: A = dY codes [K][P*Q][Np], B = X codes [C][H*W][Np]; out/acc [K][C][R][S].
-// out doubles as the int32 split-K accumulation buffer before the final scaling.
-int launch_conv_dw(const ConvGeom& g, const uint8_t* g_kpqn, const uint8_t* x_chwn,
+// dW: A = dY codes [K][Np/16][P*Q][16], B = X codes [C][Np/16][H*W][16]; out/acc [K][C][R][S].
+int launch_conv_dw(const ConvGeom& g, const uint8_t* g_codes, const uint8_t* x_codes,
                    const lbt_grad_state* st, const OperandScalars* sc, int x_unsigned, float* dW,
-                   int32_t* acc, hipStream_t s);
-
+                   int32_t* acc, int32_t* partial, hipStream_t s);
 // Linear layer: A/B roles swapped so both outputs are written along their rows.
-int launch_linear_dx(const ConvGeom& g, const uint8_t* w_ck, const uint8_t* g_nk,
+int launch_linear_dx(const ConvGeom& g, const uint8_t* w_codes, const uint8_t* g_codes,
                      const lbt_grad_state* st, const OperandScalars* sc, float* dX, int32_t* acc,
                      hipStream_t s);
-int launch_linear_dw(const ConvGeom& g, const uint8_t* g_kn, const uint8_t* x_cn,
+int launch_linear_dw(const ConvGeom& g, const uint8_t* g_codes, const uint8_t* x_codes,
                      const lbt_grad_state* st, const OperandScalars* sc, int x_unsigned, float* dW,
-                     int32_t* acc, hipStream_t s);
+                     int32_t* acc, int32_t* partial, hipStream_t s);
 
 }  // namespace lbt

@@ -9,6 +9,12 @@
 //   t      = (double)clip(x) * inv_s          -- one double multiply, no FMA
 //   code   = rint(t)  |  floor(t + r16 / 65536)
 //   code   = clamp(code, -q or 0, q)
+//
+// Synchronisation between kernels uses no zero-initialised scratch: the maximum
+// pass writes one partial maximum per workgroup, the quantizer re-reduces those
+// partials in its prologue, and the clip-out count travels in ONE 64-bit atomic
+// per workgroup (count in the low 40 bits, arrival ticket above) on a word of the
+// layer state that the last workgroup resets to zero.
 #include "lbt_internal.h"
 
 namespace lbt {
@@ -16,6 +22,8 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr uint32_t kInfBits = 0x7f800000u;
+constexpr unsigned long long kTicket = 1ull << 40;
+constexpr unsigned long long kCountMask = kTicket - 1;
 
 // ---------------------------------------------------------------------------
 // Philox4x32-10 (Salmon et al., SC'11): counter-based generator, 10 rounds.
@@ -40,6 +48,13 @@ __device__ __forceinline__ Philox4 philox4x32_10(uint32_t c0, uint32_t c1, uint3
     k1 += kWeylB;
   }
   return Philox4{{c0, c1, c2, c3}};
+}
+
+// Random words of the block of 8 elements number `blk` (= flat element index / 8).
+__device__ __forceinline__ Philox4 philox_block(unsigned long long blk, unsigned long long step,
+                                                unsigned long long seed) {
+  return philox4x32_10((uint32_t)blk, (uint32_t)(blk >> 32), (uint32_t)step,
+                       (uint32_t)(step >> 32), (uint32_t)seed, (uint32_t)(seed >> 32));
 }
 
 // 16 random bits for flat element e: lane e%8 of block e/8.
@@ -84,6 +99,18 @@ __device__ __forceinline__ int code_stochastic(float v, const QConst& k, uint32_
   return min(max(r, k.kmin), k.q);
 }
 
+// MODE 0: signed nearest, 1: unsigned nearest, 2: signed nearest + count,
+//      3: signed stochastic + count   (2 and 3 are the gradient quantizer)
+template <int MODE>
+__device__ __forceinline__ int quantize_one(float v, const QConst& qc, const Philox4& rnd,
+                                            uint32_t lane, uint32_t& cnt) {
+  int k;
+  if (MODE == 3) k = code_stochastic(v, qc, r16_of(rnd, lane));
+  else k = code_nearest(v, qc);
+  if (MODE >= 2) cnt += (fabsf(v) > qc.c) ? 1u : 0u;
+  return k;
+}
+
 __device__ __forceinline__ uint32_t wave_sum(uint32_t v) {
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
@@ -96,75 +123,109 @@ __device__ __forceinline__ uint32_t wave_max(uint32_t v) {
   return v;
 }
 
-// Block-wide sum of per-thread counts, then ONE atomic per block.
-__device__ __forceinline__ void block_count_add(uint32_t cnt, unsigned long long* target) {
+// Block-wide reductions; every thread receives the result.
+__device__ __forceinline__ uint32_t block_max(uint32_t m) {
   __shared__ uint32_t part[kThreads / 64];
-  cnt = wave_sum(cnt);
-  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = cnt;
+  m = wave_max(m);
   __syncthreads();
-  if (threadIdx.x == 0) {
-    uint32_t tot = 0;
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = m;
+  __syncthreads();
+  uint32_t t = part[0];
 #pragma unroll
-    for (int i = 0; i < kThreads / 64; ++i) tot += part[i];
-    if (tot) atomicAdd(target, (unsigned long long)tot);
-  }
+  for (int i = 1; i < kThreads / 64; ++i) t = max(t, part[i]);
+  return t;
+}
+
+__device__ __forceinline__ uint32_t block_sum(uint32_t v) {
+  __shared__ uint32_t part[kThreads / 64];
+  v = wave_sum(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = v;
+  __syncthreads();
+  uint32_t t = 0;
+#pragma unroll
+  for (int i = 0; i < kThreads / 64; ++i) t += part[i];
+  return t;
+}
+
+// Maximum of column `col` of the partial maxima left by k_absmax3.
+__device__ __forceinline__ uint32_t reduce_partials(const uint32_t* pmax, int nblocks, int col) {
+  uint32_t m = 0;
+  for (int i = threadIdx.x; i < nblocks; i += kThreads) m = max(m, pmax[i * 4 + col]);
+  return block_max(m);
 }
 
 // ---------------------------------------------------------------------------
-// small one-thread kernels
+// Gradient quantizer prologue / epilogue shared by the flat and the tiled kernels
 // ---------------------------------------------------------------------------
-__global__ void k_begin(lbt_grad_state* st, OperandScalars* sc) {
-  if (st) {
-    st->gmax = 0.0f;
-    st->n_out = 0;
-    st->status = LBT_STATUS_OK;
+struct GradSetup {
+  float gmax, c;
+  int status;
+};
+
+__device__ __forceinline__ GradSetup grad_setup(const lbt_grad_state* st, const uint32_t* pmax,
+                                                int nblocks) {
+  GradSetup g;
+  const uint32_t bits = reduce_partials(pmax, nblocks, 0);
+  g.gmax = __uint_as_float(bits);
+  g.c = 0.0f;
+  if (bits >= kInfBits) g.status = LBT_STATUS_NONFINITE;
+  else if (bits == 0) g.status = LBT_STATUS_ZERO_GRAD;
+  else {
+    g.status = LBT_STATUS_OK;
+    g.c = (float)__dmul_rn(st->gamma, (double)g.gmax);
   }
-  if (sc) {
-    sc->xmax_bits = 0;
-    sc->wmax_bits = 0;
-    sc->c_x = 0.0f;
-    sc->c_w = 0.0f;
-    sc->nonfinite = 0;
+  return g;
+}
+
+// One atomic per workgroup carries the clip-out count and the arrival ticket; the
+// last workgroup to arrive publishes the statistics and clears the word.
+__device__ __forceinline__ void grad_finish(lbt_grad_state* st, const GradSetup& g, uint32_t cnt,
+                                            unsigned long long n_total) {
+  const uint32_t tot = block_sum(cnt);
+  if (threadIdx.x == 0) {
+    const unsigned long long nblk = (unsigned long long)gridDim.x * gridDim.y * gridDim.z;
+    const unsigned long long old =
+        atomicAdd(reinterpret_cast<unsigned long long*>(&st->sync_word), kTicket + tot);
+    if ((old >> 40) == nblk - 1) {
+      st->n_out = (old + tot) & kCountMask;
+      st->n_total = n_total;
+      st->gmax = g.gmax;
+      st->clip = g.c;
+      st->scale = (g.c > 0.0f) ? (float)((double)g.c / 7.0) : 0.0f;
+      st->status = g.status;
+      st->sync_word = 0;
+    }
   }
 }
 
-__global__ void k_grad_prepare(lbt_grad_state* st, unsigned long long n) {
-  const uint32_t bits = __float_as_uint(st->gmax);
-  st->n_total = n;
-  st->n_out = 0;
-  if (bits >= kInfBits) {
-    st->status = LBT_STATUS_NONFINITE;
-    st->clip = 0.0f;
-    st->scale = 0.0f;
-  } else if (bits == 0) {
-    st->status = LBT_STATUS_ZERO_GRAD;
-    st->clip = 0.0f;
-    st->scale = 0.0f;
-  } else {
-    st->status = LBT_STATUS_OK;
-    const float c = (float)__dmul_rn(st->gamma, (double)st->gmax);
-    st->clip = c;
-    st->scale = (c > 0.0f) ? (float)((double)c / 7.0) : 0.0f;
+// Operand clip value: the caller's, or the tensor maximum from the partials.
+__device__ __forceinline__ float operand_setup(float c_given, const uint32_t* pmax, int nblocks,
+                                               int col, bool is_unsigned, float* c_out,
+                                               uint32_t* bad_out, lbt_grad_state* st,
+                                               float* clip_scale_out) {
+  float c = c_given;
+  bool bad = false;
+  if (!(c > 0.0f)) {
+    const uint32_t bits = reduce_partials(pmax, nblocks, col);
+    if (bits >= kInfBits) { bad = true; c = 0.0f; }
+    else c = __uint_as_float(bits);
   }
+  if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0) {
+    if (c_out) *c_out = c;
+    if (bad_out) *bad_out = bad ? 1u : 0u;
+    if (bad && st) st->status = LBT_STATUS_NONFINITE;
+    if (clip_scale_out) {
+      clip_scale_out[0] = c;
+      clip_scale_out[1] = (c > 0.0f) ? (float)((double)c / (is_unsigned ? 15.0 : 7.0)) : 0.0f;
+    }
+  }
+  return c;
 }
 
-__global__ void k_operand_prepare(OperandScalars* sc, lbt_grad_state* st, float c_x, float c_w) {
-  uint32_t bad = 0;
-  float cx = c_x, cw = c_w;
-  if (!(cx > 0.0f)) {
-    if (sc->xmax_bits >= kInfBits) { bad = 1; cx = 0.0f; }
-    else cx = __uint_as_float(sc->xmax_bits);
-  }
-  if (!(cw > 0.0f)) {
-    if (sc->wmax_bits >= kInfBits) { bad = 1; cw = 0.0f; }
-    else cw = __uint_as_float(sc->wmax_bits);
-  }
-  sc->c_x = cx;
-  sc->c_w = cw;
-  sc->nonfinite = bad;
-  if (bad && st) st->status = LBT_STATUS_NONFINITE;
-}
-
+// ---------------------------------------------------------------------------
+// one-thread kernels
+// ---------------------------------------------------------------------------
 __global__ void k_update_interval(lbt_grad_state* st) {
   if (st->status != LBT_STATUS_OK) return;
   const double lhs = (double)st->n_out * (double)((1 << st->bits) - 1);
@@ -180,62 +241,79 @@ __global__ void k_update_interval(lbt_grad_state* st) {
 __global__ void k_state_set(lbt_grad_state* st, lbt_grad_state v) { *st = v; }
 
 // ---------------------------------------------------------------------------
-// tensor maximum: max |x| (use_abs) or max(x, 0) as an unsigned compare of the
-// fp32 bit patterns (monotone for non-negative floats; NaN/Inf sort on top).
+// tensor maxima of up to three tensors in one launch: max |x| (use_abs) or
+// max(x, 0), as unsigned compares of fp32 bit patterns (monotone for
+// non-negative floats; NaN/Inf sort on top).  Workgroup i writes its partial
+// maximum to pmax[i][tensor] and zeros to the other columns.
 // ---------------------------------------------------------------------------
+struct MaxSeg {
+  const float* p;
+  long long n;
+  int use_abs;
+  int first_block;  // first workgroup of this tensor
+};
+
 __device__ __forceinline__ uint32_t max_key(float v, int use_abs) {
   const uint32_t b = __float_as_uint(v);
   const uint32_t mag = b & 0x7fffffffu;
   if (use_abs) return mag;
-  // signed maximum clipped at 0: negatives contribute 0, but keep NaN/Inf visible
-  if (mag >= kInfBits) return mag;
-  return (b >> 31) ? 0u : b;
+  if (mag >= kInfBits) return mag;  // keep NaN/Inf visible
+  return (b >> 31) ? 0u : b;        // negatives count as 0
 }
 
-__global__ __launch_bounds__(kThreads) void k_absmax(const float* __restrict__ x, long long n,
-                                                      int use_abs, uint32_t* max_bits) {
-  const long long n4 = n / 4;
-  const float4* x4 = reinterpret_cast<const float4*>(x);
+__device__ __forceinline__ uint32_t max_key4(const float4& v, int use_abs) {
+  return max(max(max_key(v.x, use_abs), max_key(v.y, use_abs)),
+             max(max_key(v.z, use_abs), max_key(v.w, use_abs)));
+}
+
+__global__ __launch_bounds__(kThreads) void k_absmax3(MaxSeg s0, MaxSeg s1, MaxSeg s2,
+                                                       long long per_block, uint32_t* pmax) {
+  const int blk = blockIdx.x;
+  int t = 0;
+  MaxSeg s = s0;
+  if (blk >= s2.first_block) { s = s2; t = 2; }
+  else if (blk >= s1.first_block) { s = s1; t = 1; }
+  const long long start = (long long)(blk - s.first_block) * per_block;
+  const long long count = min(per_block, s.n - start);
+  const float4* p4 = reinterpret_cast<const float4*>(s.p + start);
+  const long long n4 = count / 4;
   uint32_t m = 0;
-  const long long stride = (long long)gridDim.x * kThreads;
-  for (long long i = (long long)blockIdx.x * kThreads + threadIdx.x; i < n4; i += stride) {
-    const float4 v = x4[i];
-    m = max(m, max(max(max_key(v.x, use_abs), max_key(v.y, use_abs)),
-                   max(max_key(v.z, use_abs), max_key(v.w, use_abs))));
-  }
-  if (blockIdx.x == 0 && threadIdx.x < (n - n4 * 4)) m = max(m, max_key(x[n4 * 4 + threadIdx.x], use_abs));
-  m = wave_max(m);
-  __shared__ uint32_t part[kThreads / 64];
-  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = m;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    uint32_t t = part[0];
+  long long i = threadIdx.x;
+  for (; i + 7 * kThreads < n4; i += 8 * kThreads) {
+    float4 v[8];
 #pragma unroll
-    for (int i = 1; i < kThreads / 64; ++i) t = max(t, part[i]);
-    if (t) atomicMax(max_bits, t);
+    for (int u = 0; u < 8; ++u) v[u] = p4[i + u * kThreads];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) m = max(m, max_key4(v[u], s.use_abs));
   }
+  for (; i < n4; i += kThreads) m = max(m, max_key4(p4[i], s.use_abs));
+  if ((long long)threadIdx.x < count - n4 * 4)
+    m = max(m, max_key(s.p[start + n4 * 4 + threadIdx.x], s.use_abs));
+  m = block_max(m);
+  if (threadIdx.x < 4) pmax[blk * 4 + threadIdx.x] = ((int)threadIdx.x == t) ? m : 0u;
 }
 
 // ---------------------------------------------------------------------------
-// flat quantizer: 8 consecutive elements per thread -> one 32-bit word of codes
-// MODE 0: signed nearest, 1: unsigned nearest, 2: signed nearest + count,
-//      3: signed stochastic + count
+// flat quantizer (C-ABI code format): 8 consecutive elements per thread -> one
+// 32-bit word of codes
 // ---------------------------------------------------------------------------
 template <int MODE>
 __global__ __launch_bounds__(kThreads) void k_quantize_flat(
-    const float* __restrict__ x, long long n, const float* clip_ptr, lbt_grad_state* st,
-    unsigned long long seed, uint8_t* __restrict__ codes, float* clip_scale_out) {
-  constexpr bool kUnsigned = (MODE == 1);
-  constexpr bool kCount = (MODE >= 2);
-  constexpr bool kStoch = (MODE == 3);
-  const float c = kCount ? st->clip : *clip_ptr;
-  const QConst qc = make_qconst(c, kUnsigned);
-  const bool live = c > 0.0f;
-  const unsigned long long step = kStoch ? st->step : 0ull;
-  if (!kCount && clip_scale_out && blockIdx.x == 0 && threadIdx.x == 0) {
-    clip_scale_out[0] = c;
-    clip_scale_out[1] = live ? (float)((double)c / (double)qc.q) : 0.0f;
+    const float* __restrict__ x, long long n, float c_given, const uint32_t* pmax, int nblocks,
+    lbt_grad_state* st, unsigned long long seed, uint8_t* __restrict__ codes, float* c_out,
+    float* clip_scale_out) {
+  constexpr bool kGrad = (MODE >= 2);
+  GradSetup gs{};
+  float c;
+  if (kGrad) {
+    gs = grad_setup(st, pmax, nblocks);
+    c = gs.c;
+  } else {
+    c = operand_setup(c_given, pmax, nblocks, 1, MODE == 1, c_out, nullptr, nullptr, clip_scale_out);
   }
+  const QConst qc = make_qconst(c, MODE == 1);
+  const bool live = c > 0.0f;
+  const unsigned long long step = (MODE == 3) ? st->step : 0ull;
   const long long groups = (n + 7) / 8;
   const long long stride = (long long)gridDim.x * kThreads;
   uint32_t cnt = 0;
@@ -254,18 +332,15 @@ __global__ __launch_bounds__(kThreads) void k_quantize_flat(
     }
     uint32_t word = 0;
     if (live) {
-      Philox4 rnd;
-      if (kStoch)
-        rnd = philox4x32_10((uint32_t)gi, (uint32_t)((unsigned long long)gi >> 32), (uint32_t)step,
-                            (uint32_t)(step >> 32), (uint32_t)seed, (uint32_t)(seed >> 32));
+      Philox4 rnd{};
+      if (MODE == 3) rnd = philox_block((unsigned long long)gi, step, seed);
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
-        int k;
-        if (kStoch) k = code_stochastic(v[j], qc, r16_of(rnd, j));
-        else k = code_nearest(v[j], qc);
-        if (j >= valid) k = 0;
+        uint32_t c1 = 0;
+        int k = quantize_one<MODE>(v[j], qc, rnd, j, c1);
+        if (j >= valid) { k = 0; c1 = 0; }
+        cnt += c1;
         word |= ((uint32_t)k & 0xFu) << (4 * j);
-        if (kCount) cnt += (fabsf(v[j]) > c) ? 1u : 0u;
       }
     }
     if (valid == 8) {
@@ -275,84 +350,207 @@ __global__ __launch_bounds__(kThreads) void k_quantize_flat(
       for (int j = 0; j < nbytes; ++j) codes[gi * 4 + j] = (uint8_t)(word >> (8 * j));
     }
   }
-  if (kCount) block_count_add(cnt, reinterpret_cast<unsigned long long*>(&st->n_out));
+  if (kGrad) grad_finish(st, gs, cnt, (unsigned long long)n);
 }
 
 // ---------------------------------------------------------------------------
-// quantize + re-layout: T[A][B][L] -> out_b [A][L][Bp] and/or out_a [B][L][Ap],
-// nibbles packed along the innermost axis, zero padded to Bp / Ap.
-// A workgroup quantizes a TA x TB x TL tile into LDS (one byte per code), then
-// gathers eight codes along B (or A) into each 32-bit output word.
+// quantize + re-layout of T[A][B][L] (L contiguous) into the GEMM layouts
+//   out_b [A][BG][L][16]  sixteen consecutive b per 8-byte granule (BG = Bp/16)
+//   out_a [B][AG][L][16]  sixteen consecutive a per 8-byte granule (AG = Ap/16)
+// zero padded in the last granule.  A workgroup owns a 16(a) x 16(b) x TL(l)
+// tile: it quantizes into LDS (one byte per code, [a][b][l]), then each thread
+// gathers the sixteen codes of one granule and stores 8 bytes; consecutive
+// threads store consecutive l, so the stores are contiguous.
 // ---------------------------------------------------------------------------
-template <int TA, int TB, int TL, int MODE>
-__global__ __launch_bounds__(kThreads) void k_quantize_relayout(
-    const float* __restrict__ x, int A, int B, int L, int Ap, int Bp, const float* clip_ptr,
-    lbt_grad_state* st, unsigned long long seed, uint32_t* __restrict__ out_b,
-    uint32_t* __restrict__ out_a) {
-  constexpr bool kUnsigned = (MODE == 1);
-  constexpr bool kCount = (MODE >= 2);
-  constexpr bool kStoch = (MODE == 3);
-  constexpr int TLP = TL + 1;  // odd byte pitch spreads the strided gathers over banks
-  __shared__ uint8_t tile[TA * TB * TLP];
+struct TileArgs {
+  const float* x;
+  int A, B, L;
+  int AG, BG;
+  float c_given;
+  const uint32_t* pmax;
+  int nblocks;
+  int pmax_col;
+  lbt_grad_state* st;
+  unsigned long long seed;
+  float* c_out;
+  uint32_t* bad_out;
+  uint2* out_b;
+  uint2* out_a;
+  // optional side job: clear an int32 buffer (the split-K accumulators of dW)
+  int32_t* zero_ptr;
+  long long zero_n;
+};
 
-  const float c = kCount ? st->clip : *clip_ptr;
-  const QConst qc = make_qconst(c, kUnsigned);
+__device__ __forceinline__ void side_zero(const TileArgs& t) {
+  if (!t.zero_ptr) return;
+  const long long nblk = (long long)gridDim.x * gridDim.y * gridDim.z;
+  const long long bid = ((long long)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;
+  for (long long i = bid * kThreads + threadIdx.x; i < t.zero_n; i += nblk * kThreads)
+    t.zero_ptr[i] = 0;
+}
+
+// Phase B: gather granules out of the LDS tile.  `pitch` = bytes per (a,b) row.
+__device__ __forceinline__ void store_granules(const TileArgs& t, const uint8_t* tile, int pitch,
+                                               int tl, int a0, int b0, int l0) {
+  const int n_items = 16 * tl;
+  if (t.out_b) {
+    const int bg = b0 >> 4;
+    for (int it = threadIdx.x; it < n_items; it += kThreads) {
+      const int a = it / tl, l = it - a * tl;
+      if (a0 + a >= t.A || l0 + l >= t.L) continue;
+      uint32_t w0 = 0, w1 = 0;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        w0 |= (uint32_t)tile[(a * 16 + j) * pitch + l] << (4 * j);
+        w1 |= (uint32_t)tile[(a * 16 + 8 + j) * pitch + l] << (4 * j);
+      }
+      t.out_b[((long long)(a0 + a) * t.BG + bg) * t.L + l0 + l] = make_uint2(w0, w1);
+    }
+  }
+  if (t.out_a) {
+    const int ag = a0 >> 4;
+    for (int it = threadIdx.x; it < n_items; it += kThreads) {
+      const int b = it / tl, l = it - b * tl;
+      if (b0 + b >= t.B || l0 + l >= t.L) continue;
+      uint32_t w0 = 0, w1 = 0;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        w0 |= (uint32_t)tile[(j * 16 + b) * pitch + l] << (4 * j);
+        w1 |= (uint32_t)tile[((8 + j) * 16 + b) * pitch + l] << (4 * j);
+      }
+      t.out_a[((long long)(b0 + b) * t.AG + ag) * t.L + l0 + l] = make_uint2(w0, w1);
+    }
+  }
+}
+
+template <int MODE>
+__device__ __forceinline__ float tile_prologue(const TileArgs& t, GradSetup& gs) {
+  if (MODE >= 2) {
+    gs = grad_setup(t.st, t.pmax, t.nblocks);
+    return gs.c;
+  }
+  return operand_setup(t.c_given, t.pmax, t.nblocks, t.pmax_col, MODE == 1, t.c_out, t.bad_out,
+                       t.st, nullptr);
+}
+
+// Large L (L % 8 == 0): tile 16 x 16 x 64, one 8-element group (two float4) per item.
+template <int MODE>
+__global__ __launch_bounds__(kThreads) void k_quantize_tile(const TileArgs t) {
+  constexpr int TL = 64, PITCH = TL + 8;
+  __shared__ __attribute__((aligned(8))) uint8_t tile[256 * PITCH];
+  GradSetup gs{};
+  const float c = tile_prologue<MODE>(t, gs);
+  const QConst qc = make_qconst(c, MODE == 1);
   const bool live = c > 0.0f;
-  const unsigned long long step = kStoch ? st->step : 0ull;
-  const int l0 = blockIdx.x * TL, b0 = blockIdx.y * TB, a0 = blockIdx.z * TA;
+  const unsigned long long step = (MODE == 3) ? t.st->step : 0ull;
+  const int l0 = blockIdx.x * TL, b0 = blockIdx.y * 16, a0 = blockIdx.z * 16;
+  side_zero(t);
 
   uint32_t cnt = 0;
-  for (int idx = threadIdx.x; idx < TA * TB * TL; idx += kThreads) {
-    const int l = idx % TL, b = (idx / TL) % TB, a = idx / (TL * TB);
-    const int ga = a0 + a, gb = b0 + b, gl = l0 + l;
-    int k = 0;
-    if (ga < A && gb < B && gl < L) {
-      const long long e = ((long long)ga * B + gb) * L + gl;
-      const float v = x[e];
-      if (live) {
-        if (kStoch) {
-          const unsigned long long blk = (unsigned long long)e >> 3;
-          const Philox4 rnd = philox4x32_10((uint32_t)blk, (uint32_t)(blk >> 32), (uint32_t)step,
-                                            (uint32_t)(step >> 32), (uint32_t)seed,
-                                            (uint32_t)(seed >> 32));
-          k = code_stochastic(v, qc, r16_of(rnd, (uint32_t)e & 7u));
-        } else {
-          k = code_nearest(v, qc);
-        }
-        if (kCount) cnt += (fabsf(v) > c) ? 1u : 0u;
-      }
+  const int oct = threadIdx.x & 7;
+  const int gl = l0 + oct * 8;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int row = (threadIdx.x >> 3) + 32 * i;  // row = a * 16 + b
+    const int ga = a0 + (row >> 4), gb = b0 + (row & 15);
+    uint32_t w0 = 0, w1 = 0;
+    if (live && ga < t.A && gb < t.B && gl < t.L) {
+      const long long e0 = ((long long)ga * t.B + gb) * t.L + gl;
+      const float4 p = *reinterpret_cast<const float4*>(t.x + e0);
+      const float4 q = *reinterpret_cast<const float4*>(t.x + e0 + 4);
+      Philox4 rnd{};
+      if (MODE == 3) rnd = philox_block((unsigned long long)e0 >> 3, step, t.seed);
+      w0 = ((uint32_t)quantize_one<MODE>(p.x, qc, rnd, 0, cnt) & 0xFu) |
+           (((uint32_t)quantize_one<MODE>(p.y, qc, rnd, 1, cnt) & 0xFu) << 8) |
+           (((uint32_t)quantize_one<MODE>(p.z, qc, rnd, 2, cnt) & 0xFu) << 16) |
+           (((uint32_t)quantize_one<MODE>(p.w, qc, rnd, 3, cnt) & 0xFu) << 24);
+      w1 = ((uint32_t)quantize_one<MODE>(q.x, qc, rnd, 4, cnt) & 0xFu) |
+           (((uint32_t)quantize_one<MODE>(q.y, qc, rnd, 5, cnt) & 0xFu) << 8) |
+           (((uint32_t)quantize_one<MODE>(q.z, qc, rnd, 6, cnt) & 0xFu) << 16) |
+           (((uint32_t)quantize_one<MODE>(q.w, qc, rnd, 7, cnt) & 0xFu) << 24);
     }
-    tile[(a * TB + b) * TLP + l] = (uint8_t)(k & 0xF);
+    *reinterpret_cast<uint2*>(tile + row * PITCH + oct * 8) = make_uint2(w0, w1);
   }
   __syncthreads();
+  store_granules(t, tile, PITCH, TL, a0, b0, l0);
+  if (MODE >= 2) grad_finish(t.st, gs, cnt, (unsigned long long)t.A * t.B * t.L);
+}
 
-  if (out_b) {
-    constexpr int GB = TB / 8;
-    for (int idx = threadIdx.x; idx < TA * TL * GB; idx += kThreads) {
-      const int bg = idx % GB, l = (idx / GB) % TL, a = idx / (GB * TL);
-      const int ga = a0 + a, gl = l0 + l, gb = b0 + 8 * bg;
-      if (ga < A && gl < L && gb < Bp) {
-        uint32_t word = 0;
+// Small L with B % 16 == 0 and (B*L) % 8 == 0: tile 16 x 16 x L.  For one a the
+// sixteen rows b0..b0+15 are contiguous in memory (16*L floats, a multiple of 8
+// elements that starts on a multiple of 8), so they are read as 8-element groups
+// that may straddle rows.
+template <int MODE>
+__global__ __launch_bounds__(kThreads) void k_quantize_tile_small(const TileArgs t, int pitch) {
+  extern __shared__ __attribute__((aligned(8))) uint8_t dyn_tile[];
+  GradSetup gs{};
+  const float c = tile_prologue<MODE>(t, gs);
+  const QConst qc = make_qconst(c, MODE == 1);
+  const bool live = c > 0.0f;
+  const unsigned long long step = (MODE == 3) ? t.st->step : 0ull;
+  const int b0 = blockIdx.y * 16, a0 = blockIdx.z * 16;
+  side_zero(t);
+
+  uint32_t cnt = 0;
+  const int L = t.L;
+  const int octs = 2 * L;  // 16 * L / 8 groups per a
+  for (int it = threadIdx.x; it < 16 * octs; it += kThreads) {
+    const int a = it / octs, j = it - a * octs;
+    const int ga = a0 + a;
+    int b = (8 * j) / L, l = 8 * j - b * L;
+    float v[8];
+    Philox4 rnd{};
+    const bool have = live && ga < t.A;
+    if (have) {
+      const long long e0 = ((long long)ga * t.B + b0) * L + 8 * j;
+      const float4 p = *reinterpret_cast<const float4*>(t.x + e0);
+      const float4 q = *reinterpret_cast<const float4*>(t.x + e0 + 4);
+      v[0] = p.x; v[1] = p.y; v[2] = p.z; v[3] = p.w;
+      v[4] = q.x; v[5] = q.y; v[6] = q.z; v[7] = q.w;
+      if (MODE == 3) rnd = philox_block((unsigned long long)e0 >> 3, step, t.seed);
+    }
 #pragma unroll
-        for (int j = 0; j < 8; ++j) word |= (uint32_t)tile[(a * TB + 8 * bg + j) * TLP + l] << (4 * j);
-        out_b[(((long long)ga * L + gl) * Bp + gb) >> 3] = word;
-      }
+    for (int u = 0; u < 8; ++u) {
+      int k = 0;
+      if (have) k = quantize_one<MODE>(v[u], qc, rnd, u, cnt);
+      dyn_tile[(a * 16 + b) * pitch + l] = (uint8_t)(k & 0xF);
+      if (++l == L) { l = 0; ++b; }
     }
   }
-  if (out_a) {
-    constexpr int GA = TA / 8;
-    for (int idx = threadIdx.x; idx < TB * TL * GA; idx += kThreads) {
-      const int ag = idx % GA, l = (idx / GA) % TL, b = idx / (GA * TL);
-      const int gb = b0 + b, gl = l0 + l, ga = a0 + 8 * ag;
-      if (gb < B && gl < L && ga < Ap) {
-        uint32_t word = 0;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) word |= (uint32_t)tile[((8 * ag + j) * TB + b) * TLP + l] << (4 * j);
-        out_a[(((long long)gb * L + gl) * Ap + ga) >> 3] = word;
-      }
+  __syncthreads();
+  store_granules(t, dyn_tile, pitch, L, a0, b0, 0);
+  if (MODE >= 2) grad_finish(t.st, gs, cnt, (unsigned long long)t.A * t.B * t.L);
+}
+
+// Any shape: tile 16 x 16 x 32 with one scalar load per element.
+template <int MODE>
+__global__ __launch_bounds__(kThreads) void k_quantize_tile_generic(const TileArgs t) {
+  constexpr int TL = 32, PITCH = TL + 4;
+  __shared__ __attribute__((aligned(8))) uint8_t tile[256 * PITCH];
+  GradSetup gs{};
+  const float c = tile_prologue<MODE>(t, gs);
+  const QConst qc = make_qconst(c, MODE == 1);
+  const bool live = c > 0.0f;
+  const unsigned long long step = (MODE == 3) ? t.st->step : 0ull;
+  const int l0 = blockIdx.x * TL, b0 = blockIdx.y * 16, a0 = blockIdx.z * 16;
+  side_zero(t);
+
+  uint32_t cnt = 0;
+  for (int idx = threadIdx.x; idx < 256 * TL; idx += kThreads) {
+    const int l = idx % TL, row = idx / TL;
+    const int ga = a0 + (row >> 4), gb = b0 + (row & 15), gl = l0 + l;
+    int k = 0;
+    if (live && ga < t.A && gb < t.B && gl < t.L) {
+      const long long e = ((long long)ga * t.B + gb) * t.L + gl;
+      Philox4 rnd{};
+      if (MODE == 3) rnd = philox_block((unsigned long long)e >> 3, step, t.seed);
+      k = quantize_one<MODE>(t.x[e], qc, rnd, (uint32_t)e & 7u, cnt);
     }
+    tile[row * PITCH + l] = (uint8_t)(k & 0xF);
   }
-  if (kCount) block_count_add(cnt, reinterpret_cast<unsigned long long*>(&st->n_out));
+  __syncthreads();
+  store_granules(t, tile, PITCH, TL, a0, b0, l0);
+  if (MODE >= 2) grad_finish(t.st, gs, cnt, (unsigned long long)t.A * t.B * t.L);
 }
 
 inline int flat_grid(long long work_items) {
@@ -364,107 +562,121 @@ inline int flat_grid(long long work_items) {
 }
 
 template <int MODE>
-int relayout_dispatch(const float* x, int64_t A, int64_t B, int64_t L, const float* clip_ptr,
-                      lbt_grad_state* st, uint64_t seed, uint8_t* out_b, uint8_t* out_a,
-                      hipStream_t s) {
-  const int Ap = (int)round_up(A, kGranule), Bp = (int)round_up(B, kGranule);
-  auto ob = reinterpret_cast<uint32_t*>(out_b);
-  auto oa = reinterpret_cast<uint32_t*>(out_a);
-#define LBT_RELAYOUT(TA, TB, TL)                                                              \
-  do {                                                                                        \
-    dim3 grid((unsigned)((L + TL - 1) / TL), (unsigned)((Bp + TB - 1) / TB),                  \
-              (unsigned)((Ap + TA - 1) / TA));                                                \
-    if (grid.y > 65535u || grid.z > 65535u) return LBT_ERR_UNSUPPORTED;                       \
-    hipLaunchKernelGGL((k_quantize_relayout<TA, TB, TL, MODE>), grid, dim3(kThreads), 0, s, x, \
-                       (int)A, (int)B, (int)L, Ap, Bp, clip_ptr, st, seed, ob, oa);           \
-  } while (0)
-  if (L == 1) {
-    LBT_RELAYOUT(64, 64, 1);
-  } else if (!out_b) {
-    LBT_RELAYOUT(64, 16, 32);
+int tile_dispatch(TileArgs t, hipStream_t s) {
+  const int AG = t.AG, BG = t.BG;
+  if (AG > 65535 || BG > 65535) return LBT_ERR_UNSUPPORTED;
+  const bool aligned16 = (reinterpret_cast<uintptr_t>(t.x) % 16) == 0;
+  const long long BL = (long long)t.B * t.L;
+  if (aligned16 && t.L >= 64 && t.L % 8 == 0) {
+    dim3 grid((unsigned)((t.L + 63) / 64), (unsigned)BG, (unsigned)AG);
+    hipLaunchKernelGGL(k_quantize_tile<MODE>, grid, dim3(kThreads), 0, s, t);
+  } else if (aligned16 && t.L > 1 && t.L <= 248 && t.B % 16 == 0 && BL % 8 == 0) {
+    const int pitch = (t.L + 3) / 4 * 4 + 4;
+    dim3 grid(1, (unsigned)BG, (unsigned)AG);
+    hipLaunchKernelGGL(k_quantize_tile_small<MODE>, grid, dim3(kThreads), (size_t)256 * pitch, s, t,
+                       pitch);
   } else {
-    LBT_RELAYOUT(32, 32, 32);
+    dim3 grid((unsigned)((t.L + 31) / 32), (unsigned)BG, (unsigned)AG);
+    hipLaunchKernelGGL(k_quantize_tile_generic<MODE>, grid, dim3(kThreads), 0, s, t);
   }
-#undef LBT_RELAYOUT
   LBT_LAUNCH_CHECK();
   return LBT_OK;
 }
 
 }  // namespace
 
-int launch_begin(lbt_grad_state* st, OperandScalars* sc, hipStream_t s) {
-  ProfScope prof(KID_BEGIN, 0.0, s);
-  hipLaunchKernelGGL(k_begin, dim3(1), dim3(1), 0, s, st, sc);
+int launch_absmax3(const float* p0, int64_t n0, int abs0, const float* p1, int64_t n1, int abs1,
+                   const float* p2, int64_t n2, int abs2, uint32_t* pmax, int* nblocks_out,
+                   hipStream_t s) {
+  if (!p0) n0 = 0;
+  if (!p1) n1 = 0;
+  if (!p2) n2 = 0;
+  ProfScope prof(KID_ABSMAX, (double)(n0 + n1 + n2), s);
+  const long long total = n0 + n1 + n2;
+  long long per = (total + (kMaxPartialBlocks - 4) - 1) / (kMaxPartialBlocks - 4);
+  per = (per + 8191) / 8192 * 8192;  // 256 threads x 8 float4
+  if (per < 8192) per = 8192;
+  const long long nb0 = (n0 + per - 1) / per, nb1 = (n1 + per - 1) / per, nb2 = (n2 + per - 1) / per;
+  const long long nb = nb0 + nb1 + nb2;
+  *nblocks_out = (int)nb;
+  if (nb == 0) return LBT_OK;
+  if (nb > kMaxPartialBlocks) return LBT_ERR_UNSUPPORTED;
+  MaxSeg s0{p0, n0, abs0, 0}, s1{p1, n1, abs1, (int)nb0}, s2{p2, n2, abs2, (int)(nb0 + nb1)};
+  hipLaunchKernelGGL(k_absmax3, dim3((unsigned)nb), dim3(kThreads), 0, s, s0, s1, s2, per, pmax);
   LBT_LAUNCH_CHECK();
   return LBT_OK;
 }
 
-int launch_absmax(const float* x, int64_t n, int use_abs, uint32_t* max_bits, hipStream_t s) {
-  ProfScope prof(KID_ABSMAX, (double)n, s);
-  hipLaunchKernelGGL(k_absmax, dim3(flat_grid((n / 4 + 3) / 4)), dim3(kThreads), 0, s, x,
-                     (long long)n, use_abs, max_bits);
-  LBT_LAUNCH_CHECK();
-  return LBT_OK;
-}
-
-int launch_grad_prepare(lbt_grad_state* st, int64_t n, hipStream_t s) {
-  ProfScope prof(KID_GRAD_PREPARE, 0.0, s);
-  hipLaunchKernelGGL(k_grad_prepare, dim3(1), dim3(1), 0, s, st, (unsigned long long)n);
-  LBT_LAUNCH_CHECK();
-  return LBT_OK;
-}
-
-int launch_operand_prepare(OperandScalars* sc, lbt_grad_state* st, float c_x, float c_w,
-                           hipStream_t s) {
-  ProfScope prof(KID_OPERAND_PREPARE, 0.0, s);
-  hipLaunchKernelGGL(k_operand_prepare, dim3(1), dim3(1), 0, s, sc, st, c_x, c_w);
-  LBT_LAUNCH_CHECK();
-  return LBT_OK;
-}
-
-int launch_quantize_flat_grad(const float* g, int64_t n, lbt_grad_state* st, uint64_t seed,
-                              int rounding, uint8_t* codes, hipStream_t s) {
+int launch_quantize_flat_grad(const float* g, int64_t n, const uint32_t* pmax, int nblocks,
+                              lbt_grad_state* st, uint64_t seed, int rounding, uint8_t* codes,
+                              hipStream_t s) {
   ProfScope prof(KID_FLAT_GRAD, (double)n, s);
   const int grid = flat_grid((n + 7) / 8);
   if (rounding == LBT_ROUND_STOCHASTIC)
-    hipLaunchKernelGGL(k_quantize_flat<3>, dim3(grid), dim3(kThreads), 0, s, g, (long long)n,
-                       (const float*)nullptr, st, (unsigned long long)seed, codes, (float*)nullptr);
+    hipLaunchKernelGGL(k_quantize_flat<3>, dim3(grid), dim3(kThreads), 0, s, g, (long long)n, 0.0f,
+                       pmax, nblocks, st, (unsigned long long)seed, codes, (float*)nullptr,
+                       (float*)nullptr);
   else
-    hipLaunchKernelGGL(k_quantize_flat<2>, dim3(grid), dim3(kThreads), 0, s, g, (long long)n,
-                       (const float*)nullptr, st, (unsigned long long)seed, codes, (float*)nullptr);
+    hipLaunchKernelGGL(k_quantize_flat<2>, dim3(grid), dim3(kThreads), 0, s, g, (long long)n, 0.0f,
+                       pmax, nblocks, st, (unsigned long long)seed, codes, (float*)nullptr,
+                       (float*)nullptr);
   LBT_LAUNCH_CHECK();
   return LBT_OK;
 }
 
-int launch_quantize_flat_operand(const float* x, int64_t n, const float* clip_ptr, int is_unsigned,
-                                 uint8_t* codes, float* clip_scale_out, hipStream_t s) {
+int launch_quantize_flat_operand(const float* x, int64_t n, float c_given, const uint32_t* pmax,
+                                 int nblocks, int is_unsigned, uint8_t* codes, float* c_out,
+                                 float* clip_scale_out, hipStream_t s) {
   ProfScope prof(KID_FLAT_OPERAND, (double)n, s);
   const int grid = flat_grid((n + 7) / 8);
   if (is_unsigned)
     hipLaunchKernelGGL(k_quantize_flat<1>, dim3(grid), dim3(kThreads), 0, s, x, (long long)n,
-                       clip_ptr, (lbt_grad_state*)nullptr, 0ull, codes, clip_scale_out);
+                       c_given, pmax, nblocks, (lbt_grad_state*)nullptr, 0ull, codes, c_out,
+                       clip_scale_out);
   else
     hipLaunchKernelGGL(k_quantize_flat<0>, dim3(grid), dim3(kThreads), 0, s, x, (long long)n,
-                       clip_ptr, (lbt_grad_state*)nullptr, 0ull, codes, clip_scale_out);
+                       c_given, pmax, nblocks, (lbt_grad_state*)nullptr, 0ull, codes, c_out,
+                       clip_scale_out);
   LBT_LAUNCH_CHECK();
   return LBT_OK;
 }
 
 int launch_quantize_relayout_grad(const float* g, int64_t A, int64_t B, int64_t L,
-                                  lbt_grad_state* st, uint64_t seed, int rounding, uint8_t* out_b,
-                                  uint8_t* out_a, hipStream_t s) {
+                                  const uint32_t* pmax, int nblocks, lbt_grad_state* st,
+                                  uint64_t seed, int rounding, uint8_t* out_b, uint8_t* out_a,
+                                  hipStream_t s) {
   ProfScope prof(KID_RELAYOUT_GRAD, (double)A * (double)B * (double)L, s);
-  if (rounding == LBT_ROUND_STOCHASTIC)
-    return relayout_dispatch<3>(g, A, B, L, nullptr, st, seed, out_b, out_a, s);
-  return relayout_dispatch<2>(g, A, B, L, nullptr, st, seed, out_b, out_a, s);
+  TileArgs t{};
+  t.x = g; t.A = (int)A; t.B = (int)B; t.L = (int)L;
+  t.AG = (int)(round_up(A, kGranule) / kGranule);
+  t.BG = (int)(round_up(B, kGranule) / kGranule);
+  t.pmax = pmax; t.nblocks = nblocks; t.pmax_col = 0;
+  t.st = st; t.seed = seed;
+  t.out_b = reinterpret_cast<uint2*>(out_b);
+  t.out_a = reinterpret_cast<uint2*>(out_a);
+  if (rounding == LBT_ROUND_STOCHASTIC) return tile_dispatch<3>(t, s);
+  return tile_dispatch<2>(t, s);
 }
 
-int launch_quantize_relayout_operand(const float* x, int64_t A, int64_t B, int64_t L,
-                                     const float* clip_ptr, int is_unsigned, uint8_t* out_b,
-                                     uint8_t* out_a, hipStream_t s) {
+int launch_quantize_relayout_operand(const float* x, int64_t A, int64_t B, int64_t L, float c_given,
+                                     const uint32_t* pmax, int nblocks, int pmax_col,
+                                     int is_unsigned, float* c_out, uint32_t* bad_out,
+                                     lbt_grad_state* st, uint8_t* out_b, uint8_t* out_a,
+                                     int32_t* zero_ptr, int64_t zero_n, hipStream_t s) {
   ProfScope prof(KID_RELAYOUT_OPERAND, (double)A * (double)B * (double)L, s);
-  if (is_unsigned) return relayout_dispatch<1>(x, A, B, L, clip_ptr, nullptr, 0, out_b, out_a, s);
-  return relayout_dispatch<0>(x, A, B, L, clip_ptr, nullptr, 0, out_b, out_a, s);
+  TileArgs t{};
+  t.x = x; t.A = (int)A; t.B = (int)B; t.L = (int)L;
+  t.AG = (int)(round_up(A, kGranule) / kGranule);
+  t.BG = (int)(round_up(B, kGranule) / kGranule);
+  t.c_given = c_given;
+  t.pmax = pmax; t.nblocks = nblocks; t.pmax_col = pmax_col;
+  t.st = st;
+  t.c_out = c_out; t.bad_out = bad_out;
+  t.out_b = reinterpret_cast<uint2*>(out_b);
+  t.out_a = reinterpret_cast<uint2*>(out_a);
+  t.zero_ptr = zero_ptr; t.zero_n = zero_n;
+  if (is_unsigned) return tile_dispatch<1>(t, s);
+  return tile_dispatch<0>(t, s);
 }
 
 int launch_update_interval(lbt_grad_state* st, hipStream_t s) {

@@ -41,7 +41,7 @@ def test_binding_declares_every_symbol():
 def test_state_struct_size(lib):
     from paper_2407_12637_amd import binding
     assert lib.lbt_state_sizeof() == C.sizeof(binding.GradState) == 96
-    assert binding.GradState.gmax.offset == 72 and binding.GradState.step.offset == 48
+    assert binding.GradState.gmax.offset == 80 and binding.GradState.step.offset == 48
 
 
 def test_strerror_and_version(lib):
@@ -57,10 +57,12 @@ def test_host_validation_rejects_without_gpu(lib):
     assert lib.lbt_state_init(C.c_void_p(256), 1.0, 1e-3, 1e-3, 1e-3, 1.0, 5, None) == -3
     assert lib.lbt_state_init(C.c_void_p(256), 2.0, 1e-3, 1e-3, 1e-3, 1.0, 4, None) == -2
     p = C.c_void_p(4096)
-    assert lib.lbt_quantize_grad(p, 0, p, 0, 0, p, p, 256, None) == -2          # n <= 0
-    assert lib.lbt_quantize_grad(p, 8, p, 0, 7, p, p, 256, None) == -3          # rounding mode
-    assert lib.lbt_quantize_grad(C.c_void_p(4100), 8, p, 0, 0, p, p, 256, None) == -7
+    big = 1 << 20
+    assert lib.lbt_quantize_grad(p, 0, p, 0, 0, p, p, big, None) == -2          # n <= 0
+    assert lib.lbt_quantize_grad(p, 8, p, 0, 7, p, p, big, None) == -3          # rounding mode
+    assert lib.lbt_quantize_grad(C.c_void_p(4100), 8, p, 0, 0, p, p, big, None) == -7
     assert lib.lbt_quantize_grad(p, 8, p, 0, 0, p, p, 16, None) == -4           # workspace
+    assert lib.lbt_workspace_bytes_quantize(8) == 256 + 2048 * 16
     # conv shape checks
     assert lib.lbt_workspace_bytes_conv2d(1, 1, 2, 2, 1, 3, 3, 1, 0) == 0       # kernel > image
     need = lib.lbt_workspace_bytes_conv2d(4, 16, 12, 12, 32, 3, 3, 1, 1)
@@ -75,10 +77,13 @@ def test_host_validation_rejects_without_gpu(lib):
 
 
 def test_workspace_formula(lib):
-    # scalars + four code tensors, each padded to 256 bytes
+    # header + four code tensors + split-K partial tiles, each padded to 256 bytes
     N, Cc, H, W, K, R, S, st, pad = 64, 256, 14, 14, 256, 3, 3, 1, 1
     P = Q = 14
     pad256 = lambda b: (b + 255) // 256 * 256
-    want = 256 + pad256(N * P * Q * K // 2) + pad256(K * P * Q * N // 2) \
+    want = 256 + 2048 * 16 + pad256(N * P * Q * K // 2) + pad256(K * P * Q * N // 2) \
         + pad256(Cc * H * W * N // 2) + pad256(Cc * R * S * K // 2)
-    assert lib.lbt_workspace_bytes_conv2d(N, Cc, H, W, K, R, S, st, pad) == want
+    got = lib.lbt_workspace_bytes_conv2d(N, Cc, H, W, K, R, S, st, pad)
+    partial = got - want
+    # dW is [256][2304] int32; the contraction is cut into at most 512/36 slices
+    assert partial % (K * Cc * R * S * 4) == 0 and 2 <= partial // (K * Cc * R * S * 4) <= 14
