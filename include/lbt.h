@@ -46,7 +46,7 @@ extern "C" {
 #define LBT_STATUS_ZERO_GRAD 2   /* max|dY| == 0: codes 0, scale 0, gamma not updated   */
 
 #define LBT_ROUND_NEAREST 0      /* round half to even                              */
-#define LBT_ROUND_STOCHASTIC 1   /* floor(x_n + u), u from Philox4x32-10            */
+#define LBT_ROUND_STOCHASTIC 1   /* (floor(x_n*2^16) + r16) >> 16, r16 from Philox  */
 
 /*
  * Per-layer state of the gradient quantizer: the scalars of Alg. 1 plus the
@@ -103,6 +103,7 @@ int lbt_update_interval(lbt_grad_state* st, void* stream);
  *   (code -8 never occurs); a trailing pad nibble is 0.
  * Computes g_max, c_g = gamma * g_max, the codes, and N(G_out); writes gmax,
  * clip, scale, n_total, n_out, status to *st.  Does not change gamma or step.
+ * The code is decided in fp32: x_n = clip(g) * fl32(7 / c_g), one multiply.
  * rounding = LBT_ROUND_STOCHASTIC draws 16 bits per element from
  * Philox4x32-10 with key = seed and counter = (element/8, st->step); element
  * e uses 16-bit lane e%8 of the four output words, low half first.

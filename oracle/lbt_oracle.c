@@ -22,12 +22,17 @@
  * Readings taken where the paper is silent (kept identical in the GPU path
  * by independent code):
  *   - the clip value is held in fp32: c = (float)(gamma * (double)g_max);
- *   - normalisation is ONE double multiply by inv_s = q / c, no fused
- *     multiply-add (build with -ffp-contract=off);
+ *   - the integer code is decided in fp32, the precision of the tensors the
+ *     paper quantizes (Sec. 1: full-precision gradients are 32-bit floats):
+ *     normalisation x_n = clip(x,c)/s is ONE fp32 multiply by
+ *     inv_s = (float)(q / c), no fused multiply-add (-ffp-contract=off);
+ *     scales, denormalisation and every diagnostic stay in double;
  *   - the rounding bracket of Eq. (4) is round-half-to-even;
  *   - stochastic rounding (Sec. 4.1 says it is used for gradients, without a
- *     generator) is floor(t + u), u = r16 / 65536, r16 from Philox4x32-10
- *     (Salmon et al., SC'11) keyed by the seed and indexed by (element, step);
+ *     generator) keeps 16 fractional bits: code = floor((floor(x_n * 2^16) +
+ *     r16) / 2^16), i.e. x_n rounds up with probability floor(frac * 2^16) /
+ *     2^16; r16 are 16 bits from Philox4x32-10 (Salmon et al., SC'11) keyed by
+ *     the seed and indexed by (element, step);
  *   - G_out is counted over the whole tensor: |g| > c, strictly;
  *   - sign(0) = 0; gamma is clamped to [gamma_min, gamma_max].
  *
@@ -150,7 +155,7 @@ void orc_quantize(const float* x, int64_t n, float c, int bits, int is_unsigned,
     return;
   }
   const int q = orc_levels(bits, is_unsigned);
-  const double inv_s = (double)q / (double)c;
+  const float inv_s = (float)((double)q / (double)c);
   const float lo = is_unsigned ? 0.0f : -c;
 #pragma omp parallel for reduction(+ : cnt) schedule(static)
   for (int64_t i = 0; i < n; ++i) {
@@ -159,17 +164,21 @@ void orc_quantize(const float* x, int64_t n, float c, int bits, int is_unsigned,
     float xc = v;
     if (xc < lo) xc = lo;
     if (xc > c) xc = c;
-    /* x_n = clip(x, c) / s, as one double multiply by q / c */
-    double t = (double)xc * inv_s;
-    double r;
+    /* x_n = clip(x, c) / s, as one fp32 multiply by q / c */
+    float t = xc * inv_s;
+    int32_t k;
     if (rounding == 0) {
-      r = rint(t); /* default rounding mode: ties to even */
+      k = (int32_t)rintf(t); /* default rounding mode: ties to even */
     } else {
-      double u = (double)r16_for_element((uint64_t)i, seed, step) * (1.0 / 65536.0);
-      r = floor(t + u);
+      /* x_n in units of 2^-16 (the scaling is exact), truncated downwards */
+      int64_t fixed = (int64_t)floorf(t * 65536.0f);
+      fixed += (int64_t)r16_for_element((uint64_t)i, seed, step);
+      /* floor division by 2^16 */
+      int64_t d = fixed / 65536;
+      if (fixed % 65536 < 0) d -= 1;
+      k = (int32_t)d;
     }
-    int32_t k = (int32_t)r;
-    /* t can exceed q by one ulp of double; keep the code in range */
+    /* t can exceed q by one ulp; keep the code in range */
     int32_t kmin = is_unsigned ? 0 : -q;
     if (k > q) k = q;
     if (k < kmin) k = kmin;

@@ -5,9 +5,9 @@
 //
 // Arithmetic contract (decides integer codes, so it is fixed to the last bit):
 //   c      = (float)(gamma * (double)g_max)
-//   inv_s  = (double)q / (double)c,  q = 7 (signed) or 15 (unsigned)
-//   t      = (double)clip(x) * inv_s          -- one double multiply, no FMA
-//   code   = rint(t)  |  floor(t + r16 / 65536)
+//   inv_s  = (float)((double)q / (double)c),  q = 7 (signed) or 15 (unsigned)
+//   t      = clip(x) * inv_s                  -- one fp32 multiply, no FMA
+//   code   = rint(t)  |  (floor(t * 2^16) + r16) >> 16   (16 fractional bits)
 //   code   = clamp(code, -q or 0, q)
 //
 // Synchronisation between kernels uses no zero-initialised scratch: the maximum
@@ -68,7 +68,7 @@ __device__ __forceinline__ uint32_t r16_of(const Philox4& p, uint32_t lane) {
 struct QConst {
   float c;       // clip value; <= 0 means "all codes zero"
   float lo;      // lower clip bound: -c or 0
-  double inv_s;  // q / c
+  float inv_s;   // q / c
   int q;         // largest code
   int kmin;      // smallest code
 };
@@ -79,23 +79,24 @@ __device__ __forceinline__ QConst make_qconst(float c, bool is_unsigned) {
   k.q = is_unsigned ? 15 : 7;
   k.kmin = is_unsigned ? 0 : -7;
   k.lo = is_unsigned ? 0.0f : -c;
-  k.inv_s = (c > 0.0f) ? (double)k.q / (double)c : 0.0;
+  k.inv_s = (c > 0.0f) ? (float)((double)k.q / (double)c) : 0.0f;
   return k;
 }
 
-__device__ __forceinline__ double normalised(float v, const QConst& k) {
+__device__ __forceinline__ float normalised(float v, const QConst& k) {
   const float xc = fminf(fmaxf(v, k.lo), k.c);
-  return __dmul_rn((double)xc, k.inv_s);
+  return __fmul_rn(xc, k.inv_s);
 }
 
 __device__ __forceinline__ int code_nearest(float v, const QConst& k) {
-  const int r = (int)rint(normalised(v, k));
+  const int r = (int)rintf(normalised(v, k));
   return min(max(r, k.kmin), k.q);
 }
 
 __device__ __forceinline__ int code_stochastic(float v, const QConst& k, uint32_t r16) {
-  const double u = (double)r16 * (1.0 / 65536.0);
-  const int r = (int)floor(__dadd_rn(normalised(v, k), u));
+  // x_n in units of 2^-16 (exact scaling), truncated downwards, plus 16 random bits
+  const int fixed = (int)floorf(__fmul_rn(normalised(v, k), 65536.0f)) + (int)r16;
+  const int r = fixed >> 16;  // arithmetic shift: floor division
   return min(max(r, k.kmin), k.q);
 }
 
