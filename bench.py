@@ -153,7 +153,7 @@ def main():
                                    isinstance(spec, synth.LinearLayer)))
     for L in layers:
         L.state = lbt.new_state(gamma0=args.gamma0)
-    ws = torch.empty(max(L.ws_bytes(lbt) for L in layers), dtype=torch.uint8, device="cuda")
+    ws = torch.zeros(max(L.ws_bytes(lbt) for L in layers), dtype=torch.uint8, device="cuda")
     gemm_ops = sum(2.0 * L.spec.gemm_ops for L in layers)       # dX and dW
     n_grad = sum(L.dY.numel() for L in layers)
 

@@ -27,8 +27,10 @@ inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 struct OperandScalars {
   float c_x;       // clip value actually used for X
   float c_w;       // ... for W
-  uint32_t bad_x;  // operand maximum was Inf/NaN
+  uint32_t bad_x;  // bit 0: operand maximum was Inf/NaN; bit 1: internal barrier timed out
   uint32_t bad_w;
+  unsigned long long sync_x;  // finish tickets of the fused operand quantizers; cleared by the
+  unsigned long long sync_w;  // gradient quantizer, which always runs first
 };
 
 // ---- profile.hip: optional event timing of every launch ------------------------
@@ -54,9 +56,14 @@ class ProfScope {
 
 // ---- quantize.hip -------------------------------------------------------------
 constexpr int kMaxPartialBlocks = 2048;  // partial-maximum slots in the workspace header
-// Workspace header: OperandScalars (256 bytes), then pmax[kMaxPartialBlocks][4] uint32.
+// Workspace header: 16 grid-barrier counters 256 bytes apart (the caller hands the
+// workspace over zero-filled and the library leaves these zero after every call), then
+// OperandScalars (256 bytes), pmax[kMaxPartialBlocks][4] uint32 for launch_absmax3, and
+// [kMaxPartialBlocks][2] uint32 for the fused quantizers.
+constexpr size_t kWsBarrierBytes = 16 * 256;
 constexpr size_t kWsScalarsBytes = 256;
-constexpr size_t kWsHeaderBytes = kWsScalarsBytes + (size_t)kMaxPartialBlocks * 16;
+constexpr size_t kWsHeaderBytes =
+    kWsBarrierBytes + kWsScalarsBytes + (size_t)kMaxPartialBlocks * (16 + 8);
 
 // One launch for the maxima of up to three tensors (null pointer = absent); partial
 // maxima go to pmax[block][tensor].  *nblocks_out = number of partial rows written.
@@ -71,18 +78,34 @@ int launch_quantize_flat_operand(const float* x, int64_t n, float c_given, const
                                  float* clip_scale_out, hipStream_t s);
 // Quantize T[A][B][L] (L contiguous) into GEMM layouts of 8-byte granules (16 codes):
 // out_b [A][ceil(B/16)][L][16] and out_a [B][ceil(A/16)][L][16] (either may be null).
-// The gradient flavour takes its clip value from gamma in *st and pmax column 0 and
-// leaves the statistics in *st; the operand flavour takes c_given (> 0) or pmax column
-// pmax_col, writes the clip value to *c_out, and can clear an int32 buffer on the side.
+// Shapes for which relayout_is_fused() holds run as ONE kernel that also finds the
+// tensor maximum (grid barrier); the others need launch_absmax3 first (pmax/nblocks).
+struct RelayoutIo {
+  const uint32_t* pmax;      // two-kernel path: partial maxima from launch_absmax3
+  int nblocks;
+  int pmax_col;
+  uint32_t* pmax_own;        // fused path: scratch for kMaxPartialBlocks x 2 partial maxima
+  unsigned long long* ctr;   // fused path: 16 barrier counters, 256 bytes apart, zero on entry
+  unsigned long long* sync;  // fused operand path: finish ticket (zero on entry)
+  lbt_grad_state* st;
+  uint8_t* out_b;
+  uint8_t* out_a;
+};
+bool relayout_is_fused(const float* x, int64_t A, int64_t B, int64_t L);
+// Gradient flavour: clip value from gamma in *st and the tensor maximum; statistics go to
+// *st.  clear0/clear1: words it zeroes (barrier words of the operand kernels that follow).
+// side_x: optional small tensor whose max |.| it also computes (fused path only) and
+// writes to *side_c_out.
 int launch_quantize_relayout_grad(const float* g, int64_t A, int64_t B, int64_t L,
-                                  const uint32_t* pmax, int nblocks, lbt_grad_state* st,
-                                  uint64_t seed, int rounding, uint8_t* out_b, uint8_t* out_a,
-                                  hipStream_t s);
-int launch_quantize_relayout_operand(const float* x, int64_t A, int64_t B, int64_t L, float c_given,
-                                     const uint32_t* pmax, int nblocks, int pmax_col,
+                                  const RelayoutIo& io, uint64_t seed, int rounding,
+                                  unsigned long long* clear0, unsigned long long* clear1,
+                                  const float* side_x, int64_t side_n, float* side_c_out,
+                                  uint32_t* side_bad_out, hipStream_t s);
+// Operand flavour: clip value c_given (> 0), else *c_ptr, else the tensor maximum.
+int launch_quantize_relayout_operand(const float* x, int64_t A, int64_t B, int64_t L,
+                                     const RelayoutIo& io, float c_given, const float* c_ptr,
                                      int is_unsigned, float* c_out, uint32_t* bad_out,
-                                     lbt_grad_state* st, uint8_t* out_b, uint8_t* out_a,
-                                     int32_t* zero_ptr, int64_t zero_n, hipStream_t s);
+                                     hipStream_t s);
 int launch_update_interval(lbt_grad_state* st, hipStream_t s);
 int launch_state_init(lbt_grad_state* st, const lbt_grad_state& v, hipStream_t s);
 

@@ -15,6 +15,9 @@
 // partials in its prologue, and the clip-out count travels in ONE 64-bit atomic
 // per workgroup (count in the low 40 bits, arrival ticket above) on a word of the
 // layer state that the last workgroup resets to zero.
+#include <map>
+#include <mutex>
+
 #include "lbt_internal.h"
 
 namespace lbt {
@@ -126,33 +129,33 @@ __device__ __forceinline__ uint32_t wave_max(uint32_t v) {
 
 // Block-wide reductions; every thread receives the result.
 __device__ __forceinline__ uint32_t block_max(uint32_t m) {
-  __shared__ uint32_t part[kThreads / 64];
+  __shared__ uint32_t part[16];
+  const int nw = blockDim.x >> 6;
   m = wave_max(m);
   __syncthreads();
   if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = m;
   __syncthreads();
   uint32_t t = part[0];
-#pragma unroll
-  for (int i = 1; i < kThreads / 64; ++i) t = max(t, part[i]);
+  for (int i = 1; i < nw; ++i) t = max(t, part[i]);
   return t;
 }
 
 __device__ __forceinline__ uint32_t block_sum(uint32_t v) {
-  __shared__ uint32_t part[kThreads / 64];
+  __shared__ uint32_t part[16];
+  const int nw = blockDim.x >> 6;
   v = wave_sum(v);
   __syncthreads();
   if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = v;
   __syncthreads();
   uint32_t t = 0;
-#pragma unroll
-  for (int i = 0; i < kThreads / 64; ++i) t += part[i];
+  for (int i = 0; i < nw; ++i) t += part[i];
   return t;
 }
 
 // Maximum of column `col` of the partial maxima left by k_absmax3.
 __device__ __forceinline__ uint32_t reduce_partials(const uint32_t* pmax, int nblocks, int col) {
   uint32_t m = 0;
-  for (int i = threadIdx.x; i < nblocks; i += kThreads) m = max(m, pmax[i * 4 + col]);
+  for (int i = threadIdx.x; i < nblocks; i += blockDim.x) m = max(m, pmax[i * 4 + col]);
   return block_max(m);
 }
 
@@ -181,14 +184,19 @@ __device__ __forceinline__ GradSetup grad_setup(const lbt_grad_state* st, const 
 
 // One atomic per workgroup carries the clip-out count and the arrival ticket; the
 // last workgroup to arrive publishes the statistics and clears the word.
+// The last workgroup also clears the grid-barrier counters `ctr` if the kernel used them.
 __device__ __forceinline__ void grad_finish(lbt_grad_state* st, const GradSetup& g, uint32_t cnt,
-                                            unsigned long long n_total) {
+                                            unsigned long long n_total, unsigned long long* ctr) {
   const uint32_t tot = block_sum(cnt);
   if (threadIdx.x == 0) {
     const unsigned long long nblk = (unsigned long long)gridDim.x * gridDim.y * gridDim.z;
     const unsigned long long old =
         atomicAdd(reinterpret_cast<unsigned long long*>(&st->sync_word), kTicket + tot);
     if ((old >> 40) == nblk - 1) {
+      if (ctr) {
+#pragma unroll
+        for (int j = 0; j < 16; ++j) ctr[j * 32] = 0;
+      }
       st->n_out = (old + tot) & kCountMask;
       st->n_total = n_total;
       st->gmax = g.gmax;
@@ -351,7 +359,7 @@ __global__ __launch_bounds__(kThreads) void k_quantize_flat(
       for (int j = 0; j < nbytes; ++j) codes[gi * 4 + j] = (uint8_t)(word >> (8 * j));
     }
   }
-  if (kGrad) grad_finish(st, gs, cnt, (unsigned long long)n);
+  if (kGrad) grad_finish(st, gs, cnt, (unsigned long long)n, nullptr);
 }
 
 // ---------------------------------------------------------------------------
@@ -367,28 +375,31 @@ struct TileArgs {
   const float* x;
   int A, B, L;
   int AG, BG;
+  // clip value: c_given if > 0, else *c_ptr if c_ptr, else the tensor maximum
   float c_given;
+  const float* c_ptr;
+  // two-kernel path: partial maxima left by k_absmax3
   const uint32_t* pmax;
   int nblocks;
   int pmax_col;
+  // fused path: this kernel's own partial maxima [gridDim.x][2] and its barrier word
+  uint32_t* pmax_own;
+  unsigned long long* ctr;     // grid-barrier arrival counters (zero on entry)
+  unsigned long long* sync;    // operand kernels: finish ticket (zero on entry)
+  unsigned long long* clear0;  // finish tickets of later kernels, cleared by the gradient kernel
+  unsigned long long* clear1;
   lbt_grad_state* st;
   unsigned long long seed;
   float* c_out;
   uint32_t* bad_out;
   uint2* out_b;
   uint2* out_a;
-  // optional side job: clear an int32 buffer (the split-K accumulators of dW)
-  int32_t* zero_ptr;
-  long long zero_n;
+  // fused gradient kernel, side job: max |.| of a second, small tensor (the weights)
+  const float* side_x;
+  long long side_n;
+  float* side_c_out;
+  uint32_t* side_bad_out;
 };
-
-__device__ __forceinline__ void side_zero(const TileArgs& t) {
-  if (!t.zero_ptr) return;
-  const long long nblk = (long long)gridDim.x * gridDim.y * gridDim.z;
-  const long long bid = ((long long)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;
-  for (long long i = bid * kThreads + threadIdx.x; i < t.zero_n; i += nblk * kThreads)
-    t.zero_ptr[i] = 0;
-}
 
 // Phase B: gather granules out of the LDS tile.  `pitch` = bytes per (a,b) row.
 __device__ __forceinline__ void store_granules(const TileArgs& t, const uint8_t* tile, int pitch,
@@ -396,7 +407,7 @@ __device__ __forceinline__ void store_granules(const TileArgs& t, const uint8_t*
   const int n_items = 16 * tl;
   if (t.out_b) {
     const int bg = b0 >> 4;
-    for (int it = threadIdx.x; it < n_items; it += kThreads) {
+    for (int it = threadIdx.x; it < n_items; it += blockDim.x) {
       const int a = it / tl, l = it - a * tl;
       if (a0 + a >= t.A || l0 + l >= t.L) continue;
       uint32_t w0 = 0, w1 = 0;
@@ -410,7 +421,7 @@ __device__ __forceinline__ void store_granules(const TileArgs& t, const uint8_t*
   }
   if (t.out_a) {
     const int ag = a0 >> 4;
-    for (int it = threadIdx.x; it < n_items; it += kThreads) {
+    for (int it = threadIdx.x; it < n_items; it += blockDim.x) {
       const int b = it / tl, l = it - b * tl;
       if (b0 + b >= t.B || l0 + l >= t.L) continue;
       uint32_t w0 = 0, w1 = 0;
@@ -424,117 +435,331 @@ __device__ __forceinline__ void store_granules(const TileArgs& t, const uint8_t*
   }
 }
 
-template <int MODE>
-__device__ __forceinline__ float tile_prologue(const TileArgs& t, GradSetup& gs) {
+// ---------------------------------------------------------------------------
+// Fused single-sweep quantizer.  The grid is sized to be resident all at once.
+// Phase 1: every workgroup reads its tiles, keeps the first R of them in registers
+// and publishes the maximum of what it read at a grid-wide barrier (bounded spin).
+// Phase 2: every workgroup reduces the partial maxima to g_max, derives the clip
+// value and quantizes its tiles -- from registers where it kept them, by
+// re-reading (L2 / memory-side cache) where it did not.
+//   large tiles (SMALL = false): 16 x 16 x 64 window of l, L % 8 == 0
+//   small tiles (SMALL = true):  16 x 16 x L with B % 16 == 0 and (B*L) % 8 == 0;
+//     for one a the sixteen rows are contiguous (16*L floats) and are read as
+//     8-element groups that may straddle rows.
+// A thread owns up to 8 groups of 8 consecutive elements per tile.
+// ---------------------------------------------------------------------------
+constexpr int kSpinLimit = 1 << 22;
+constexpr int kBarrierSlots = 16;    // arrival counters, one per 256 bytes (different channels)
+constexpr int kBarrierStride = 32;   // in 64-bit words
+
+// Grid barrier that also publishes two 32-bit values per workgroup.  No memory
+// fence is used (a device-scope fence costs tens of ns per workgroup and those
+// costs add up serially): the values are written with device-scope atomic
+// exchanges whose results are awaited, then the arrival is counted on one of 16
+// counters; readers use device-scope loads.  Returns false on time-out (never
+// expected: the grid is resident).  The counters must be zero on entry and are
+// cleared again by the last workgroup to finish the kernel.
+__device__ __forceinline__ bool grid_barrier_publish(unsigned long long* ctr, uint32_t* slot,
+                                                     uint32_t v0, uint32_t v1, unsigned nblocks) {
+  __shared__ int ok_flag;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const uint32_t o0 = atomicExch(slot, v0);
+    const uint32_t o1 = atomicExch(slot + 1, v1);
+    // the arrival is issued only after both exchanges have returned their old values
+    asm volatile("" : : "v"(o0), "v"(o1) : "memory");
+    atomicAdd(&ctr[(blockIdx.x % kBarrierSlots) * kBarrierStride], 1ull);
+    int ok = 0;
+    for (int spin = 0; spin < kSpinLimit; ++spin) {
+      unsigned long long arrived = 0;
+#pragma unroll
+      for (int j = 0; j < kBarrierSlots; ++j)
+        arrived += __hip_atomic_load(&ctr[j * kBarrierStride], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (arrived >= nblocks) { ok = 1; break; }
+      __builtin_amdgcn_s_sleep(4);
+    }
+    ok_flag = ok;
+  }
+  __syncthreads();
+  return ok_flag != 0;
+}
+
+__device__ __forceinline__ void barrier_reset(unsigned long long* ctr) {
+#pragma unroll
+  for (int j = 0; j < kBarrierSlots; ++j) ctr[j * kBarrierStride] = 0;
+}
+
+struct ItemPos {
+  long long e0;   // flat index of the first of the 8 elements
+  int row, l;     // large: LDS row (a*16+b) and l within the window; small: a and group j
+  bool valid;
+};
+
+template <bool SMALL, int THREADS>
+__device__ __forceinline__ ItemPos item_pos(const TileArgs& t, int a0, int b0, int l0, int i) {
+  ItemPos p;
+  const int it = threadIdx.x + THREADS * i;
+  if (SMALL) {
+    const int octs = 2 * t.L;
+    const int a = it / octs, j = it - a * octs;
+    p.row = a;
+    p.l = j;
+    p.valid = (a < 16) && (a0 + a < t.A);
+    p.e0 = ((long long)(a0 + a) * t.B + b0) * t.L + 8 * j;
+  } else {
+    const int row = it >> 3, oct = it & 7;
+    const int ga = a0 + (row >> 4), gb = b0 + (row & 15), gl = l0 + oct * 8;
+    p.row = row;
+    p.l = oct * 8;
+    p.valid = ga < t.A && gb < t.B && gl < t.L;
+    p.e0 = ((long long)ga * t.B + gb) * t.L + gl;
+  }
+  return p;
+}
+
+__device__ __forceinline__ void load8(const float* x, long long e0, float v[8]) {
+  const float4 p = *reinterpret_cast<const float4*>(x + e0);
+  const float4 q = *reinterpret_cast<const float4*>(x + e0 + 4);
+  v[0] = p.x; v[1] = p.y; v[2] = p.z; v[3] = p.w;
+  v[4] = q.x; v[5] = q.y; v[6] = q.z; v[7] = q.w;
+}
+
+__device__ __forceinline__ uint32_t max_key8(const float v[8], int use_abs) {
+  uint32_t m = 0;
+#pragma unroll
+  for (int u = 0; u < 8; ++u) m = max(m, max_key(v[u], use_abs));
+  return m;
+}
+
+template <int MODE, int THREADS, int R, bool SMALL>
+__global__ __launch_bounds__(THREADS) void k_quantize_fused(const TileArgs t, int pitch) {
+  extern __shared__ __attribute__((aligned(8))) uint8_t dyn_tile[];
+  constexpr bool kGrad = MODE >= 2;
+  constexpr int kUseAbs = (MODE == 1) ? 0 : 1;
+  const int G = gridDim.x, bid = blockIdx.x;
+  const int tiles_l = SMALL ? 1 : (t.L + 63) / 64;
+  const int tiles = tiles_l * t.BG * t.AG;
+  const int tl = SMALL ? t.L : 64;
+  const bool need_max = kGrad || (!(t.c_given > 0.0f) && !t.c_ptr);
+  if (kGrad && bid == 0 && threadIdx.x == 0) {
+    if (t.clear0) *t.clear0 = 0;
+    if (t.clear1) *t.clear1 = 0;
+  }
+  auto tile_origin = [&](int tile_id, int& a0, int& b0, int& l0) {
+    const int lt = tile_id % tiles_l, rest = tile_id / tiles_l;
+    l0 = lt * 64;
+    b0 = (rest % t.BG) * 16;
+    a0 = (rest / t.BG) * 16;
+  };
+
+  // ---- phase 1: read, keep, maximum ------------------------------------------------
+  float cache[R][8][8];
+  uint32_t bits = 0, side_bits = 0;
+  bool poisoned = false;
+  if (need_max) {
+    uint32_t m = 0, m_side = 0;
+    // All loads of the kept tiles are issued before any value is used (invalid items
+    // read element 0 and are ignored), so a thread has up to 2*8*R requests in flight.
+    bool ok[R][8];
+#pragma unroll
+    for (int k = 0; k < R; ++k) {
+      const int tile_id = bid + k * G;
+      int a0, b0, l0;
+      tile_origin(tile_id < tiles ? tile_id : 0, a0, b0, l0);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const ItemPos p = item_pos<SMALL, THREADS>(t, a0, b0, l0, i);
+        ok[k][i] = p.valid && tile_id < tiles;
+        load8(t.x, ok[k][i] ? p.e0 : 0, cache[k][i]);
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < R; ++k)
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        if (ok[k][i]) m = max(m, max_key8(cache[k][i], kUseAbs));
+    for (int k = R; bid + k * G < tiles; ++k) {
+      int a0, b0, l0;
+      tile_origin(bid + k * G, a0, b0, l0);
+      float v[8][8];
+      bool okv[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const ItemPos p = item_pos<SMALL, THREADS>(t, a0, b0, l0, i);
+        okv[i] = p.valid;
+        load8(t.x, p.valid ? p.e0 : 0, v[i]);
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        if (okv[i]) m = max(m, max_key8(v[i], kUseAbs));
+    }
+    if (kGrad && t.side_x) {
+      for (long long i = (long long)bid * THREADS + threadIdx.x; i < t.side_n; i += (long long)G * THREADS)
+        m_side = max(m_side, max_key(t.side_x[i], 1));
+      m_side = block_max(m_side);
+    }
+    m = block_max(m);
+    poisoned = !grid_barrier_publish(t.ctr, t.pmax_own + 2 * bid, m, m_side, (unsigned)G);
+    uint32_t mm = 0, ms = 0;
+    for (int i = threadIdx.x; i < G; i += THREADS) {
+      // device-scope loads: the values were written by workgroups on other dies
+      mm = max(mm, __hip_atomic_load(&t.pmax_own[2 * i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+      ms = max(ms, __hip_atomic_load(&t.pmax_own[2 * i + 1], __ATOMIC_RELAXED,
+                                     __HIP_MEMORY_SCOPE_AGENT));
+    }
+    bits = block_max(mm);
+    if (kGrad && t.side_x) side_bits = block_max(ms);
+  }
+
+  // ---- clip value ----------------------------------------------------------------------
+  GradSetup gs{};
+  float c;
+  if (kGrad) {
+    gs.gmax = __uint_as_float(bits);
+    gs.c = 0.0f;
+    if (bits >= kInfBits) gs.status = LBT_STATUS_NONFINITE;
+    else if (bits == 0) gs.status = LBT_STATUS_ZERO_GRAD;
+    else {
+      gs.status = LBT_STATUS_OK;
+      gs.c = (float)__dmul_rn(t.st->gamma, (double)gs.gmax);
+    }
+    if (t.side_x && side_bits >= kInfBits && gs.status == LBT_STATUS_OK)
+      gs.status = LBT_STATUS_NONFINITE;  // non-finite weights
+    if (poisoned) gs.status = LBT_STATUS_INTERNAL;
+    c = gs.c;
+    if (t.side_x && bid == 0 && threadIdx.x == 0) {
+      const bool bad = side_bits >= kInfBits;
+      *t.side_c_out = bad ? 0.0f : __uint_as_float(side_bits);
+      *t.side_bad_out = bad ? 1u : 0u;
+    }
+  } else {
+    bool bad = false;
+    c = t.c_given;
+    if (!(c > 0.0f)) {
+      if (t.c_ptr) c = *t.c_ptr;
+      else if (bits >= kInfBits) { bad = true; c = 0.0f; }
+      else c = __uint_as_float(bits);
+    }
+    if (bid == 0 && threadIdx.x == 0) {
+      if (t.c_out) *t.c_out = c;
+      if (t.bad_out) *t.bad_out = (bad ? 1u : 0u) | (poisoned ? 2u : 0u);
+      if (bad && t.st) t.st->status = LBT_STATUS_NONFINITE;
+    }
+  }
+  const QConst qc = make_qconst(c, MODE == 1);
+  const bool live = c > 0.0f;
+  const unsigned long long step = (MODE == 3) ? t.st->step : 0ull;
+
+  // ---- phase 2: quantize tile by tile --------------------------------------------------
+  uint32_t cnt = 0;
+  auto quantize_item = [&](const ItemPos& p, const float v[8], bool have) {
+    // eight codes of one group -> LDS bytes
+    if (SMALL) {
+      if (p.row >= 16) return;  // beyond the tile's groups
+      int b = (8 * p.l) / t.L, l = 8 * p.l - b * t.L;
+      Philox4 rnd{};
+      if (MODE == 3 && have) rnd = philox_block((unsigned long long)p.e0 >> 3, step, t.seed);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        int k = 0;
+        if (have) k = quantize_one<MODE>(v[u], qc, rnd, u, cnt);
+        dyn_tile[(p.row * 16 + b) * pitch + l] = (uint8_t)(k & 0xF);
+        if (++l == t.L) { l = 0; ++b; }
+      }
+    } else {
+      uint32_t w0 = 0, w1 = 0;
+      if (have) {
+        Philox4 rnd{};
+        if (MODE == 3) rnd = philox_block((unsigned long long)p.e0 >> 3, step, t.seed);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          w0 |= ((uint32_t)quantize_one<MODE>(v[u], qc, rnd, u, cnt) & 0xFu) << (8 * u);
+          w1 |= ((uint32_t)quantize_one<MODE>(v[4 + u], qc, rnd, 4 + u, cnt) & 0xFu) << (8 * u);
+        }
+      }
+      *reinterpret_cast<uint2*>(dyn_tile + p.row * pitch + p.l) = make_uint2(w0, w1);
+    }
+  };
+  auto finish_tile = [&](int a0, int b0, int l0) {
+    __syncthreads();
+    store_granules(t, dyn_tile, pitch, tl, a0, b0, l0);
+    __syncthreads();
+  };
+
+  auto reload_tile = [&](int a0, int b0, int l0) {
+    float v[8][8];
+    ItemPos p[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      p[i] = item_pos<SMALL, THREADS>(t, a0, b0, l0, i);
+      load8(t.x, p[i].valid ? p[i].e0 : 0, v[i]);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) quantize_item(p[i], v[i], p[i].valid && live);
+    finish_tile(a0, b0, l0);
+  };
+#pragma unroll
+  for (int k = 0; k < R; ++k) {
+    const int tile_id = bid + k * G;
+    if (tile_id < tiles) {
+      int a0, b0, l0;
+      tile_origin(tile_id, a0, b0, l0);
+      if (need_max) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const ItemPos p = item_pos<SMALL, THREADS>(t, a0, b0, l0, i);
+          quantize_item(p, cache[k][i], p.valid && live);
+        }
+        finish_tile(a0, b0, l0);
+      } else {
+        reload_tile(a0, b0, l0);
+      }
+    }
+  }
+  for (int k = R; bid + k * G < tiles; ++k) {
+    int a0, b0, l0;
+    tile_origin(bid + k * G, a0, b0, l0);
+    reload_tile(a0, b0, l0);
+  }
+  if (kGrad) {
+    grad_finish(t.st, gs, cnt, (unsigned long long)t.A * t.B * t.L, t.ctr);
+  } else if (need_max && threadIdx.x == 0) {
+    // last workgroup out clears the barrier counters for the next kernel
+    const unsigned long long old = atomicAdd(t.sync, 1ull);
+    if (old == (unsigned long long)G - 1) {
+      barrier_reset(t.ctr);
+      *t.sync = 0;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Any shape, two kernels (k_absmax3 first, or a clip value from the caller):
+// tile 16 x 16 x TL with one scalar load per element.  TL = 1 serves matrices.
+// ---------------------------------------------------------------------------
+template <int MODE, int TL>
+__global__ __launch_bounds__(kThreads) void k_quantize_tile_generic(const TileArgs t) {
+  constexpr int PITCH = (TL == 1) ? 1 : TL + 4;
+  __shared__ __attribute__((aligned(8))) uint8_t tile[256 * PITCH];
+  GradSetup gs{};
+  float c;
   if (MODE >= 2) {
     gs = grad_setup(t.st, t.pmax, t.nblocks);
-    return gs.c;
+    c = gs.c;
+  } else if (!(t.c_given > 0.0f) && t.c_ptr) {
+    c = *t.c_ptr;
+  } else {
+    c = operand_setup(t.c_given, t.pmax, t.nblocks, t.pmax_col, MODE == 1, t.c_out, t.bad_out, t.st,
+                      nullptr);
   }
-  return operand_setup(t.c_given, t.pmax, t.nblocks, t.pmax_col, MODE == 1, t.c_out, t.bad_out,
-                       t.st, nullptr);
-}
-
-// Large L (L % 8 == 0): tile 16 x 16 x 64, one 8-element group (two float4) per item.
-template <int MODE>
-__global__ __launch_bounds__(kThreads) void k_quantize_tile(const TileArgs t) {
-  constexpr int TL = 64, PITCH = TL + 8;
-  __shared__ __attribute__((aligned(8))) uint8_t tile[256 * PITCH];
-  GradSetup gs{};
-  const float c = tile_prologue<MODE>(t, gs);
   const QConst qc = make_qconst(c, MODE == 1);
   const bool live = c > 0.0f;
   const unsigned long long step = (MODE == 3) ? t.st->step : 0ull;
   const int l0 = blockIdx.x * TL, b0 = blockIdx.y * 16, a0 = blockIdx.z * 16;
-  side_zero(t);
-
-  uint32_t cnt = 0;
-  const int oct = threadIdx.x & 7;
-  const int gl = l0 + oct * 8;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int row = (threadIdx.x >> 3) + 32 * i;  // row = a * 16 + b
-    const int ga = a0 + (row >> 4), gb = b0 + (row & 15);
-    uint32_t w0 = 0, w1 = 0;
-    if (live && ga < t.A && gb < t.B && gl < t.L) {
-      const long long e0 = ((long long)ga * t.B + gb) * t.L + gl;
-      const float4 p = *reinterpret_cast<const float4*>(t.x + e0);
-      const float4 q = *reinterpret_cast<const float4*>(t.x + e0 + 4);
-      Philox4 rnd{};
-      if (MODE == 3) rnd = philox_block((unsigned long long)e0 >> 3, step, t.seed);
-      w0 = ((uint32_t)quantize_one<MODE>(p.x, qc, rnd, 0, cnt) & 0xFu) |
-           (((uint32_t)quantize_one<MODE>(p.y, qc, rnd, 1, cnt) & 0xFu) << 8) |
-           (((uint32_t)quantize_one<MODE>(p.z, qc, rnd, 2, cnt) & 0xFu) << 16) |
-           (((uint32_t)quantize_one<MODE>(p.w, qc, rnd, 3, cnt) & 0xFu) << 24);
-      w1 = ((uint32_t)quantize_one<MODE>(q.x, qc, rnd, 4, cnt) & 0xFu) |
-           (((uint32_t)quantize_one<MODE>(q.y, qc, rnd, 5, cnt) & 0xFu) << 8) |
-           (((uint32_t)quantize_one<MODE>(q.z, qc, rnd, 6, cnt) & 0xFu) << 16) |
-           (((uint32_t)quantize_one<MODE>(q.w, qc, rnd, 7, cnt) & 0xFu) << 24);
-    }
-    *reinterpret_cast<uint2*>(tile + row * PITCH + oct * 8) = make_uint2(w0, w1);
+  if (MODE >= 2 && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0) {
+    if (t.clear0) *t.clear0 = 0;
+    if (t.clear1) *t.clear1 = 0;
   }
-  __syncthreads();
-  store_granules(t, tile, PITCH, TL, a0, b0, l0);
-  if (MODE >= 2) grad_finish(t.st, gs, cnt, (unsigned long long)t.A * t.B * t.L);
-}
-
-// Small L with B % 16 == 0 and (B*L) % 8 == 0: tile 16 x 16 x L.  For one a the
-// sixteen rows b0..b0+15 are contiguous in memory (16*L floats, a multiple of 8
-// elements that starts on a multiple of 8), so they are read as 8-element groups
-// that may straddle rows.
-template <int MODE>
-__global__ __launch_bounds__(kThreads) void k_quantize_tile_small(const TileArgs t, int pitch) {
-  extern __shared__ __attribute__((aligned(8))) uint8_t dyn_tile[];
-  GradSetup gs{};
-  const float c = tile_prologue<MODE>(t, gs);
-  const QConst qc = make_qconst(c, MODE == 1);
-  const bool live = c > 0.0f;
-  const unsigned long long step = (MODE == 3) ? t.st->step : 0ull;
-  const int b0 = blockIdx.y * 16, a0 = blockIdx.z * 16;
-  side_zero(t);
-
-  uint32_t cnt = 0;
-  const int L = t.L;
-  const int octs = 2 * L;  // 16 * L / 8 groups per a
-  for (int it = threadIdx.x; it < 16 * octs; it += kThreads) {
-    const int a = it / octs, j = it - a * octs;
-    const int ga = a0 + a;
-    int b = (8 * j) / L, l = 8 * j - b * L;
-    float v[8];
-    Philox4 rnd{};
-    const bool have = live && ga < t.A;
-    if (have) {
-      const long long e0 = ((long long)ga * t.B + b0) * L + 8 * j;
-      const float4 p = *reinterpret_cast<const float4*>(t.x + e0);
-      const float4 q = *reinterpret_cast<const float4*>(t.x + e0 + 4);
-      v[0] = p.x; v[1] = p.y; v[2] = p.z; v[3] = p.w;
-      v[4] = q.x; v[5] = q.y; v[6] = q.z; v[7] = q.w;
-      if (MODE == 3) rnd = philox_block((unsigned long long)e0 >> 3, step, t.seed);
-    }
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      int k = 0;
-      if (have) k = quantize_one<MODE>(v[u], qc, rnd, u, cnt);
-      dyn_tile[(a * 16 + b) * pitch + l] = (uint8_t)(k & 0xF);
-      if (++l == L) { l = 0; ++b; }
-    }
-  }
-  __syncthreads();
-  store_granules(t, dyn_tile, pitch, L, a0, b0, 0);
-  if (MODE >= 2) grad_finish(t.st, gs, cnt, (unsigned long long)t.A * t.B * t.L);
-}
-
-// Any shape: tile 16 x 16 x 32 with one scalar load per element.
-template <int MODE>
-__global__ __launch_bounds__(kThreads) void k_quantize_tile_generic(const TileArgs t) {
-  constexpr int TL = 32, PITCH = TL + 4;
-  __shared__ __attribute__((aligned(8))) uint8_t tile[256 * PITCH];
-  GradSetup gs{};
-  const float c = tile_prologue<MODE>(t, gs);
-  const QConst qc = make_qconst(c, MODE == 1);
-  const bool live = c > 0.0f;
-  const unsigned long long step = (MODE == 3) ? t.st->step : 0ull;
-  const int l0 = blockIdx.x * TL, b0 = blockIdx.y * 16, a0 = blockIdx.z * 16;
-  side_zero(t);
 
   uint32_t cnt = 0;
   for (int idx = threadIdx.x; idx < 256 * TL; idx += kThreads) {
@@ -551,7 +776,7 @@ __global__ __launch_bounds__(kThreads) void k_quantize_tile_generic(const TileAr
   }
   __syncthreads();
   store_granules(t, tile, PITCH, TL, a0, b0, l0);
-  if (MODE >= 2) grad_finish(t.st, gs, cnt, (unsigned long long)t.A * t.B * t.L);
+  if (MODE >= 2) grad_finish(t.st, gs, cnt, (unsigned long long)t.A * t.B * t.L, nullptr);
 }
 
 inline int flat_grid(long long work_items) {
@@ -562,23 +787,81 @@ inline int flat_grid(long long work_items) {
   return (int)blocks;
 }
 
+enum FusedKind { kNotFused = 0, kFusedLarge, kFusedSmall256, kFusedSmall1024 };
+
+FusedKind fused_kind(const float* x, long long A, long long B, long long L) {
+  (void)A;
+  if (reinterpret_cast<uintptr_t>(x) % 16 != 0) return kNotFused;
+  if (L >= 64 && L % 8 == 0) return kFusedLarge;
+  if (L >= 2 && L <= 248 && B % 16 == 0 && (B * L) % 8 == 0)
+    return L <= 64 ? kFusedSmall256 : kFusedSmall1024;
+  return kNotFused;
+}
+
+int device_cus() {
+  static int cus = 0;
+  if (!cus) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return 0;
+    cus = prop.multiProcessorCount;
+  }
+  return cus;
+}
+
+// Launch the fused kernel on a grid that is resident all at once.
+template <int MODE, int THREADS, int R, bool SMALL>
+int launch_fused(const TileArgs& t, int pitch, hipStream_t s) {
+  const size_t dyn = (size_t)256 * pitch;
+  // resident workgroups per compute unit for this LDS size: asked once, then remembered
+  static std::mutex mu;
+  static std::map<size_t, int> known;
+  int per_cu = 0;
+  {
+    std::lock_guard<std::mutex> lk(mu);
+    auto it = known.find(dyn);
+    if (it != known.end()) {
+      per_cu = it->second;
+    } else {
+      if (hipOccupancyMaxActiveBlocksPerMultiprocessor(
+              &per_cu, k_quantize_fused<MODE, THREADS, R, SMALL>, THREADS, dyn) != hipSuccess ||
+          per_cu < 1)
+        return LBT_ERR_HIP;
+      known[dyn] = per_cu;
+    }
+  }
+  const int cus = device_cus();
+  if (cus < 1) return LBT_ERR_HIP;
+  const long long tiles_l = SMALL ? 1 : (t.L + 63) / 64;
+  const long long tiles = tiles_l * t.BG * t.AG;
+  long long grid = (long long)per_cu * cus;
+  if (grid > kMaxPartialBlocks) grid = kMaxPartialBlocks;
+  if (grid > tiles) grid = tiles;
+  hipLaunchKernelGGL((k_quantize_fused<MODE, THREADS, R, SMALL>), dim3((unsigned)grid), dim3(THREADS),
+                     dyn, s, t, pitch);
+  LBT_LAUNCH_CHECK();
+  return LBT_OK;
+}
+
 template <int MODE>
-int tile_dispatch(TileArgs t, hipStream_t s) {
-  const int AG = t.AG, BG = t.BG;
-  if (AG > 65535 || BG > 65535) return LBT_ERR_UNSUPPORTED;
-  const bool aligned16 = (reinterpret_cast<uintptr_t>(t.x) % 16) == 0;
-  const long long BL = (long long)t.B * t.L;
-  if (aligned16 && t.L >= 64 && t.L % 8 == 0) {
-    dim3 grid((unsigned)((t.L + 63) / 64), (unsigned)BG, (unsigned)AG);
-    hipLaunchKernelGGL(k_quantize_tile<MODE>, grid, dim3(kThreads), 0, s, t);
-  } else if (aligned16 && t.L > 1 && t.L <= 248 && t.B % 16 == 0 && BL % 8 == 0) {
-    const int pitch = (t.L + 3) / 4 * 4 + 4;
-    dim3 grid(1, (unsigned)BG, (unsigned)AG);
-    hipLaunchKernelGGL(k_quantize_tile_small<MODE>, grid, dim3(kThreads), (size_t)256 * pitch, s, t,
-                       pitch);
+int tile_dispatch(const TileArgs& t, hipStream_t s) {
+  if (t.AG > 65535 || t.BG > 65535) return LBT_ERR_UNSUPPORTED;
+  switch (fused_kind(t.x, t.A, t.B, t.L)) {
+    case kFusedLarge:
+      return launch_fused<MODE, 256, 2, false>(t, 72, s);
+    case kFusedSmall256:
+      return launch_fused<MODE, 256, 2, true>(t, (t.L + 3) / 4 * 4 + 4, s);
+    case kFusedSmall1024:
+      return launch_fused<MODE, 1024, 1, true>(t, (t.L + 3) / 4 * 4 + 4, s);
+    default:
+      break;
+  }
+  if (t.L == 1) {
+    dim3 grid(1, (unsigned)t.BG, (unsigned)t.AG);
+    hipLaunchKernelGGL((k_quantize_tile_generic<MODE, 1>), grid, dim3(kThreads), 0, s, t);
   } else {
-    dim3 grid((unsigned)((t.L + 31) / 32), (unsigned)BG, (unsigned)AG);
-    hipLaunchKernelGGL(k_quantize_tile_generic<MODE>, grid, dim3(kThreads), 0, s, t);
+    dim3 grid((unsigned)((t.L + 31) / 32), (unsigned)t.BG, (unsigned)t.AG);
+    hipLaunchKernelGGL((k_quantize_tile_generic<MODE, 32>), grid, dim3(kThreads), 0, s, t);
   }
   LBT_LAUNCH_CHECK();
   return LBT_OK;
@@ -642,40 +925,46 @@ int launch_quantize_flat_operand(const float* x, int64_t n, float c_given, const
   return LBT_OK;
 }
 
-int launch_quantize_relayout_grad(const float* g, int64_t A, int64_t B, int64_t L,
-                                  const uint32_t* pmax, int nblocks, lbt_grad_state* st,
-                                  uint64_t seed, int rounding, uint8_t* out_b, uint8_t* out_a,
-                                  hipStream_t s) {
-  ProfScope prof(KID_RELAYOUT_GRAD, (double)A * (double)B * (double)L, s);
-  TileArgs t{};
-  t.x = g; t.A = (int)A; t.B = (int)B; t.L = (int)L;
+bool relayout_is_fused(const float* x, int64_t A, int64_t B, int64_t L) {
+  return fused_kind(x, A, B, L) != kNotFused;
+}
+
+static void fill_tile_args(TileArgs& t, const float* x, int64_t A, int64_t B, int64_t L,
+                           const RelayoutIo& io) {
+  t.x = x; t.A = (int)A; t.B = (int)B; t.L = (int)L;
   t.AG = (int)(round_up(A, kGranule) / kGranule);
   t.BG = (int)(round_up(B, kGranule) / kGranule);
-  t.pmax = pmax; t.nblocks = nblocks; t.pmax_col = 0;
-  t.st = st; t.seed = seed;
-  t.out_b = reinterpret_cast<uint2*>(out_b);
-  t.out_a = reinterpret_cast<uint2*>(out_a);
+  t.pmax = io.pmax; t.nblocks = io.nblocks; t.pmax_col = io.pmax_col;
+  t.pmax_own = io.pmax_own; t.sync = io.sync; t.ctr = io.ctr;
+  t.st = io.st;
+  t.out_b = reinterpret_cast<uint2*>(io.out_b);
+  t.out_a = reinterpret_cast<uint2*>(io.out_a);
+}
+
+int launch_quantize_relayout_grad(const float* g, int64_t A, int64_t B, int64_t L,
+                                  const RelayoutIo& io, uint64_t seed, int rounding,
+                                  unsigned long long* clear0, unsigned long long* clear1,
+                                  const float* side_x, int64_t side_n, float* side_c_out,
+                                  uint32_t* side_bad_out, hipStream_t s) {
+  ProfScope prof(KID_RELAYOUT_GRAD, (double)A * (double)B * (double)L, s);
+  TileArgs t{};
+  fill_tile_args(t, g, A, B, L, io);
+  t.seed = seed;
+  t.clear0 = clear0; t.clear1 = clear1;
+  t.side_x = side_x; t.side_n = side_n; t.side_c_out = side_c_out; t.side_bad_out = side_bad_out;
   if (rounding == LBT_ROUND_STOCHASTIC) return tile_dispatch<3>(t, s);
   return tile_dispatch<2>(t, s);
 }
 
-int launch_quantize_relayout_operand(const float* x, int64_t A, int64_t B, int64_t L, float c_given,
-                                     const uint32_t* pmax, int nblocks, int pmax_col,
+int launch_quantize_relayout_operand(const float* x, int64_t A, int64_t B, int64_t L,
+                                     const RelayoutIo& io, float c_given, const float* c_ptr,
                                      int is_unsigned, float* c_out, uint32_t* bad_out,
-                                     lbt_grad_state* st, uint8_t* out_b, uint8_t* out_a,
-                                     int32_t* zero_ptr, int64_t zero_n, hipStream_t s) {
+                                     hipStream_t s) {
   ProfScope prof(KID_RELAYOUT_OPERAND, (double)A * (double)B * (double)L, s);
   TileArgs t{};
-  t.x = x; t.A = (int)A; t.B = (int)B; t.L = (int)L;
-  t.AG = (int)(round_up(A, kGranule) / kGranule);
-  t.BG = (int)(round_up(B, kGranule) / kGranule);
-  t.c_given = c_given;
-  t.pmax = pmax; t.nblocks = nblocks; t.pmax_col = pmax_col;
-  t.st = st;
+  fill_tile_args(t, x, A, B, L, io);
+  t.c_given = c_given; t.c_ptr = c_ptr;
   t.c_out = c_out; t.bad_out = bad_out;
-  t.out_b = reinterpret_cast<uint2*>(out_b);
-  t.out_a = reinterpret_cast<uint2*>(out_a);
-  t.zero_ptr = zero_ptr; t.zero_n = zero_n;
   if (is_unsigned) return tile_dispatch<1>(t, s);
   return tile_dispatch<0>(t, s);
 }

@@ -25,7 +25,7 @@ def unpack_nibbles(packed: np.ndarray, n: int, signed: bool) -> np.ndarray:
 def quantize_grad(g: np.ndarray, st, seed=0, rounding=0):
     n = g.size
     codes = torch.full(((n + 1) // 2,), 0xEE, dtype=torch.uint8, device=DEV)
-    ws = torch.empty(lbt.lbt_workspace_bytes_quantize(n), dtype=torch.uint8, device=DEV)
+    ws = torch.zeros(lbt.lbt_workspace_bytes_quantize(n), dtype=torch.uint8, device=DEV)
     lbt.lbt_quantize_grad(dev(g.reshape(-1)), st, seed, rounding, codes, ws)
     return codes.cpu().numpy()
 
@@ -34,7 +34,7 @@ def quantize_operand(x: np.ndarray, c: float, unsigned: bool):
     n = x.size
     codes = torch.full(((n + 1) // 2,), 0xEE, dtype=torch.uint8, device=DEV)
     cs = torch.zeros(2, dtype=torch.float32, device=DEV)
-    ws = torch.empty(lbt.lbt_workspace_bytes_quantize(n), dtype=torch.uint8, device=DEV)
+    ws = torch.zeros(lbt.lbt_workspace_bytes_quantize(n), dtype=torch.uint8, device=DEV)
     lbt.lbt_quantize_operand(dev(x.reshape(-1)), c, unsigned, 4, codes, cs, ws)
     return codes.cpu().numpy(), cs.cpu().numpy()
 
@@ -47,7 +47,7 @@ def backward_linear(X, W, dY, st, c_x=0.0, x_unsigned=False, c_w=0.0, seed=0, ro
                     want_dx=True, want_dw=True):
     M, K = X.shape
     N = W.shape[1]
-    ws = torch.empty(lbt.lbt_workspace_bytes_linear(M, K, N), dtype=torch.uint8, device=DEV)
+    ws = torch.zeros(lbt.lbt_workspace_bytes_linear(M, K, N), dtype=torch.uint8, device=DEV)
     r = Result()
     dX = torch.full((M, K), float("nan"), device=DEV) if want_dx else None
     dW = torch.full((K, N), float("nan"), device=DEV) if want_dw else None
@@ -64,7 +64,7 @@ def backward_conv2d(X, W, dY, stride, pad, st, c_x=0.0, x_unsigned=True, c_w=0.0
                     rounding=0, want_dx=True, want_dw=True, with_acc=True):
     N, Cc, H, Wd = X.shape
     K, _, R, S = W.shape
-    ws = torch.empty(lbt.lbt_workspace_bytes_conv2d(N, Cc, H, Wd, K, R, S, stride, pad),
+    ws = torch.zeros(lbt.lbt_workspace_bytes_conv2d(N, Cc, H, Wd, K, R, S, stride, pad),
                      dtype=torch.uint8, device=DEV)
     r = Result()
     dX = torch.full(X.shape, float("nan"), device=DEV) if want_dx else None
