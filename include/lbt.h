@@ -14,10 +14,8 @@
  *     by the caller; the library never allocates, frees or retains them.
  *     fp32 tensors must be 16-byte aligned, code buffers 4-byte aligned,
  *     workspaces 256-byte aligned.
- *   - A workspace must be zero-filled once after it is allocated (its first
- *     4 KiB hold grid-synchronisation counters that the library expects to
- *     find zero and leaves zero); after that it can be reused from call to
- *     call and between layers, by one stream at a time.
+ *   - A workspace needs no initialisation and can be reused from call to call
+ *     and between layers, by one stream at a time.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Calls only enqueue work; they do not synchronise with the host, except
  *     lbt_state_read which waits for its copy.
@@ -48,7 +46,6 @@ extern "C" {
 #define LBT_STATUS_OK 0
 #define LBT_STATUS_NONFINITE 1   /* NaN or Inf seen in a tensor whose maximum was taken */
 #define LBT_STATUS_ZERO_GRAD 2   /* max|dY| == 0: codes 0, scale 0, gamma not updated   */
-#define LBT_STATUS_INTERNAL 3    /* an internal grid barrier timed out: results invalid */
 
 #define LBT_ROUND_NEAREST 0      /* round half to even                              */
 #define LBT_ROUND_STOCHASTIC 1   /* (floor(x_n*2^16) + r16) >> 16, r16 from Philox  */

@@ -68,15 +68,14 @@ int backward_common(const float* X, const float* W, const float* dY, const ConvG
   if (ws_bytes < lay.total) return LBT_ERR_WORKSPACE;
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   uint8_t* base = static_cast<uint8_t*>(ws);
-  unsigned long long* ctr = reinterpret_cast<unsigned long long*>(base);
-  OperandScalars* sc = reinterpret_cast<OperandScalars*>(base + kWsBarrierBytes);
+  OperandScalars* sc = reinterpret_cast<OperandScalars*>(base + lay.off_scalars);
   uint8_t* g_npqk = base + lay.off_g_npqk;
   uint8_t* g_kpqn = base + lay.off_g_kpqn;
   uint8_t* x_chwn = base + lay.off_x_chwn;
   uint8_t* w_crsk = base + lay.off_w_crsk;
   int32_t* partial = reinterpret_cast<int32_t*>(base + lay.off_partial);
 
-  uint32_t* pmax = reinterpret_cast<uint32_t*>(base + kWsBarrierBytes + kWsScalarsBytes);
+  uint32_t* pmax = reinterpret_cast<uint32_t*>(base + kWsScalarsBytes);
   const int64_t n_dy = (int64_t)g.N * g.K * g.P * g.Q;
   const int64_t n_x = (int64_t)g.N * g.C * g.H * g.W;
   const int64_t n_w = (int64_t)g.K * g.C * g.R * g.S;
@@ -85,46 +84,26 @@ int backward_common(const float* X, const float* W, const float* dY, const ConvG
   const bool want_cw = dX && !(c_w > 0.0f), want_cx = dW && !(c_x > 0.0f);
   // Tensor shapes as the re-layout sees them: T[A][B][L], L contiguous
   const int64_t wA = w_is_ck ? g.C : g.K, wB = w_is_ck ? g.K : g.C, wL = w_is_ck ? 1 : RS;
-  const bool fused_g = relayout_is_fused(dY, g.N, g.K, PQ);
-  const bool fused_x = dW && relayout_is_fused(X, g.N, g.C, HW);
-  const bool fused_w = dX && relayout_is_fused(W, wA, wB, wL);
-  // 1. a separate maximum pass only for the tensors whose quantizer cannot find it itself
-  //    (the fused gradient kernel also takes the weights' maximum on the side)
-  const bool max_g = !fused_g;
-  const bool max_x = want_cx && !fused_x;
-  const bool max_w = want_cw && !fused_g && !fused_w;
-  if (max_g || max_x || max_w) {
-    if ((rc = launch_absmax3(max_g ? dY : nullptr, n_dy, 1, max_x ? X : nullptr, n_x,
-                             x_unsigned ? 0 : 1, max_w ? W : nullptr, n_w, 1, pmax, &nblocks, s)))
-      return rc;
-  }
-  // The fused kernels keep their own partial maxima behind the rows launch_absmax3 may use.
-  uint32_t* pmax_own = pmax + (size_t)kMaxPartialBlocks * 4;
-  unsigned long long* sync_x = &sc->sync_x;
-  unsigned long long* sync_w = &sc->sync_w;
+  // 1. maxima of dY, and of X / W where no clip value was given, in one launch
+  if ((rc = launch_absmax3(dY, n_dy, 1, want_cx ? X : nullptr, n_x, x_unsigned ? 0 : 1,
+                           want_cw ? W : nullptr, n_w, 1, pmax, &nblocks, s)))
+    return rc;
   // 2. gradient codes in the layouts the two products read
   {
-    RelayoutIo io{pmax, nblocks, 0, pmax_own, ctr, nullptr, st, dX ? g_npqk : nullptr,
-                  dW ? g_kpqn : nullptr};
-    const bool side = want_cw && fused_g;
-    if ((rc = launch_quantize_relayout_grad(dY, g.N, g.K, PQ, io, seed, rounding, sync_x, sync_w,
-                                            side ? W : nullptr, n_w, &sc->c_w, &sc->bad_w, s)))
-      return rc;
+    RelayoutIo io{pmax, nblocks, 0, st, dX ? g_npqk : nullptr, dW ? g_kpqn : nullptr};
+    if ((rc = launch_quantize_relayout_grad(dY, g.N, g.K, PQ, io, seed, rounding, s))) return rc;
   }
   // 3. activation codes
   if (dW) {
-    RelayoutIo io{pmax, nblocks, 1, pmax_own, ctr, sync_x, st, nullptr, x_chwn};
-    if ((rc = launch_quantize_relayout_operand(X, g.N, g.C, HW, io, c_x, nullptr, x_unsigned,
-                                               &sc->c_x, &sc->bad_x, s)))
+    RelayoutIo io{pmax, nblocks, 1, st, nullptr, x_chwn};
+    if ((rc = launch_quantize_relayout_operand(X, g.N, g.C, HW, io, c_x, x_unsigned, &sc->c_x,
+                                               &sc->bad_x, s)))
       return rc;
   }
   // 4. weight codes, then the two products
   if (dX) {
-    RelayoutIo io{pmax, nblocks, 2, pmax_own, ctr, sync_w, st, w_is_ck ? w_crsk : nullptr,
-                  w_is_ck ? nullptr : w_crsk};
-    const float* c_ptr = (want_cw && fused_g) ? &sc->c_w : nullptr;
-    if ((rc = launch_quantize_relayout_operand(W, wA, wB, wL, io, c_w, c_ptr, 0, &sc->c_w,
-                                               c_ptr ? nullptr : &sc->bad_w, s)))
+    RelayoutIo io{pmax, nblocks, 2, st, w_is_ck ? w_crsk : nullptr, w_is_ck ? nullptr : w_crsk};
+    if ((rc = launch_quantize_relayout_operand(W, wA, wB, wL, io, c_w, 0, &sc->c_w, &sc->bad_w, s)))
       return rc;
     rc = w_is_ck ? launch_linear_dx(g, w_crsk, g_npqk, st, sc, dX, acc_dX, s)
                  : launch_conv_dx(g, w_crsk, g_npqk, st, sc, dX, acc_dX, s);
@@ -211,7 +190,7 @@ int lbt_quantize_grad(const float* g, int64_t n, lbt_grad_state* st, uint64_t se
   if (ws_bytes < lbt_workspace_bytes_quantize(n)) return LBT_ERR_WORKSPACE;
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   uint32_t* pmax =
-      reinterpret_cast<uint32_t*>(static_cast<uint8_t*>(ws) + kWsBarrierBytes + kWsScalarsBytes);
+      reinterpret_cast<uint32_t*>(static_cast<uint8_t*>(ws) + kWsScalarsBytes);
   int rc, nblocks = 0;
   if ((rc = launch_absmax3(g, n, 1, nullptr, 0, 0, nullptr, 0, 0, pmax, &nblocks, s))) return rc;
   return launch_quantize_flat_grad(g, n, pmax, nblocks, st, seed, rounding, codes, s);
@@ -226,10 +205,9 @@ int lbt_quantize_operand(const float* x, int64_t n, float c, int is_unsigned, in
   if (!aligned(x, 16) || !aligned(codes, 4) || !aligned(ws, 256)) return LBT_ERR_ALIGN;
   if (ws_bytes < lbt_workspace_bytes_quantize(n)) return LBT_ERR_WORKSPACE;
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-  OperandScalars* sc =
-      reinterpret_cast<OperandScalars*>(static_cast<uint8_t*>(ws) + kWsBarrierBytes);
+  OperandScalars* sc = static_cast<OperandScalars*>(ws);
   uint32_t* pmax =
-      reinterpret_cast<uint32_t*>(static_cast<uint8_t*>(ws) + kWsBarrierBytes + kWsScalarsBytes);
+      reinterpret_cast<uint32_t*>(static_cast<uint8_t*>(ws) + kWsScalarsBytes);
   int rc, nblocks = 0;
   if (!(c > 0.0f))
     if ((rc = launch_absmax3(nullptr, 0, 0, x, n, is_unsigned ? 0 : 1, nullptr, 0, 0, pmax, &nblocks,

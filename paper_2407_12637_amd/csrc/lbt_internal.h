@@ -27,10 +27,8 @@ inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 struct OperandScalars {
   float c_x;       // clip value actually used for X
   float c_w;       // ... for W
-  uint32_t bad_x;  // bit 0: operand maximum was Inf/NaN; bit 1: internal barrier timed out
+  uint32_t bad_x;  // operand maximum was Inf/NaN
   uint32_t bad_w;
-  unsigned long long sync_x;  // finish tickets of the fused operand quantizers; cleared by the
-  unsigned long long sync_w;  // gradient quantizer, which always runs first
 };
 
 // ---- profile.hip: optional event timing of every launch ------------------------
@@ -56,14 +54,9 @@ class ProfScope {
 
 // ---- quantize.hip -------------------------------------------------------------
 constexpr int kMaxPartialBlocks = 2048;  // partial-maximum slots in the workspace header
-// Workspace header: 16 grid-barrier counters 256 bytes apart (the caller hands the
-// workspace over zero-filled and the library leaves these zero after every call), then
-// OperandScalars (256 bytes), pmax[kMaxPartialBlocks][4] uint32 for launch_absmax3, and
-// [kMaxPartialBlocks][2] uint32 for the fused quantizers.
-constexpr size_t kWsBarrierBytes = 16 * 256;
+// Workspace header: OperandScalars (256 bytes), then pmax[kMaxPartialBlocks][4] uint32.
 constexpr size_t kWsScalarsBytes = 256;
-constexpr size_t kWsHeaderBytes =
-    kWsBarrierBytes + kWsScalarsBytes + (size_t)kMaxPartialBlocks * (16 + 8);
+constexpr size_t kWsHeaderBytes = kWsScalarsBytes + (size_t)kMaxPartialBlocks * 16;
 
 // One launch for the maxima of up to three tensors (null pointer = absent); partial
 // maxima go to pmax[block][tensor].  *nblocks_out = number of partial rows written.
@@ -78,34 +71,23 @@ int launch_quantize_flat_operand(const float* x, int64_t n, float c_given, const
                                  float* clip_scale_out, hipStream_t s);
 // Quantize T[A][B][L] (L contiguous) into GEMM layouts of 8-byte granules (16 codes):
 // out_b [A][ceil(B/16)][L][16] and out_a [B][ceil(A/16)][L][16] (either may be null).
-// Shapes for which relayout_is_fused() holds run as ONE kernel that also finds the
-// tensor maximum (grid barrier); the others need launch_absmax3 first (pmax/nblocks).
+// The tensor maximum, where needed, comes from the partial maxima of launch_absmax3.
 struct RelayoutIo {
-  const uint32_t* pmax;      // two-kernel path: partial maxima from launch_absmax3
+  const uint32_t* pmax;
   int nblocks;
   int pmax_col;
-  uint32_t* pmax_own;        // fused path: scratch for kMaxPartialBlocks x 2 partial maxima
-  unsigned long long* ctr;   // fused path: 16 barrier counters, 256 bytes apart, zero on entry
-  unsigned long long* sync;  // fused operand path: finish ticket (zero on entry)
   lbt_grad_state* st;
   uint8_t* out_b;
   uint8_t* out_a;
 };
-bool relayout_is_fused(const float* x, int64_t A, int64_t B, int64_t L);
-// Gradient flavour: clip value from gamma in *st and the tensor maximum; statistics go to
-// *st.  clear0/clear1: words it zeroes (barrier words of the operand kernels that follow).
-// side_x: optional small tensor whose max |.| it also computes (fused path only) and
-// writes to *side_c_out.
+// Gradient flavour: clip value from gamma in *st and the maximum; statistics go to *st.
 int launch_quantize_relayout_grad(const float* g, int64_t A, int64_t B, int64_t L,
                                   const RelayoutIo& io, uint64_t seed, int rounding,
-                                  unsigned long long* clear0, unsigned long long* clear1,
-                                  const float* side_x, int64_t side_n, float* side_c_out,
-                                  uint32_t* side_bad_out, hipStream_t s);
-// Operand flavour: clip value c_given (> 0), else *c_ptr, else the tensor maximum.
+                                  hipStream_t s);
+// Operand flavour: clip value c_given (> 0), else the tensor maximum; written to *c_out.
 int launch_quantize_relayout_operand(const float* x, int64_t A, int64_t B, int64_t L,
-                                     const RelayoutIo& io, float c_given, const float* c_ptr,
-                                     int is_unsigned, float* c_out, uint32_t* bad_out,
-                                     hipStream_t s);
+                                     const RelayoutIo& io, float c_given, int is_unsigned,
+                                     float* c_out, uint32_t* bad_out, hipStream_t s);
 int launch_update_interval(lbt_grad_state* st, hipStream_t s);
 int launch_state_init(lbt_grad_state* st, const lbt_grad_state& v, hipStream_t s);
 

@@ -10,14 +10,13 @@
 //   code   = rint(t)  |  (floor(t * 2^16) + r16) >> 16   (16 fractional bits)
 //   code   = clamp(code, -q or 0, q)
 //
-// Synchronisation between kernels uses no zero-initialised scratch: the maximum
-// pass writes one partial maximum per workgroup, the quantizer re-reduces those
-// partials in its prologue, and the clip-out count travels in ONE 64-bit atomic
-// per workgroup (count in the low 40 bits, arrival ticket above) on a word of the
-// layer state that the last workgroup resets to zero.
-#include <map>
-#include <mutex>
-
+// A tensor is swept twice: k_absmax3 takes the maxima of up to three tensors in one
+// launch (one partial maximum per workgroup, no atomics), then a quantizer kernel
+// re-reduces those partials in its prologue and streams the tensor once more (the
+// second read mostly hits the memory-side cache).  The clip-out count travels in ONE
+// 64-bit atomic per workgroup (count in the low 40 bits, arrival ticket above) on a
+// word of the layer state that the last workgroup resets to zero; no scratch memory
+// has to be zero-initialised by anyone.
 #include "lbt_internal.h"
 
 namespace lbt {
@@ -184,19 +183,14 @@ __device__ __forceinline__ GradSetup grad_setup(const lbt_grad_state* st, const 
 
 // One atomic per workgroup carries the clip-out count and the arrival ticket; the
 // last workgroup to arrive publishes the statistics and clears the word.
-// The last workgroup also clears the grid-barrier counters `ctr` if the kernel used them.
 __device__ __forceinline__ void grad_finish(lbt_grad_state* st, const GradSetup& g, uint32_t cnt,
-                                            unsigned long long n_total, unsigned long long* ctr) {
+                                            unsigned long long n_total) {
   const uint32_t tot = block_sum(cnt);
   if (threadIdx.x == 0) {
     const unsigned long long nblk = (unsigned long long)gridDim.x * gridDim.y * gridDim.z;
     const unsigned long long old =
         atomicAdd(reinterpret_cast<unsigned long long*>(&st->sync_word), kTicket + tot);
     if ((old >> 40) == nblk - 1) {
-      if (ctr) {
-#pragma unroll
-        for (int j = 0; j < 16; ++j) ctr[j * 32] = 0;
-      }
       st->n_out = (old + tot) & kCountMask;
       st->n_total = n_total;
       st->gmax = g.gmax;
@@ -359,7 +353,7 @@ __global__ __launch_bounds__(kThreads) void k_quantize_flat(
       for (int j = 0; j < nbytes; ++j) codes[gi * 4 + j] = (uint8_t)(word >> (8 * j));
     }
   }
-  if (kGrad) grad_finish(st, gs, cnt, (unsigned long long)n, nullptr);
+  if (kGrad) grad_finish(st, gs, cnt, (unsigned long long)n);
 }
 
 // ---------------------------------------------------------------------------
@@ -375,33 +369,22 @@ struct TileArgs {
   const float* x;
   int A, B, L;
   int AG, BG;
-  // clip value: c_given if > 0, else *c_ptr if c_ptr, else the tensor maximum
+  // clip value: c_given if > 0, else *c_ptr if c_ptr, else the tensor maximum (pmax)
   float c_given;
   const float* c_ptr;
-  // two-kernel path: partial maxima left by k_absmax3
-  const uint32_t* pmax;
+  const uint32_t* pmax;  // partial maxima left by k_absmax3
   int nblocks;
   int pmax_col;
-  // fused path: this kernel's own partial maxima [gridDim.x][2] and its barrier word
-  uint32_t* pmax_own;
-  unsigned long long* ctr;     // grid-barrier arrival counters (zero on entry)
-  unsigned long long* sync;    // operand kernels: finish ticket (zero on entry)
-  unsigned long long* clear0;  // finish tickets of later kernels, cleared by the gradient kernel
-  unsigned long long* clear1;
   lbt_grad_state* st;
   unsigned long long seed;
   float* c_out;
   uint32_t* bad_out;
   uint2* out_b;
   uint2* out_a;
-  // fused gradient kernel, side job: max |.| of a second, small tensor (the weights)
-  const float* side_x;
-  long long side_n;
-  float* side_c_out;
-  uint32_t* side_bad_out;
 };
 
 // Phase B: gather granules out of the LDS tile.  `pitch` = bytes per (a,b) row.
+// Byte-wise version (any tile length): one LDS byte read per code.
 __device__ __forceinline__ void store_granules(const TileArgs& t, const uint8_t* tile, int pitch,
                                                int tl, int a0, int b0, int l0) {
   const int n_items = 16 * tl;
@@ -435,230 +418,166 @@ __device__ __forceinline__ void store_granules(const TileArgs& t, const uint8_t*
   }
 }
 
+// Word-wise version for tile lengths that are multiples of 4: a thread takes the 16 LDS
+// words that hold four consecutive l of the sixteen rows of one granule column, merges
+// row pairs into bytes (two nibbles) and transposes 8 x 4 bytes with byte permutes,
+// producing the four granules l .. l+3 (32 contiguous bytes of output).
+//   base: LDS byte offset of row 0 of the group; stride: bytes between its rows
+__device__ __forceinline__ void granules4(const uint8_t* tile, int base, int stride, uint2 out[4]) {
+  uint32_t d[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const uint32_t lo = *reinterpret_cast<const uint32_t*>(tile + base + (2 * j) * stride);
+    const uint32_t hi = *reinterpret_cast<const uint32_t*>(tile + base + (2 * j + 1) * stride);
+    d[j] = lo | (hi << 4);  // byte i: rows 2j (low nibble) and 2j+1 (high nibble) at l + i
+  }
+  // __builtin_amdgcn_perm(hi, lo, sel): result byte k = byte sel[k] of the 8-byte {hi:lo}
+  uint32_t p01[2], p23[2], p45[2], p67[2];
+  p01[0] = __builtin_amdgcn_perm(d[1], d[0], 0x05010400u);  // [d0.b0, d1.b0, d0.b1, d1.b1]
+  p01[1] = __builtin_amdgcn_perm(d[1], d[0], 0x07030602u);  // [d0.b2, d1.b2, d0.b3, d1.b3]
+  p23[0] = __builtin_amdgcn_perm(d[3], d[2], 0x05010400u);
+  p23[1] = __builtin_amdgcn_perm(d[3], d[2], 0x07030602u);
+  p45[0] = __builtin_amdgcn_perm(d[5], d[4], 0x05010400u);
+  p45[1] = __builtin_amdgcn_perm(d[5], d[4], 0x07030602u);
+  p67[0] = __builtin_amdgcn_perm(d[7], d[6], 0x05010400u);
+  p67[1] = __builtin_amdgcn_perm(d[7], d[6], 0x07030602u);
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    // l + 2h uses the low halves of the pair words, l + 2h + 1 the high halves
+    out[2 * h].x = __builtin_amdgcn_perm(p23[h], p01[h], 0x05040100u);
+    out[2 * h].y = __builtin_amdgcn_perm(p67[h], p45[h], 0x05040100u);
+    out[2 * h + 1].x = __builtin_amdgcn_perm(p23[h], p01[h], 0x07060302u);
+    out[2 * h + 1].y = __builtin_amdgcn_perm(p67[h], p45[h], 0x07060302u);
+  }
+}
+
+__device__ __forceinline__ void store_granules_w4(const TileArgs& t, const uint8_t* tile, int pitch,
+                                                  int tl, int a0, int b0, int l0) {
+  const int quads = tl >> 2, n_items = 16 * quads;
+  if (t.out_b) {
+    const int bg = b0 >> 4;
+    for (int it = threadIdx.x; it < n_items; it += blockDim.x) {
+      const int a = it / quads, l = (it - a * quads) * 4;
+      if (a0 + a >= t.A) continue;
+      uint2 g4[4];
+      granules4(tile, (a * 16) * pitch + l, pitch, g4);
+      uint2* dst = t.out_b + ((long long)(a0 + a) * t.BG + bg) * t.L + l0 + l;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) dst[i] = g4[i];
+    }
+  }
+  if (t.out_a) {
+    const int ag = a0 >> 4;
+    for (int it = threadIdx.x; it < n_items; it += blockDim.x) {
+      const int b = it / quads, l = (it - b * quads) * 4;
+      if (b0 + b >= t.B) continue;
+      uint2 g4[4];
+      granules4(tile, b * pitch + l, 16 * pitch, g4);
+      uint2* dst = t.out_a + ((long long)(b0 + b) * t.AG + ag) * t.L + l0 + l;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) dst[i] = g4[i];
+    }
+  }
+}
+
 // ---------------------------------------------------------------------------
-// Fused single-sweep quantizer.  The grid is sized to be resident all at once.
-// Phase 1: every workgroup reads its tiles, keeps the first R of them in registers
-// and publishes the maximum of what it read at a grid-wide barrier (bounded spin).
-// Phase 2: every workgroup reduces the partial maxima to g_max, derives the clip
-// value and quantizes its tiles -- from registers where it kept them, by
-// re-reading (L2 / memory-side cache) where it did not.
-//   large tiles (SMALL = false): 16 x 16 x 64 window of l, L % 8 == 0
-//   small tiles (SMALL = true):  16 x 16 x L with B % 16 == 0 and (B*L) % 8 == 0;
+// Streaming tile quantizer: one 16(a) x 16(b) x window(l) tile per workgroup.
+//   windowed tiles (SMALL = false): L % 4 == 0, window_len(L) <= 64 elements of l;
+//   whole-row tiles (SMALL = true): 16 x 16 x L with B % 16 == 0 and (B*L) % 8 == 0;
 //     for one a the sixteen rows are contiguous (16*L floats) and are read as
 //     8-element groups that may straddle rows.
-// A thread owns up to 8 groups of 8 consecutive elements per tile.
+// One work item = one aligned block of 8 consecutive elements (the unit of the random
+// number generator), as two halves of 4.  In a windowed tile a half can fall outside
+// the window or the row; such a half is not read and not written.
 // ---------------------------------------------------------------------------
-constexpr int kSpinLimit = 1 << 22;
-constexpr int kBarrierSlots = 16;    // arrival counters, one per 256 bytes (different channels)
-constexpr int kBarrierStride = 32;   // in 64-bit words
-
-// Grid barrier that also publishes two 32-bit values per workgroup.  No memory
-// fence is used (a device-scope fence costs tens of ns per workgroup and those
-// costs add up serially): the values are written with device-scope atomic
-// exchanges whose results are awaited, then the arrival is counted on one of 16
-// counters; readers use device-scope loads.  Returns false on time-out (never
-// expected: the grid is resident).  The counters must be zero on entry and are
-// cleared again by the last workgroup to finish the kernel.
-__device__ __forceinline__ bool grid_barrier_publish(unsigned long long* ctr, uint32_t* slot,
-                                                     uint32_t v0, uint32_t v1, unsigned nblocks) {
-  __shared__ int ok_flag;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    const uint32_t o0 = atomicExch(slot, v0);
-    const uint32_t o1 = atomicExch(slot + 1, v1);
-    // the arrival is issued only after both exchanges have returned their old values
-    asm volatile("" : : "v"(o0), "v"(o1) : "memory");
-    atomicAdd(&ctr[(blockIdx.x % kBarrierSlots) * kBarrierStride], 1ull);
-    int ok = 0;
-    for (int spin = 0; spin < kSpinLimit; ++spin) {
-      unsigned long long arrived = 0;
-#pragma unroll
-      for (int j = 0; j < kBarrierSlots; ++j)
-        arrived += __hip_atomic_load(&ctr[j * kBarrierStride], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if (arrived >= nblocks) { ok = 1; break; }
-      __builtin_amdgcn_s_sleep(4);
-    }
-    ok_flag = ok;
-  }
-  __syncthreads();
-  return ok_flag != 0;
-}
-
-__device__ __forceinline__ void barrier_reset(unsigned long long* ctr) {
-#pragma unroll
-  for (int j = 0; j < kBarrierSlots; ++j) ctr[j * kBarrierStride] = 0;
-}
-
 struct ItemPos {
-  long long e0;   // flat index of the first of the 8 elements
-  int row, l;     // large: LDS row (a*16+b) and l within the window; small: a and group j
-  bool valid;
+  long long e0;    // flat index of the block's first element (a multiple of 8)
+  int row;         // windowed: LDS row a*16+b; whole-row: a
+  int off;         // windowed: LDS byte offset of the first half inside the row (may be < 0
+                   //           when that half is invalid); whole-row: group index j
+  bool v0, v1;     // halves to read and quantize
+  bool z0, z1;     // halves to zero-fill in LDS (padding rows)
 };
 
-template <bool SMALL, int THREADS>
-__device__ __forceinline__ ItemPos item_pos(const TileArgs& t, int a0, int b0, int l0, int i) {
+template <bool SMALL>
+__device__ __forceinline__ ItemPos item_pos(const TileArgs& t, int a0, int b0, int l0, int tl,
+                                            int it) {
   ItemPos p;
-  const int it = threadIdx.x + THREADS * i;
   if (SMALL) {
     const int octs = 2 * t.L;
     const int a = it / octs, j = it - a * octs;
     p.row = a;
-    p.l = j;
-    p.valid = (a < 16) && (a0 + a < t.A);
+    p.off = j;
+    p.v0 = p.v1 = (a < 16) && (a0 + a < t.A);
+    p.z0 = p.z1 = (a < 16) && !p.v0;
     p.e0 = ((long long)(a0 + a) * t.B + b0) * t.L + 8 * j;
   } else {
-    const int row = it >> 3, oct = it & 7;
-    const int ga = a0 + (row >> 4), gb = b0 + (row & 15), gl = l0 + oct * 8;
+    const int row = it >> 3, j = it & 7;
+    const int ga = a0 + (row >> 4), gb = b0 + (row & 15);
+    const bool row_ok = ga < t.A && gb < t.B;
+    // padding rows are zero-filled with the block pattern of a row that starts at 0
+    const long long e_row = row_ok ? ((long long)ga * t.B + gb) * t.L : 0;
+    const int l_end = min(l0 + tl, t.L);
+    p.e0 = (((e_row + l0) >> 3) + j) << 3;
+    const int lq0 = (int)(p.e0 - e_row), lq1 = lq0 + 4;
+    const bool in0 = lq0 >= l0 && lq0 + 4 <= l_end, in1 = lq1 >= l0 && lq1 + 4 <= l_end;
     p.row = row;
-    p.l = oct * 8;
-    p.valid = ga < t.A && gb < t.B && gl < t.L;
-    p.e0 = ((long long)ga * t.B + gb) * t.L + gl;
+    p.off = lq0 - l0;
+    p.v0 = row_ok && in0;
+    p.v1 = row_ok && in1;
+    p.z0 = !row_ok && in0;
+    p.z1 = !row_ok && in1;
   }
   return p;
 }
 
-__device__ __forceinline__ void load8(const float* x, long long e0, float v[8]) {
-  const float4 p = *reinterpret_cast<const float4*>(x + e0);
-  const float4 q = *reinterpret_cast<const float4*>(x + e0 + 4);
-  v[0] = p.x; v[1] = p.y; v[2] = p.z; v[3] = p.w;
-  v[4] = q.x; v[5] = q.y; v[6] = q.z; v[7] = q.w;
+// Both halves are always loaded (an invalid half reads elements 0..3 and is ignored), so
+// that no branch separates the loads of different items.
+__device__ __forceinline__ void load8(const float* x, const ItemPos& p, float v[8]) {
+  const float4 lo = *reinterpret_cast<const float4*>(x + (p.v0 ? p.e0 : 0));
+  const float4 hi = *reinterpret_cast<const float4*>(x + (p.v1 ? p.e0 + 4 : 0));
+  v[0] = lo.x; v[1] = lo.y; v[2] = lo.z; v[3] = lo.w;
+  v[4] = hi.x; v[5] = hi.y; v[6] = hi.z; v[7] = hi.w;
 }
 
-__device__ __forceinline__ uint32_t max_key8(const float v[8], int use_abs) {
-  uint32_t m = 0;
-#pragma unroll
-  for (int u = 0; u < 8; ++u) m = max(m, max_key(v[u], use_abs));
-  return m;
+// Window length along l of the windowed tiles: a multiple of 4 (of 8 when rows start on
+// multiples of 8) such that a row window overlaps at most 8 generator blocks.
+__host__ __device__ inline int window_len(int L) {
+  const int cap = (L % 8 == 0) ? 64 : 56;
+  const int nw = (L + cap - 1) / cap;
+  const int per = (L + nw - 1) / nw;
+  return (L % 8 == 0) ? (per + 7) / 8 * 8 : (per + 3) / 4 * 4;
 }
 
-template <int MODE, int THREADS, int R, bool SMALL>
-__global__ __launch_bounds__(THREADS) void k_quantize_fused(const TileArgs t, int pitch) {
+template <int MODE, bool SMALL>
+__global__ __launch_bounds__(kThreads) void k_quantize_stream(const TileArgs t, int pitch, int tl) {
   extern __shared__ __attribute__((aligned(8))) uint8_t dyn_tile[];
   constexpr bool kGrad = MODE >= 2;
-  constexpr int kUseAbs = (MODE == 1) ? 0 : 1;
-  const int G = gridDim.x, bid = blockIdx.x;
-  const int tiles_l = SMALL ? 1 : (t.L + 63) / 64;
-  const int tiles = tiles_l * t.BG * t.AG;
-  const int tl = SMALL ? t.L : 64;
-  const bool need_max = kGrad || (!(t.c_given > 0.0f) && !t.c_ptr);
-  if (kGrad && bid == 0 && threadIdx.x == 0) {
-    if (t.clear0) *t.clear0 = 0;
-    if (t.clear1) *t.clear1 = 0;
-  }
-  auto tile_origin = [&](int tile_id, int& a0, int& b0, int& l0) {
-    const int lt = tile_id % tiles_l, rest = tile_id / tiles_l;
-    l0 = lt * 64;
-    b0 = (rest % t.BG) * 16;
-    a0 = (rest / t.BG) * 16;
-  };
-
-  // ---- phase 1: read, keep, maximum ------------------------------------------------
-  float cache[R][8][8];
-  uint32_t bits = 0, side_bits = 0;
-  bool poisoned = false;
-  if (need_max) {
-    uint32_t m = 0, m_side = 0;
-    // All loads of the kept tiles are issued before any value is used (invalid items
-    // read element 0 and are ignored), so a thread has up to 2*8*R requests in flight.
-    bool ok[R][8];
-#pragma unroll
-    for (int k = 0; k < R; ++k) {
-      const int tile_id = bid + k * G;
-      int a0, b0, l0;
-      tile_origin(tile_id < tiles ? tile_id : 0, a0, b0, l0);
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const ItemPos p = item_pos<SMALL, THREADS>(t, a0, b0, l0, i);
-        ok[k][i] = p.valid && tile_id < tiles;
-        load8(t.x, ok[k][i] ? p.e0 : 0, cache[k][i]);
-      }
-    }
-#pragma unroll
-    for (int k = 0; k < R; ++k)
-#pragma unroll
-      for (int i = 0; i < 8; ++i)
-        if (ok[k][i]) m = max(m, max_key8(cache[k][i], kUseAbs));
-    for (int k = R; bid + k * G < tiles; ++k) {
-      int a0, b0, l0;
-      tile_origin(bid + k * G, a0, b0, l0);
-      float v[8][8];
-      bool okv[8];
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const ItemPos p = item_pos<SMALL, THREADS>(t, a0, b0, l0, i);
-        okv[i] = p.valid;
-        load8(t.x, p.valid ? p.e0 : 0, v[i]);
-      }
-#pragma unroll
-      for (int i = 0; i < 8; ++i)
-        if (okv[i]) m = max(m, max_key8(v[i], kUseAbs));
-    }
-    if (kGrad && t.side_x) {
-      for (long long i = (long long)bid * THREADS + threadIdx.x; i < t.side_n; i += (long long)G * THREADS)
-        m_side = max(m_side, max_key(t.side_x[i], 1));
-      m_side = block_max(m_side);
-    }
-    m = block_max(m);
-    poisoned = !grid_barrier_publish(t.ctr, t.pmax_own + 2 * bid, m, m_side, (unsigned)G);
-    uint32_t mm = 0, ms = 0;
-    for (int i = threadIdx.x; i < G; i += THREADS) {
-      // device-scope loads: the values were written by workgroups on other dies
-      mm = max(mm, __hip_atomic_load(&t.pmax_own[2 * i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-      ms = max(ms, __hip_atomic_load(&t.pmax_own[2 * i + 1], __ATOMIC_RELAXED,
-                                     __HIP_MEMORY_SCOPE_AGENT));
-    }
-    bits = block_max(mm);
-    if (kGrad && t.side_x) side_bits = block_max(ms);
-  }
-
-  // ---- clip value ----------------------------------------------------------------------
   GradSetup gs{};
   float c;
   if (kGrad) {
-    gs.gmax = __uint_as_float(bits);
-    gs.c = 0.0f;
-    if (bits >= kInfBits) gs.status = LBT_STATUS_NONFINITE;
-    else if (bits == 0) gs.status = LBT_STATUS_ZERO_GRAD;
-    else {
-      gs.status = LBT_STATUS_OK;
-      gs.c = (float)__dmul_rn(t.st->gamma, (double)gs.gmax);
-    }
-    if (t.side_x && side_bits >= kInfBits && gs.status == LBT_STATUS_OK)
-      gs.status = LBT_STATUS_NONFINITE;  // non-finite weights
-    if (poisoned) gs.status = LBT_STATUS_INTERNAL;
+    gs = grad_setup(t.st, t.pmax, t.nblocks);
     c = gs.c;
-    if (t.side_x && bid == 0 && threadIdx.x == 0) {
-      const bool bad = side_bits >= kInfBits;
-      *t.side_c_out = bad ? 0.0f : __uint_as_float(side_bits);
-      *t.side_bad_out = bad ? 1u : 0u;
-    }
+  } else if (!(t.c_given > 0.0f) && t.c_ptr) {
+    c = *t.c_ptr;
   } else {
-    bool bad = false;
-    c = t.c_given;
-    if (!(c > 0.0f)) {
-      if (t.c_ptr) c = *t.c_ptr;
-      else if (bits >= kInfBits) { bad = true; c = 0.0f; }
-      else c = __uint_as_float(bits);
-    }
-    if (bid == 0 && threadIdx.x == 0) {
-      if (t.c_out) *t.c_out = c;
-      if (t.bad_out) *t.bad_out = (bad ? 1u : 0u) | (poisoned ? 2u : 0u);
-      if (bad && t.st) t.st->status = LBT_STATUS_NONFINITE;
-    }
+    c = operand_setup(t.c_given, t.pmax, t.nblocks, t.pmax_col, MODE == 1, t.c_out, t.bad_out, t.st,
+                      nullptr);
   }
   const QConst qc = make_qconst(c, MODE == 1);
   const bool live = c > 0.0f;
   const unsigned long long step = (MODE == 3) ? t.st->step : 0ull;
+  const int l0 = blockIdx.x * tl, b0 = blockIdx.y * 16, a0 = blockIdx.z * 16;
 
-  // ---- phase 2: quantize tile by tile --------------------------------------------------
   uint32_t cnt = 0;
-  auto quantize_item = [&](const ItemPos& p, const float v[8], bool have) {
-    // eight codes of one group -> LDS bytes
+  auto quantize_item = [&](const ItemPos& p, const float v[8]) {
+    // eight codes of one generator block -> LDS bytes
+    Philox4 rnd{};
+    if (MODE == 3 && live) rnd = philox_block((unsigned long long)p.e0 >> 3, step, t.seed);
     if (SMALL) {
       if (p.row >= 16) return;  // beyond the tile's groups
-      int b = (8 * p.l) / t.L, l = 8 * p.l - b * t.L;
-      Philox4 rnd{};
-      if (MODE == 3 && have) rnd = philox_block((unsigned long long)p.e0 >> 3, step, t.seed);
+      int b = (8 * p.off) / t.L, l = 8 * p.off - b * t.L;
+      const bool have = p.v0 && live;
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
         int k = 0;
@@ -668,69 +587,40 @@ __global__ __launch_bounds__(THREADS) void k_quantize_fused(const TileArgs t, in
       }
     } else {
       uint32_t w0 = 0, w1 = 0;
-      if (have) {
-        Philox4 rnd{};
-        if (MODE == 3) rnd = philox_block((unsigned long long)p.e0 >> 3, step, t.seed);
+      if (live) {
+        if (p.v0) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          w0 |= ((uint32_t)quantize_one<MODE>(v[u], qc, rnd, u, cnt) & 0xFu) << (8 * u);
-          w1 |= ((uint32_t)quantize_one<MODE>(v[4 + u], qc, rnd, 4 + u, cnt) & 0xFu) << (8 * u);
+          for (int u = 0; u < 4; ++u)
+            w0 |= ((uint32_t)quantize_one<MODE>(v[u], qc, rnd, u, cnt) & 0xFu) << (8 * u);
+        }
+        if (p.v1) {
+#pragma unroll
+          for (int u = 0; u < 4; ++u)
+            w1 |= ((uint32_t)quantize_one<MODE>(v[4 + u], qc, rnd, 4 + u, cnt) & 0xFu) << (8 * u);
         }
       }
-      *reinterpret_cast<uint2*>(dyn_tile + p.row * pitch + p.l) = make_uint2(w0, w1);
+      uint8_t* dst = dyn_tile + p.row * pitch + p.off;
+      if (p.v0 || p.z0) *reinterpret_cast<uint32_t*>(dst) = w0;
+      if (p.v1 || p.z1) *reinterpret_cast<uint32_t*>(dst + 4) = w1;
     }
   };
-  auto finish_tile = [&](int a0, int b0, int l0) {
-    __syncthreads();
-    store_granules(t, dyn_tile, pitch, tl, a0, b0, l0);
-    __syncthreads();
-  };
-
-  auto reload_tile = [&](int a0, int b0, int l0) {
-    float v[8][8];
-    ItemPos p[8];
+  // items in batches of four: the eight loads of a batch are in flight together
+  const int n_items = SMALL ? 32 * t.L : 8 * kThreads;
+  for (int base = 0; base < n_items; base += 4 * kThreads) {
+    float v[4][8];
+    ItemPos p[4];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      p[i] = item_pos<SMALL, THREADS>(t, a0, b0, l0, i);
-      load8(t.x, p[i].valid ? p[i].e0 : 0, v[i]);
+    for (int i = 0; i < 4; ++i) {
+      p[i] = item_pos<SMALL>(t, a0, b0, l0, tl, base + i * kThreads + threadIdx.x);
+      if (live) load8(t.x, p[i], v[i]);
     }
 #pragma unroll
-    for (int i = 0; i < 8; ++i) quantize_item(p[i], v[i], p[i].valid && live);
-    finish_tile(a0, b0, l0);
-  };
-#pragma unroll
-  for (int k = 0; k < R; ++k) {
-    const int tile_id = bid + k * G;
-    if (tile_id < tiles) {
-      int a0, b0, l0;
-      tile_origin(tile_id, a0, b0, l0);
-      if (need_max) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          const ItemPos p = item_pos<SMALL, THREADS>(t, a0, b0, l0, i);
-          quantize_item(p, cache[k][i], p.valid && live);
-        }
-        finish_tile(a0, b0, l0);
-      } else {
-        reload_tile(a0, b0, l0);
-      }
-    }
+    for (int i = 0; i < 4; ++i) quantize_item(p[i], v[i]);
   }
-  for (int k = R; bid + k * G < tiles; ++k) {
-    int a0, b0, l0;
-    tile_origin(bid + k * G, a0, b0, l0);
-    reload_tile(a0, b0, l0);
-  }
-  if (kGrad) {
-    grad_finish(t.st, gs, cnt, (unsigned long long)t.A * t.B * t.L, t.ctr);
-  } else if (need_max && threadIdx.x == 0) {
-    // last workgroup out clears the barrier counters for the next kernel
-    const unsigned long long old = atomicAdd(t.sync, 1ull);
-    if (old == (unsigned long long)G - 1) {
-      barrier_reset(t.ctr);
-      *t.sync = 0;
-    }
-  }
+  __syncthreads();
+  if (SMALL) store_granules(t, dyn_tile, pitch, t.L, a0, b0, 0);
+  else store_granules_w4(t, dyn_tile, pitch, min(tl, t.L - l0), a0, b0, l0);
+  if (kGrad) grad_finish(t.st, gs, cnt, (unsigned long long)t.A * t.B * t.L);
 }
 
 // ---------------------------------------------------------------------------
@@ -756,11 +646,6 @@ __global__ __launch_bounds__(kThreads) void k_quantize_tile_generic(const TileAr
   const bool live = c > 0.0f;
   const unsigned long long step = (MODE == 3) ? t.st->step : 0ull;
   const int l0 = blockIdx.x * TL, b0 = blockIdx.y * 16, a0 = blockIdx.z * 16;
-  if (MODE >= 2 && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0) {
-    if (t.clear0) *t.clear0 = 0;
-    if (t.clear1) *t.clear1 = 0;
-  }
-
   uint32_t cnt = 0;
   for (int idx = threadIdx.x; idx < 256 * TL; idx += kThreads) {
     const int l = idx % TL, row = idx / TL;
@@ -776,7 +661,7 @@ __global__ __launch_bounds__(kThreads) void k_quantize_tile_generic(const TileAr
   }
   __syncthreads();
   store_granules(t, tile, PITCH, TL, a0, b0, l0);
-  if (MODE >= 2) grad_finish(t.st, gs, cnt, (unsigned long long)t.A * t.B * t.L, nullptr);
+  if (MODE >= 2) grad_finish(t.st, gs, cnt, (unsigned long long)t.A * t.B * t.L);
 }
 
 inline int flat_grid(long long work_items) {
@@ -787,81 +672,41 @@ inline int flat_grid(long long work_items) {
   return (int)blocks;
 }
 
-enum FusedKind { kNotFused = 0, kFusedLarge, kFusedSmall256, kFusedSmall1024 };
+enum TileKind { kGenericTile = 0, kWindowed, kWholeRow };
 
-FusedKind fused_kind(const float* x, long long A, long long B, long long L) {
-  (void)A;
-  if (reinterpret_cast<uintptr_t>(x) % 16 != 0) return kNotFused;
-  if (L >= 64 && L % 8 == 0) return kFusedLarge;
-  if (L >= 2 && L <= 248 && B % 16 == 0 && (B * L) % 8 == 0)
-    return L <= 64 ? kFusedSmall256 : kFusedSmall1024;
-  return kNotFused;
-}
-
-int device_cus() {
-  static int cus = 0;
-  if (!cus) {
-    int dev = 0;
-    hipDeviceProp_t prop;
-    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return 0;
-    cus = prop.multiProcessorCount;
-  }
-  return cus;
-}
-
-// Launch the fused kernel on a grid that is resident all at once.
-template <int MODE, int THREADS, int R, bool SMALL>
-int launch_fused(const TileArgs& t, int pitch, hipStream_t s) {
-  const size_t dyn = (size_t)256 * pitch;
-  // resident workgroups per compute unit for this LDS size: asked once, then remembered
-  static std::mutex mu;
-  static std::map<size_t, int> known;
-  int per_cu = 0;
-  {
-    std::lock_guard<std::mutex> lk(mu);
-    auto it = known.find(dyn);
-    if (it != known.end()) {
-      per_cu = it->second;
-    } else {
-      if (hipOccupancyMaxActiveBlocksPerMultiprocessor(
-              &per_cu, k_quantize_fused<MODE, THREADS, R, SMALL>, THREADS, dyn) != hipSuccess ||
-          per_cu < 1)
-        return LBT_ERR_HIP;
-      known[dyn] = per_cu;
-    }
-  }
-  const int cus = device_cus();
-  if (cus < 1) return LBT_ERR_HIP;
-  const long long tiles_l = SMALL ? 1 : (t.L + 63) / 64;
-  const long long tiles = tiles_l * t.BG * t.AG;
-  long long grid = (long long)per_cu * cus;
-  if (grid > kMaxPartialBlocks) grid = kMaxPartialBlocks;
-  if (grid > tiles) grid = tiles;
-  hipLaunchKernelGGL((k_quantize_fused<MODE, THREADS, R, SMALL>), dim3((unsigned)grid), dim3(THREADS),
-                     dyn, s, t, pitch);
-  LBT_LAUNCH_CHECK();
-  return LBT_OK;
+TileKind tile_kind(const float* x, long long B, long long L) {
+  if (reinterpret_cast<uintptr_t>(x) % 16 != 0) return kGenericTile;
+  if (L >= 16 && L % 4 == 0) return kWindowed;
+  if (L >= 2 && L <= 248 && B % 16 == 0 && (B * L) % 8 == 0) return kWholeRow;
+  return kGenericTile;
 }
 
 template <int MODE>
 int tile_dispatch(const TileArgs& t, hipStream_t s) {
   if (t.AG > 65535 || t.BG > 65535) return LBT_ERR_UNSUPPORTED;
-  switch (fused_kind(t.x, t.A, t.B, t.L)) {
-    case kFusedLarge:
-      return launch_fused<MODE, 256, 2, false>(t, 72, s);
-    case kFusedSmall256:
-      return launch_fused<MODE, 256, 2, true>(t, (t.L + 3) / 4 * 4 + 4, s);
-    case kFusedSmall1024:
-      return launch_fused<MODE, 1024, 1, true>(t, (t.L + 3) / 4 * 4 + 4, s);
-    default:
+  switch (tile_kind(t.x, t.B, t.L)) {
+    case kWindowed: {
+      const int tl = window_len(t.L), pitch = 72;
+      dim3 grid((unsigned)((t.L + tl - 1) / tl), (unsigned)t.BG, (unsigned)t.AG);
+      hipLaunchKernelGGL((k_quantize_stream<MODE, false>), grid, dim3(kThreads), (size_t)256 * pitch,
+                         s, t, pitch, tl);
       break;
-  }
-  if (t.L == 1) {
-    dim3 grid(1, (unsigned)t.BG, (unsigned)t.AG);
-    hipLaunchKernelGGL((k_quantize_tile_generic<MODE, 1>), grid, dim3(kThreads), 0, s, t);
-  } else {
-    dim3 grid((unsigned)((t.L + 31) / 32), (unsigned)t.BG, (unsigned)t.AG);
-    hipLaunchKernelGGL((k_quantize_tile_generic<MODE, 32>), grid, dim3(kThreads), 0, s, t);
+    }
+    case kWholeRow: {
+      const int pitch = (t.L + 3) / 4 * 4 + 4;
+      dim3 grid(1, (unsigned)t.BG, (unsigned)t.AG);
+      hipLaunchKernelGGL((k_quantize_stream<MODE, true>), grid, dim3(kThreads), (size_t)256 * pitch,
+                         s, t, pitch, t.L);
+      break;
+    }
+    default:
+      if (t.L == 1) {
+        dim3 grid(1, (unsigned)t.BG, (unsigned)t.AG);
+        hipLaunchKernelGGL((k_quantize_tile_generic<MODE, 1>), grid, dim3(kThreads), 0, s, t);
+      } else {
+        dim3 grid((unsigned)((t.L + 31) / 32), (unsigned)t.BG, (unsigned)t.AG);
+        hipLaunchKernelGGL((k_quantize_tile_generic<MODE, 32>), grid, dim3(kThreads), 0, s, t);
+      }
   }
   LBT_LAUNCH_CHECK();
   return LBT_OK;
@@ -877,7 +722,8 @@ int launch_absmax3(const float* p0, int64_t n0, int abs0, const float* p1, int64
   if (!p2) n2 = 0;
   ProfScope prof(KID_ABSMAX, (double)(n0 + n1 + n2), s);
   const long long total = n0 + n1 + n2;
-  long long per = (total + (kMaxPartialBlocks - 4) - 1) / (kMaxPartialBlocks - 4);
+  // at most ~1000 partial rows, so that a consumer's prologue reads 4 per thread
+  long long per = (total + 999) / 1000;
   per = (per + 8191) / 8192 * 8192;  // 256 threads x 8 float4
   if (per < 8192) per = 8192;
   const long long nb0 = (n0 + per - 1) / per, nb1 = (n1 + per - 1) / per, nb2 = (n2 + per - 1) / per;
@@ -925,17 +771,12 @@ int launch_quantize_flat_operand(const float* x, int64_t n, float c_given, const
   return LBT_OK;
 }
 
-bool relayout_is_fused(const float* x, int64_t A, int64_t B, int64_t L) {
-  return fused_kind(x, A, B, L) != kNotFused;
-}
-
 static void fill_tile_args(TileArgs& t, const float* x, int64_t A, int64_t B, int64_t L,
                            const RelayoutIo& io) {
   t.x = x; t.A = (int)A; t.B = (int)B; t.L = (int)L;
   t.AG = (int)(round_up(A, kGranule) / kGranule);
   t.BG = (int)(round_up(B, kGranule) / kGranule);
   t.pmax = io.pmax; t.nblocks = io.nblocks; t.pmax_col = io.pmax_col;
-  t.pmax_own = io.pmax_own; t.sync = io.sync; t.ctr = io.ctr;
   t.st = io.st;
   t.out_b = reinterpret_cast<uint2*>(io.out_b);
   t.out_a = reinterpret_cast<uint2*>(io.out_a);
@@ -943,27 +784,22 @@ static void fill_tile_args(TileArgs& t, const float* x, int64_t A, int64_t B, in
 
 int launch_quantize_relayout_grad(const float* g, int64_t A, int64_t B, int64_t L,
                                   const RelayoutIo& io, uint64_t seed, int rounding,
-                                  unsigned long long* clear0, unsigned long long* clear1,
-                                  const float* side_x, int64_t side_n, float* side_c_out,
-                                  uint32_t* side_bad_out, hipStream_t s) {
+                                  hipStream_t s) {
   ProfScope prof(KID_RELAYOUT_GRAD, (double)A * (double)B * (double)L, s);
   TileArgs t{};
   fill_tile_args(t, g, A, B, L, io);
   t.seed = seed;
-  t.clear0 = clear0; t.clear1 = clear1;
-  t.side_x = side_x; t.side_n = side_n; t.side_c_out = side_c_out; t.side_bad_out = side_bad_out;
   if (rounding == LBT_ROUND_STOCHASTIC) return tile_dispatch<3>(t, s);
   return tile_dispatch<2>(t, s);
 }
 
 int launch_quantize_relayout_operand(const float* x, int64_t A, int64_t B, int64_t L,
-                                     const RelayoutIo& io, float c_given, const float* c_ptr,
-                                     int is_unsigned, float* c_out, uint32_t* bad_out,
-                                     hipStream_t s) {
+                                     const RelayoutIo& io, float c_given, int is_unsigned,
+                                     float* c_out, uint32_t* bad_out, hipStream_t s) {
   ProfScope prof(KID_RELAYOUT_OPERAND, (double)A * (double)B * (double)L, s);
   TileArgs t{};
   fill_tile_args(t, x, A, B, L, io);
-  t.c_given = c_given; t.c_ptr = c_ptr;
+  t.c_given = c_given;
   t.c_out = c_out; t.bad_out = bad_out;
   if (is_unsigned) return tile_dispatch<1>(t, s);
   return tile_dispatch<0>(t, s);

@@ -62,7 +62,7 @@ def test_host_validation_rejects_without_gpu(lib):
     assert lib.lbt_quantize_grad(p, 8, p, 0, 7, p, p, big, None) == -3          # rounding mode
     assert lib.lbt_quantize_grad(C.c_void_p(4100), 8, p, 0, 0, p, p, big, None) == -7
     assert lib.lbt_quantize_grad(p, 8, p, 0, 0, p, p, 16, None) == -4           # workspace
-    assert lib.lbt_workspace_bytes_quantize(8) == 4096 + 256 + 2048 * 24
+    assert lib.lbt_workspace_bytes_quantize(8) == 256 + 2048 * 16
     # conv shape checks
     assert lib.lbt_workspace_bytes_conv2d(1, 1, 2, 2, 1, 3, 3, 1, 0) == 0       # kernel > image
     need = lib.lbt_workspace_bytes_conv2d(4, 16, 12, 12, 32, 3, 3, 1, 1)
@@ -81,7 +81,7 @@ def test_workspace_formula(lib):
     N, Cc, H, W, K, R, S, st, pad = 64, 256, 14, 14, 256, 3, 3, 1, 1
     P = Q = 14
     pad256 = lambda b: (b + 255) // 256 * 256
-    want = 4096 + 256 + 2048 * 24 + pad256(N * P * Q * K // 2) + pad256(K * P * Q * N // 2) \
+    want = 256 + 2048 * 16 + pad256(N * P * Q * K // 2) + pad256(K * P * Q * N // 2) \
         + pad256(Cc * H * W * N // 2) + pad256(Cc * R * S * K // 2)
     got = lib.lbt_workspace_bytes_conv2d(N, Cc, H, W, K, R, S, st, pad)
     partial = got - want
