@@ -350,11 +350,11 @@ template <int BM, int MODE>
 void launch_variant(const GemmArgs& g, bool a_uns, bool b_uns, unsigned grid, size_t dyn,
                     hipStream_t s) {
   if (a_uns)
-    hipLaunchKernelGGL((k_implicit_gemm<BM, true, false, MODE>), dim3(grid), dim3(kThreads), dyn, s, g);
+    LBT_LAUNCH((k_implicit_gemm<BM, true, false, MODE>), dim3(grid), dim3(kThreads), dyn, s, g);
   else if (b_uns)
-    hipLaunchKernelGGL((k_implicit_gemm<BM, false, true, MODE>), dim3(grid), dim3(kThreads), dyn, s, g);
+    LBT_LAUNCH((k_implicit_gemm<BM, false, true, MODE>), dim3(grid), dim3(kThreads), dyn, s, g);
   else
-    hipLaunchKernelGGL((k_implicit_gemm<BM, false, false, MODE>), dim3(grid), dim3(kThreads), dyn, s, g);
+    LBT_LAUNCH((k_implicit_gemm<BM, false, false, MODE>), dim3(grid), dim3(kThreads), dyn, s, g);
 }
 
 int run_gemm(GemmArgs& g, int mode, bool a_uns, bool b_uns, int bm, int splits, int kid,
@@ -416,7 +416,7 @@ int run_splitk(GemmArgs& g, bool a_uns, bool b_uns, long long true_k, int32_t* a
   g.acc = acc;
   long long blocks = (n_out + kThreads - 1) / kThreads;
   if (blocks > 4096) blocks = 4096;
-  hipLaunchKernelGGL(k_splitk_reduce, dim3((unsigned)blocks), dim3(kThreads), 0, s, partial,
+  LBT_LAUNCH(k_splitk_reduce, dim3((unsigned)blocks), dim3(kThreads), 0, s, partial,
                      plan.splits, n_out, g);
   LBT_LAUNCH_CHECK();
   return LBT_OK;

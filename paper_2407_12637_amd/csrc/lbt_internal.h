@@ -52,6 +52,10 @@ class ProfScope {
   hipStream_t s_;
 };
 
+// Every kernel of the library is launched through this macro.
+#define LBT_LAUNCH(kernel, grid, block, shmem, stream, ...) \
+  hipLaunchKernelGGL(kernel, grid, block, shmem, stream, __VA_ARGS__)
+
 // ---- quantize.hip -------------------------------------------------------------
 constexpr int kMaxPartialBlocks = 2048;  // partial-maximum slots in the workspace header
 // Workspace header: OperandScalars (256 bytes), then pmax[kMaxPartialBlocks][4] uint32.

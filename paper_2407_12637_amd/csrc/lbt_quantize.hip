@@ -688,24 +688,24 @@ int tile_dispatch(const TileArgs& t, hipStream_t s) {
     case kWindowed: {
       const int tl = window_len(t.L), pitch = 72;
       dim3 grid((unsigned)((t.L + tl - 1) / tl), (unsigned)t.BG, (unsigned)t.AG);
-      hipLaunchKernelGGL((k_quantize_stream<MODE, false>), grid, dim3(kThreads), (size_t)256 * pitch,
+      LBT_LAUNCH((k_quantize_stream<MODE, false>), grid, dim3(kThreads), (size_t)256 * pitch,
                          s, t, pitch, tl);
       break;
     }
     case kWholeRow: {
       const int pitch = (t.L + 3) / 4 * 4 + 4;
       dim3 grid(1, (unsigned)t.BG, (unsigned)t.AG);
-      hipLaunchKernelGGL((k_quantize_stream<MODE, true>), grid, dim3(kThreads), (size_t)256 * pitch,
+      LBT_LAUNCH((k_quantize_stream<MODE, true>), grid, dim3(kThreads), (size_t)256 * pitch,
                          s, t, pitch, t.L);
       break;
     }
     default:
       if (t.L == 1) {
         dim3 grid(1, (unsigned)t.BG, (unsigned)t.AG);
-        hipLaunchKernelGGL((k_quantize_tile_generic<MODE, 1>), grid, dim3(kThreads), 0, s, t);
+        LBT_LAUNCH((k_quantize_tile_generic<MODE, 1>), grid, dim3(kThreads), 0, s, t);
       } else {
         dim3 grid((unsigned)((t.L + 31) / 32), (unsigned)t.BG, (unsigned)t.AG);
-        hipLaunchKernelGGL((k_quantize_tile_generic<MODE, 32>), grid, dim3(kThreads), 0, s, t);
+        LBT_LAUNCH((k_quantize_tile_generic<MODE, 32>), grid, dim3(kThreads), 0, s, t);
       }
   }
   LBT_LAUNCH_CHECK();
@@ -732,7 +732,7 @@ int launch_absmax3(const float* p0, int64_t n0, int abs0, const float* p1, int64
   if (nb == 0) return LBT_OK;
   if (nb > kMaxPartialBlocks) return LBT_ERR_UNSUPPORTED;
   MaxSeg s0{p0, n0, abs0, 0}, s1{p1, n1, abs1, (int)nb0}, s2{p2, n2, abs2, (int)(nb0 + nb1)};
-  hipLaunchKernelGGL(k_absmax3, dim3((unsigned)nb), dim3(kThreads), 0, s, s0, s1, s2, per, pmax);
+  LBT_LAUNCH(k_absmax3, dim3((unsigned)nb), dim3(kThreads), 0, s, s0, s1, s2, per, pmax);
   LBT_LAUNCH_CHECK();
   return LBT_OK;
 }
@@ -743,11 +743,11 @@ int launch_quantize_flat_grad(const float* g, int64_t n, const uint32_t* pmax, i
   ProfScope prof(KID_FLAT_GRAD, (double)n, s);
   const int grid = flat_grid((n + 7) / 8);
   if (rounding == LBT_ROUND_STOCHASTIC)
-    hipLaunchKernelGGL(k_quantize_flat<3>, dim3(grid), dim3(kThreads), 0, s, g, (long long)n, 0.0f,
+    LBT_LAUNCH(k_quantize_flat<3>, dim3(grid), dim3(kThreads), 0, s, g, (long long)n, 0.0f,
                        pmax, nblocks, st, (unsigned long long)seed, codes, (float*)nullptr,
                        (float*)nullptr);
   else
-    hipLaunchKernelGGL(k_quantize_flat<2>, dim3(grid), dim3(kThreads), 0, s, g, (long long)n, 0.0f,
+    LBT_LAUNCH(k_quantize_flat<2>, dim3(grid), dim3(kThreads), 0, s, g, (long long)n, 0.0f,
                        pmax, nblocks, st, (unsigned long long)seed, codes, (float*)nullptr,
                        (float*)nullptr);
   LBT_LAUNCH_CHECK();
@@ -760,11 +760,11 @@ int launch_quantize_flat_operand(const float* x, int64_t n, float c_given, const
   ProfScope prof(KID_FLAT_OPERAND, (double)n, s);
   const int grid = flat_grid((n + 7) / 8);
   if (is_unsigned)
-    hipLaunchKernelGGL(k_quantize_flat<1>, dim3(grid), dim3(kThreads), 0, s, x, (long long)n,
+    LBT_LAUNCH(k_quantize_flat<1>, dim3(grid), dim3(kThreads), 0, s, x, (long long)n,
                        c_given, pmax, nblocks, (lbt_grad_state*)nullptr, 0ull, codes, c_out,
                        clip_scale_out);
   else
-    hipLaunchKernelGGL(k_quantize_flat<0>, dim3(grid), dim3(kThreads), 0, s, x, (long long)n,
+    LBT_LAUNCH(k_quantize_flat<0>, dim3(grid), dim3(kThreads), 0, s, x, (long long)n,
                        c_given, pmax, nblocks, (lbt_grad_state*)nullptr, 0ull, codes, c_out,
                        clip_scale_out);
   LBT_LAUNCH_CHECK();
@@ -807,14 +807,14 @@ int launch_quantize_relayout_operand(const float* x, int64_t A, int64_t B, int64
 
 int launch_update_interval(lbt_grad_state* st, hipStream_t s) {
   ProfScope prof(KID_UPDATE, 0.0, s);
-  hipLaunchKernelGGL(k_update_interval, dim3(1), dim3(1), 0, s, st);
+  LBT_LAUNCH(k_update_interval, dim3(1), dim3(1), 0, s, st);
   LBT_LAUNCH_CHECK();
   return LBT_OK;
 }
 
 int launch_state_init(lbt_grad_state* st, const lbt_grad_state& v, hipStream_t s) {
   ProfScope prof(KID_STATE, 0.0, s);
-  hipLaunchKernelGGL(k_state_set, dim3(1), dim3(1), 0, s, st, v);
+  LBT_LAUNCH(k_state_set, dim3(1), dim3(1), 0, s, st, v);
   LBT_LAUNCH_CHECK();
   return LBT_OK;
 }
