@@ -12,7 +12,7 @@ SOURCES = ["lbt_api.hip", "lbt_quantize.hip", "lbt_gemm.hip", "lbt_profile.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
-    "-ffp-contract=off",                       # codes are decided by un-fused double arithmetic
+    "-ffp-contract=off",                       # codes are decided by un-fused fp32 arithmetic
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function",
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,

@@ -90,19 +90,20 @@ int backward_common(const float* X, const float* W, const float* dY, const ConvG
     return rc;
   // 2. gradient codes in the layouts the two products read
   {
-    RelayoutIo io{pmax, nblocks, 0, st, dX ? g_npqk : nullptr, dW ? g_kpqn : nullptr};
+    RelayoutIo io{pmax, nblocks, 0, st, dX ? g_npqk : nullptr, dW ? g_kpqn : nullptr, 0};
     if ((rc = launch_quantize_relayout_grad(dY, g.N, g.K, PQ, io, seed, rounding, s))) return rc;
   }
   // 3. activation codes
   if (dW) {
-    RelayoutIo io{pmax, nblocks, 1, st, nullptr, x_chwn};
+    RelayoutIo io{pmax, nblocks, 1, st, nullptr, x_chwn, 0};
     if ((rc = launch_quantize_relayout_operand(X, g.N, g.C, HW, io, c_x, x_unsigned, &sc->c_x,
                                                &sc->bad_x, s)))
       return rc;
   }
   // 4. weight codes, then the two products
   if (dX) {
-    RelayoutIo io{pmax, nblocks, 2, st, w_is_ck ? w_crsk : nullptr, w_is_ck ? nullptr : w_crsk};
+    // conv weights tap-major [C][R*S][Kp/16][16]: the dX kernel walks the contraction tap by tap
+    RelayoutIo io{pmax, nblocks, 2, st, w_is_ck ? w_crsk : nullptr, w_is_ck ? nullptr : w_crsk, 1};
     if ((rc = launch_quantize_relayout_operand(W, wA, wB, wL, io, c_w, 0, &sc->c_w, &sc->bad_w, s)))
       return rc;
     rc = w_is_ck ? launch_linear_dx(g, w_crsk, g_npqk, st, sc, dX, acc_dX, s)

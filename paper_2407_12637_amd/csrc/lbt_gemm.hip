@@ -3,23 +3,28 @@
 // Both gradients of a convolution (and of a linear layer, which is the 1x1 case
 // on a 1x1 image) are computed by one implicit-GEMM kernel
 //     D[m][j] = sum_k A[m][k] * B[j][k]
-// whose operands are 4-bit codes packed two per byte along the contraction axis:
-//   dX: A = weights  [C][Kp/16][R*S][16] (dense rows), B row j = output pixel (n,h,w),
-//       gathered from the gradient codes [N][Kp/16][P*Q][16] tap by tap;
+// whose operands are 4-bit codes packed two per byte along the contraction axis,
+// in granules ("chunks") of 16 codes = 8 bytes:
+//   dX: A = weights  [C][R*S][Kp/16][16] (dense rows, tap-major), B row j = input pixel
+//       (n,h,w), gathered from the gradient codes [N][Kp/16][P*Q][16] tap by tap;
 //   dW: A = gradient [K][Np/16][P*Q][16] (dense rows), B row j = (c,r,s), gathered
 //       from the activation codes [C][Np/16][H*W][16] with the tap's shift.
-// The contraction axis is cut into chunks of 16 codes (8 bytes), numbered
-// t = group * inner + position (group: which sixteen channels / samples; position:
-// tap for dX, output pixel for dW); a chunk is either wholly inside the image or
-// wholly padding, so the gather works on whole chunks.
+// A chunk is either wholly inside the image or wholly padding, so the gather works on
+// whole chunks.  dX runs over the contraction tap by tap (all channel groups of one tap,
+// then the next tap; the group count is padded to 1, 2, 4 or a multiple of 8 with
+// zero chunks so that a K step of 8 chunks never straddles taps unevenly); dW runs
+// over t = sample_group * P*Q + output pixel.
 //
-// A workgroup (4 waves) owns a BM x 128 tile of D.  Per K step of 8 chunks it stages
-// the packed operand tiles in LDS (double buffered; the global loads of step i+1 are
-// in flight while step i runs on the matrix cores).  Codes are widened to int8 in
-// registers after the LDS read: a signed nibble is moved to the top of its byte
+// A workgroup (4 waves) owns a BM x BN tile of D (64 or 128 each; smaller tiles when the
+// problem would otherwise not fill the chip).  Per K step of 8 chunks (128 codes) it
+// reads the packed granules with buffer loads (out-of-range offsets return zero, which
+// is how padding, ragged edges and the K tail are masked), widens them to int8 ONCE and
+// stores them in LDS (double buffered, 16 bytes per granule); the waves then feed
+// v_mfma_i32_32x32x32_i8 straight from 16-byte LDS reads.  Global loads run two steps
+// ahead of the matrix cores.  Widening: a signed nibble is moved to the top of its byte
 // (value * 16, exact two's complement), an unsigned nibble is masked in place; the
-// accumulators therefore carry a factor 256 or 16 that the epilogue shifts out
-// exactly.  v_mfma_i32_32x32x32_i8, int32 accumulation, exact.
+// accumulators therefore carry a factor 256 or 16 that the epilogue shifts out exactly.
+// int32 accumulation, exact.
 //
 // dW has a small output and a very long contraction: the contraction is split
 // over workgroups, each writes its partial tile with plain stores, and a second
@@ -32,27 +37,29 @@ namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
+typedef unsigned v2u __attribute__((ext_vector_type(2)));
 
 constexpr int kThreads = 256;
-constexpr int BN = 128;             // columns of D per workgroup
-constexpr int BKC = 8;              // chunks (of 16 codes) per K step: 128 codes = 64 bytes per row
-constexpr int PITCH = BKC * 8 + 8;  // LDS row pitch in bytes (72: conflict-free 8-byte reads)
-constexpr int kXcds = 8;            // workgroups are dealt round-robin to 8 dies, each with its own L2
+constexpr int BKC = 8;                  // chunks (of 16 codes) per K step
+constexpr int PITCH = BKC * 16 + 16;    // LDS bytes per tile row: 128 int8 codes + 16 pad
+constexpr int kXcds = 8;                // workgroups are dealt round-robin to 8 dies, each with its own L2
 
 struct GemmArgs {
   const uint8_t* A;
   const uint8_t* B;
-  long long lda;      // bytes per A row
+  unsigned a_bytes, b_bytes;  // sizes of the two code tensors (buffer bounds)
+  unsigned lda;       // bytes per A row
   int M, NJ;          // rows of A, rows of B
-  int chunks;         // total K chunks
-  int chunks_per_split;
+  int chunks;         // MODE 1: K chunks; MODE 0: padded chunk count R*S*Gp
+  int steps, steps_per_split;
   int tiles_m, tiles_n, total_blocks;
   int epi;            // 0 = scaled store to NCHW dX, 1 = int32 partial tile (split K),
                       // 2 = scaled store row-major
   int scale_kind;     // 0: s_g*s_w   1: s_x*s_g (signed x)   2: s_x*s_g (unsigned x)
   int N, C, H, W, K, R, S, P, Q, stride, pad;
-  int inner;          // chunk t = group * inner + pos; inner = R*S (dX) or P*Q (dW)
+  int inner;          // MODE 1: chunk t = group * inner + pos, inner = P*Q (1 for linear)
   int groups;         // granule groups per row of the gathered tensor (Kp/16 or Np/16)
+  int gp, gp_log2;    // MODE 0: padded group count; gp_log2 >= 0 when gp is 1, 2 or 4, else -1
   int shift;          // log2 of the factor carried by the accumulators
   const lbt_grad_state* st;
   const OperandScalars* sc;
@@ -61,24 +68,25 @@ struct GemmArgs {
   int32_t* partial;   // [splits][M][NJ] for epi 1
 };
 
-// Signed nibbles -> int8 values 16*code (nibble placed in the high half of each byte).
-__device__ __forceinline__ void widen_signed(uint32_t p, int& even, int& odd) {
-  odd = (int)(p & 0xF0F0F0F0u);
-  even = (int)((p << 4) & 0xF0F0F0F0u);
-}
-// Unsigned nibbles -> int8 values code.
-__device__ __forceinline__ void widen_unsigned(uint32_t p, int& even, int& odd) {
-  even = (int)(p & 0x0F0F0F0Fu);
-  odd = (int)((p >> 4) & 0x0F0F0F0Fu);
-}
-
+// Packed granule (16 nibbles) -> 16 int8 values.  Byte i of a packed word holds codes
+// 2i (low nibble) and 2i+1 (high nibble); the result keeps the evens of each word together
+// and the odds together, the same permutation for both operands of a product.
+//   signed:   value * 16 (nibble in the top half of the byte)
+//   unsigned: value
 template <bool UNS>
-__device__ __forceinline__ v4i widen(uint2 p) {
+__device__ __forceinline__ v4i widen(v2u p) {
   v4i r;
-  int a, b, c, d;
-  if (UNS) { widen_unsigned(p.x, a, b); widen_unsigned(p.y, c, d); }
-  else { widen_signed(p.x, a, b); widen_signed(p.y, c, d); }
-  r[0] = a; r[1] = b; r[2] = c; r[3] = d;
+  if (UNS) {
+    r[0] = (int)(p[0] & 0x0F0F0F0Fu);
+    r[1] = (int)((p[0] >> 4) & 0x0F0F0F0Fu);
+    r[2] = (int)(p[1] & 0x0F0F0F0Fu);
+    r[3] = (int)((p[1] >> 4) & 0x0F0F0F0Fu);
+  } else {
+    r[0] = (int)((p[0] << 4) & 0xF0F0F0F0u);
+    r[1] = (int)(p[0] & 0xF0F0F0F0u);
+    r[2] = (int)((p[1] << 4) & 0xF0F0F0F0u);
+    r[3] = (int)(p[1] & 0xF0F0F0F0u);
+  }
   return r;
 }
 
@@ -90,19 +98,22 @@ __device__ __forceinline__ float output_scale(const GemmArgs& g) {
   return (float)(s_g * other);
 }
 
-// MODE 0: B rows are output pixels (dX of a convolution)
+// MODE 0: B rows are input pixels (dX of a convolution)
 // MODE 1: B rows are (c,r,s) triples read with the tap's shift (dW; also every
 //         linear-layer product, where the image is 1x1)
-template <int BM, bool A_UNSIGNED, bool B_UNSIGNED, int MODE>
+template <int BM, int BN, bool A_UNSIGNED, bool B_UNSIGNED, int MODE>
 __global__ __launch_bounds__(kThreads) void k_implicit_gemm(const GemmArgs g) {
-  constexpr int WGM = (BM == 128) ? 2 : 1;     // wave grid: WGM x WGN
+  // wave grid WGM x WGN: 128x128 -> 2x2, 64x128 -> 1x4, 128x64 -> 4x1, 64x64 -> 2x2
+  constexpr int WGM = (BM == BN) ? 2 : (BM > BN ? 4 : 1);
   constexpr int WGN = 4 / WGM;
   constexpr int WM = BM / WGM, WN = BN / WGN;  // wave tile
   constexpr int TM = WM / 32, TN = WN / 32;    // 32x32 MFMA blocks per wave
-  constexpr int NA = BM * BKC / kThreads, NB = BN * BKC / kThreads;
-  __shared__ __attribute__((aligned(16))) uint8_t sA[2][BM * PITCH];
-  __shared__ __attribute__((aligned(16))) uint8_t sB[2][BN * PITCH];
-  extern __shared__ int s_tap[];  // MODE 0: [BN][R*S] pixel offset of each tap, or -1
+  constexpr int NA = BM * BKC / kThreads, NB = BN * BKC / kThreads;  // granules per thread per step
+  // dynamic LDS: two stages of the A tile, two of the B tile, then (MODE 0) the tap table
+  extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+  uint8_t* const sA0 = lds;
+  uint8_t* const sB0 = lds + 2 * BM * PITCH;
+  int* const s_tap = reinterpret_cast<int*>(lds + 2 * (BM + BN) * PITCH);  // [BN][R*S]
 
   // workgroup id -> tile, so that the workgroups sharing a B tile run on one die
   const int per_xcd = gridDim.x / kXcds;
@@ -115,93 +126,133 @@ __global__ __launch_bounds__(kThreads) void k_implicit_gemm(const GemmArgs g) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = (wave / WGN) * WM, wn = (wave % WGN) * WN;
   const int m0 = m_tile * BM, j0 = n_tile * BN;
-  const int t_begin = split * g.chunks_per_split;
-  const int t_end = min(t_begin + g.chunks_per_split, g.chunks);
+  const int s_begin = split * g.steps_per_split;
+  const int n_steps = min(s_begin + g.steps_per_split, g.steps) - s_begin;
   const int HW = g.H * g.W, PQ = g.P * g.Q, RS = g.R * g.S;
 
-  // ---- A staging: chunk-fastest, thread owns chunk column (tid & 7) of NA rows ----------
-  const uint8_t* a_ptr[NA];
-  bool a_ok[NA];
-  const int a_cpos = tid & 7;
+  // Raw buffer views of the code tensors: a load whose offset is >= the size returns 0.
+  const __amdgpu_buffer_rsrc_t rsrc_a =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(g.A), 0, g.a_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsrc_b =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(g.B), 0, g.b_bytes, 0x00020000);
+  const unsigned oob_a = g.a_bytes, oob_b = g.b_bytes;
+
+  // ---- A staging: chunk-fastest; a thread owns chunk column `col` of NA rows ------------
+  const int col = tid & (BKC - 1);
+  unsigned a_row[NA];
 #pragma unroll
-  for (int i = 0; i < NA; ++i) {
-    const int row = m0 + ((tid + kThreads * i) >> 3);
-    a_ok[i] = row < g.M;
-    a_ptr[i] = g.A + (long long)row * g.lda + (long long)(t_begin + a_cpos) * 8;
-  }
-  int a_t = t_begin + a_cpos;
+  for (int i = 0; i < NA; ++i) a_row[i] = (unsigned)(m0 + (tid >> 3) + 32 * i) * g.lda;
+  // MODE 0 walks (tap, group); all threads of the workgroup share (tap_base, kg_base)
+  const bool small = g.gp_log2 >= 0;
+  int tap_base = 0, kg_base = 0;
+  int a_dt = 0, a_kgo = col;
+  // MODE 1 walks chunk t = 8 * step + col
+  int t_cur = s_begin * BKC + col;
 
   // ---- B staging ---------------------------------------------------------------------------
-  // MODE 1: chunk-fastest like A; per row (c,r,s); thread-level running (group, p, q).
-  int b_base[NB], b_dh[NB], b_dw[NB];
-  bool b_ok[NB];
-  int b_t = 0, b_grp = 0, b_p = 0, b_q = 0;
-  // MODE 0: row-fastest; thread owns ONE pixel row and NB chunk columns.
-  int x_row = 0, x_base = 0;
-  bool x_ok = false;
-  int x_t[NB], x_grp[NB], x_tap[NB];
+  // MODE 1: chunk-fastest like A; row i is a (c,r,s) triple; the thread's running output
+  // position (group, p, q) belongs to its chunk column.
+  unsigned b_row[NB];
+  int b_dh[NB], b_dw[NB];
+  int b_grp = 0, b_p = 0, b_q = 0;
+  // MODE 0: row-fastest; the thread owns ONE pixel row and NB chunk columns.
+  const int x_row = tid % BN;
+  unsigned x_const[NB];
+  int x_dt[NB];
   if (MODE == 1) {
 #pragma unroll
     for (int i = 0; i < NB; ++i) {
-      const int j = j0 + ((tid + kThreads * i) >> 3);
-      b_ok[i] = j < g.NJ;
-      const int s_ = j % g.S, r_ = (j / g.S) % g.R, c_ = j / RS;
-      b_base[i] = c_ * g.groups * HW;
+      const int j = j0 + (tid >> 3) + 32 * i;
+      const int c_ = j / RS, rs = j - c_ * RS;
+      const int r_ = rs / g.S, s_ = rs - r_ * g.S;
       b_dh[i] = r_ - g.pad;
       b_dw[i] = s_ - g.pad;
+      b_row[i] = j < g.NJ ? (unsigned)(c_ * g.groups * HW + b_dh[i] * g.W + b_dw[i]) * 8u : oob_b;
     }
-    b_t = t_begin + (tid & 7);
-    b_grp = b_t / g.inner;
-    const int pos = b_t - b_grp * g.inner;
+    b_grp = t_cur / g.inner;
+    const int pos = t_cur - b_grp * g.inner;
     b_p = pos / g.Q;
     b_q = pos - b_p * g.Q;
   } else {
-    x_row = tid % BN;
+    const int t0 = s_begin * BKC;
+    if (small) {
+      tap_base = t0 >> g.gp_log2;
+      a_dt = col >> g.gp_log2;
+      a_kgo = col & (g.gp - 1);
+    } else {
+      tap_base = t0 / g.gp;
+      kg_base = t0 - tap_base * g.gp;
+    }
     const int j = j0 + x_row;
-    x_ok = j < g.NJ;
+    const bool x_ok = j < g.NJ;
     const int n_ = j / HW, hw = j - n_ * HW;
     const int h_ = hw / g.W, w_ = hw - h_ * g.W;
-    x_base = n_ * g.groups * PQ;
-    // tap table of this row; the 256 / BN threads that share the row split the taps
-    for (int tap = tid / BN; tap < RS; tap += kThreads / BN) {
-      const int fr = tap / g.S, fs = tap - fr * g.S;
-      const int hp = h_ + g.pad - fr, wq = w_ + g.pad - fs;
-      int off = -1;
-      if (x_ok && hp >= 0 && wq >= 0) {
-        const int p = hp / g.stride, q = wq / g.stride;
-        if (p * g.stride == hp && q * g.stride == wq && p < g.P && q < g.Q) off = p * g.Q + q;
+    // tap table of this row: byte offset of output pixel (p,q) inside one channel group, or
+    // -1 when the tap falls outside the output / between strides.  The 256 / BN threads
+    // that share the row split the taps.
+    {
+      constexpr int SUB = kThreads / BN;
+      int fr = 0, fs = tid / BN;
+      while (fs >= g.S) { fs -= g.S; ++fr; }
+      for (int tap = tid / BN; tap < RS; tap += SUB) {
+        const int hp = h_ + g.pad - fr, wq = w_ + g.pad - fs;
+        int off = -1;
+        if (x_ok && hp >= 0 && wq >= 0) {
+          int p, q;
+          bool on_grid;
+          if (g.stride == 1) {
+            p = hp; q = wq; on_grid = true;
+          } else if (g.stride == 2) {
+            p = hp >> 1; q = wq >> 1; on_grid = ((hp | wq) & 1) == 0;
+          } else {
+            p = hp / g.stride; q = wq / g.stride;
+            on_grid = p * g.stride == hp && q * g.stride == wq;
+          }
+          if (on_grid && p < g.P && q < g.Q) off = (p * g.Q + q) * 8;
+        }
+        s_tap[x_row * RS + tap] = off;
+        fs += SUB;
+        while (fs >= g.S) { fs -= g.S; ++fr; }
       }
-      s_tap[x_row * RS + tap] = off;
     }
 #pragma unroll
     for (int i = 0; i < NB; ++i) {
-      x_t[i] = t_begin + tid / BN + i * (kThreads / BN);
-      x_grp[i] = x_t[i] / g.inner;
-      x_tap[i] = x_t[i] - x_grp[i] * g.inner;
+      const int c = tid / BN + i * (kThreads / BN);
+      const int dt = small ? c >> g.gp_log2 : 0;
+      const int kgo = small ? c & (g.gp - 1) : c;
+      x_dt[i] = dt;
+      x_const[i] = (unsigned)((n_ * g.groups + kgo) * PQ) * 8u;
     }
     __syncthreads();
   }
 
-  uint2 ra[NA], rb[NB];
-  auto load_tiles = [&]() {
-#pragma unroll
-    for (int i = 0; i < NA; ++i) {
-      ra[i] = make_uint2(0, 0);
-      if (a_ok[i] && a_t < t_end) ra[i] = *reinterpret_cast<const uint2*>(a_ptr[i]);
-      a_ptr[i] += BKC * 8;
-    }
-    a_t += BKC;
+  // Issue the global loads of the next K step into (xa, xb) and advance the walk.  Steps
+  // past the end of this workgroup's K range load zero A columns, so the pipeline below
+  // can run them unconditionally.
+  int ld_step = 0;
+  auto load_step = [&](v2u (&xa)[NA], v2u (&xb)[NB]) {
+    const bool live = ld_step < n_steps;
+    ++ld_step;
     if (MODE == 1) {
-      const bool in_k = b_t < t_end;
+      const unsigned a_col = (live && t_cur < g.chunks) ? (unsigned)t_cur * 8u : oob_a;
 #pragma unroll
-      for (int i = 0; i < NB; ++i) {
-        rb[i] = make_uint2(0, 0);
-        const int h = b_p * g.stride + b_dh[i], w = b_q * g.stride + b_dw[i];
-        if (in_k && b_ok[i] && (unsigned)h < (unsigned)g.H && (unsigned)w < (unsigned)g.W)
-          rb[i] = *reinterpret_cast<const uint2*>(
-              g.B + ((long long)b_base[i] + (long long)b_grp * HW + h * g.W + w) * 8);
+      for (int i = 0; i < NA; ++i)
+        xa[i] = __builtin_amdgcn_raw_buffer_load_b64(rsrc_a, min(a_row[i] + a_col, oob_a), 0, 0);
+      const int ph = b_p * g.stride, qw = b_q * g.stride;
+      const unsigned pos = (unsigned)(b_grp * HW + ph * g.W + qw) * 8u;
+      if (g.pad == 0) {
+#pragma unroll
+        for (int i = 0; i < NB; ++i)
+          xb[i] = __builtin_amdgcn_raw_buffer_load_b64(rsrc_b, b_row[i] + pos, 0, 0);
+      } else {
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+          const bool in = (unsigned)(ph + b_dh[i]) < (unsigned)g.H &&
+                          (unsigned)(qw + b_dw[i]) < (unsigned)g.W;
+          xb[i] = __builtin_amdgcn_raw_buffer_load_b64(rsrc_b, in ? b_row[i] + pos : oob_b, 0, 0);
+        }
       }
-      b_t += BKC;
+      t_cur += BKC;
       if (g.inner == 1) {
         b_grp += BKC;
       } else {
@@ -210,38 +261,46 @@ __global__ __launch_bounds__(kThreads) void k_implicit_gemm(const GemmArgs g) {
         while (b_p >= g.P) { b_p -= g.P; ++b_grp; }
       }
     } else {
+      const int tap_a = tap_base + a_dt, kg_a = kg_base + a_kgo;
+      const unsigned a_col =
+          (live && tap_a < RS && kg_a < g.groups) ? (unsigned)(tap_a * g.groups + kg_a) * 8u : oob_a;
+#pragma unroll
+      for (int i = 0; i < NA; ++i)
+        xa[i] = __builtin_amdgcn_raw_buffer_load_b64(rsrc_a, min(a_row[i] + a_col, oob_a), 0, 0);
+      const unsigned kg_off = (unsigned)(kg_base * PQ) * 8u;
 #pragma unroll
       for (int i = 0; i < NB; ++i) {
-        rb[i] = make_uint2(0, 0);
-        if (x_t[i] < t_end) {
-          const int off = s_tap[x_row * RS + x_tap[i]];
-          if (off >= 0)
-            rb[i] = *reinterpret_cast<const uint2*>(
-                g.B + ((long long)x_base + (long long)x_grp[i] * PQ + off) * 8);
-        }
-        x_t[i] += BKC;
-        if (g.inner == 1) {
-          x_grp[i] += BKC;
-        } else {
-          x_tap[i] += BKC;
-          while (x_tap[i] >= RS) { x_tap[i] -= RS; ++x_grp[i]; }
-        }
+        // columns past the last tap or group meet zero A columns: any in-table tap will do
+        const int tap = min(tap_base + x_dt[i], RS - 1);
+        const int off = s_tap[x_row * RS + tap];
+        xb[i] = __builtin_amdgcn_raw_buffer_load_b64(
+            rsrc_b, off >= 0 ? x_const[i] + kg_off + (unsigned)off : oob_b, 0, 0);
+      }
+      if (small) {
+        tap_base += BKC >> g.gp_log2;
+      } else {
+        kg_base += BKC;
+        if (kg_base >= g.gp) { kg_base = 0; ++tap_base; }
       }
     }
   };
-  auto store_tiles = [&](int buf) {
+  // Widen a loaded step and put it into LDS stage `buf`.
+  auto store_step = [&](const v2u (&xa)[NA], const v2u (&xb)[NB], int buf) {
 #pragma unroll
     for (int i = 0; i < NA; ++i)
-      *reinterpret_cast<uint2*>(&sA[buf][((tid + kThreads * i) >> 3) * PITCH + a_cpos * 8]) = ra[i];
+      *reinterpret_cast<v4i*>(&sA0[buf * BM * PITCH + ((tid >> 3) + 32 * i) * PITCH + col * 16]) =
+          widen<A_UNSIGNED>(xa[i]);
     if (MODE == 1) {
 #pragma unroll
       for (int i = 0; i < NB; ++i)
-        *reinterpret_cast<uint2*>(&sB[buf][((tid + kThreads * i) >> 3) * PITCH + (tid & 7) * 8]) = rb[i];
+        *reinterpret_cast<v4i*>(&sB0[buf * BN * PITCH + ((tid >> 3) + 32 * i) * PITCH + col * 16]) =
+            widen<B_UNSIGNED>(xb[i]);
     } else {
 #pragma unroll
       for (int i = 0; i < NB; ++i)
-        *reinterpret_cast<uint2*>(
-            &sB[buf][x_row * PITCH + (tid / BN + i * (kThreads / BN)) * 8]) = rb[i];
+        *reinterpret_cast<v4i*>(
+            &sB0[buf * BN * PITCH + x_row * PITCH + (tid / BN + i * (kThreads / BN)) * 16]) =
+            widen<B_UNSIGNED>(xb[i]);
     }
   };
 
@@ -253,37 +312,47 @@ __global__ __launch_bounds__(kThreads) void k_implicit_gemm(const GemmArgs g) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
-  if (t_begin < t_end) {
-    load_tiles();
-    store_tiles(0);
-  }
-  __syncthreads();
-  int buf = 0;
-  for (int t0 = t_begin; t0 < t_end; t0 += BKC) {
-    const bool more = t0 + BKC < t_end;
-    if (more) load_tiles();
+  // One K step on the matrix cores: four 32x32x32 products per accumulator block; a lane
+  // feeds row (lane % 32) and chunk 2*kk + lane/32.
+  auto compute = [&](int buf) {
 #pragma unroll
     for (int kk = 0; kk < BKC / 2; ++kk) {
-      // one 32x32x32 step: lane holds row (lane % 32) and chunk 2*kk + lane/32
-      const int coff = (2 * kk + (lane >> 5)) * 8;
+      const int coff = (2 * kk + (lane >> 5)) * 16;
       v4i fa[TM], fb[TN];
 #pragma unroll
       for (int i = 0; i < TM; ++i)
-        fa[i] = widen<A_UNSIGNED>(*reinterpret_cast<const uint2*>(
-            &sA[buf][(wm + i * 32 + (lane & 31)) * PITCH + coff]));
+        fa[i] = *reinterpret_cast<const v4i*>(
+            &sA0[buf * BM * PITCH + (wm + i * 32 + (lane & 31)) * PITCH + coff]);
 #pragma unroll
       for (int j = 0; j < TN; ++j)
-        fb[j] = widen<B_UNSIGNED>(*reinterpret_cast<const uint2*>(
-            &sB[buf][(wn + j * 32 + (lane & 31)) * PITCH + coff]));
+        fb[j] = *reinterpret_cast<const v4i*>(
+            &sB0[buf * BN * PITCH + (wn + j * 32 + (lane & 31)) * PITCH + coff]);
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], acc[i][j], 0, 0, 0);
     }
-    if (more) store_tiles(buf ^ 1);
+  };
+
+  // Software pipeline: while step s runs out of LDS stage s % 2, step s + 1 sits in one
+  // register set (its loads issued a whole step ago) and step s + 2 is being loaded into
+  // the other.  No branch inside the loop touches memory, so the loads of one step are
+  // only waited for a full step after they were issued.
+  v2u ra0[NA], rb0[NB], ra1[NA], rb1[NB];
+  load_step(ra0, rb0);
+  load_step(ra1, rb1);
+  store_step(ra0, rb0, 0);
+  __syncthreads();
+  for (int s = 0; s < n_steps; s += 2) {
+    load_step(ra0, rb0);
+    compute(0);
+    store_step(ra1, rb1, 1);
     __syncthreads();
-    buf ^= 1;
+    load_step(ra1, rb1);
+    compute(1);
+    store_step(ra0, rb0, 0);
+    __syncthreads();
   }
 
   // ---- epilogue.  32x32 accumulator block: lane holds column (lane % 32) and rows
@@ -292,16 +361,16 @@ __global__ __launch_bounds__(kThreads) void k_implicit_gemm(const GemmArgs g) {
   const float scale = (g.epi == 1) ? 0.0f : output_scale(g);
 #pragma unroll
   for (int j = 0; j < TN; ++j) {
-    const int col = j0 + wn + j * 32 + (lane & 31);
-    if (col >= g.NJ) continue;
+    const int col_j = j0 + wn + j * 32 + (lane & 31);
+    if (col_j >= g.NJ) continue;
     long long base;
     long long row_stride;
     if (g.epi == 0) {
-      const int n_ = col / HW, hw = col - n_ * HW;
+      const int n_ = col_j / HW, hw = col_j - n_ * HW;
       base = (long long)n_ * g.C * HW + hw;
       row_stride = HW;
     } else {
-      base = col;
+      base = col_j;
       row_stride = g.NJ;
     }
 #pragma unroll
@@ -346,50 +415,98 @@ void fill_geom(GemmArgs& g, const ConvGeom& c) {
   g.P = c.P; g.Q = c.Q; g.stride = c.stride; g.pad = c.pad;
 }
 
-template <int BM, int MODE>
-void launch_variant(const GemmArgs& g, bool a_uns, bool b_uns, unsigned grid, size_t dyn,
-                    hipStream_t s) {
-  if (a_uns)
-    LBT_LAUNCH((k_implicit_gemm<BM, true, false, MODE>), dim3(grid), dim3(kThreads), dyn, s, g);
-  else if (b_uns)
-    LBT_LAUNCH((k_implicit_gemm<BM, false, true, MODE>), dim3(grid), dim3(kThreads), dyn, s, g);
-  else
-    LBT_LAUNCH((k_implicit_gemm<BM, false, false, MODE>), dim3(grid), dim3(kThreads), dyn, s, g);
+constexpr size_t kMaxDynLds = 100 * 1024;
+
+template <int BM, int BN, bool A_UNS, bool B_UNS, int MODE>
+int launch_one(const GemmArgs& g, unsigned grid, size_t dyn, hipStream_t s) {
+  const auto kernel = k_implicit_gemm<BM, BN, A_UNS, B_UNS, MODE>;
+  // more than 64 KiB of dynamic LDS has to be allowed once per kernel
+  static bool raised = false;
+  if (!raised) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)kMaxDynLds) != hipSuccess)
+      return LBT_ERR_HIP;
+    raised = true;
+  }
+  LBT_LAUNCH(kernel, dim3(grid), dim3(kThreads), dyn, s, g);
+  return LBT_OK;
 }
 
-int run_gemm(GemmArgs& g, int mode, bool a_uns, bool b_uns, int bm, int splits, int kid,
+template <int BM, int BN, int MODE>
+int launch_variant(const GemmArgs& g, bool a_uns, bool b_uns, unsigned grid, size_t dyn,
+                   hipStream_t s) {
+  if (a_uns) return launch_one<BM, BN, true, false, MODE>(g, grid, dyn, s);
+  if (b_uns) return launch_one<BM, BN, false, true, MODE>(g, grid, dyn, s);
+  return launch_one<BM, BN, false, false, MODE>(g, grid, dyn, s);
+}
+
+int run_gemm(GemmArgs& g, int mode, bool a_uns, bool b_uns, int bm, int bn, int splits, int kid,
              hipStream_t s) {
   // algorithmic work: the convolution's multiply-adds, padding taps included
   const double work = 2.0 * g.N * g.P * g.Q * (double)g.K * g.C * g.R * g.S;
   ProfScope prof(kid, work, s);
   if (a_uns && b_uns) return LBT_ERR_UNSUPPORTED;
+  // 32-bit buffer offsets: both code tensors below 2 GiB, with room for the rows of a
+  // ragged last tile
+  if ((unsigned long long)g.a_bytes >= (1ull << 31) || (unsigned long long)g.b_bytes >= (1ull << 31) ||
+      (unsigned long long)(g.M + 128) * g.lda + g.a_bytes >= (1ull << 32))
+    return LBT_ERR_UNSUPPORTED;
   g.tiles_m = (g.M + bm - 1) / bm;
-  g.tiles_n = (g.NJ + BN - 1) / BN;
+  g.tiles_n = (g.NJ + bn - 1) / bn;
   const long long total = (long long)g.tiles_m * g.tiles_n * splits;
   if (total > (1ll << 30)) return LBT_ERR_UNSUPPORTED;
   g.total_blocks = (int)total;
   const unsigned grid = (unsigned)((total + kXcds - 1) / kXcds * kXcds);
-  size_t dyn = 0;
+  size_t dyn = (size_t)2 * (bm + bn) * PITCH;
   if (mode == 0) {
-    dyn = (size_t)BN * g.R * g.S * sizeof(int);
-    if (dyn > 25 * 1024) return LBT_ERR_UNSUPPORTED;  // filter windows up to 7x7
-    if (bm == 64) launch_variant<64, 0>(g, false, false, grid, dyn, s);
-    else launch_variant<128, 0>(g, false, false, grid, dyn, s);
-  } else {
-    if (bm == 64) launch_variant<64, 1>(g, a_uns, b_uns, grid, dyn, s);
-    else launch_variant<128, 1>(g, a_uns, b_uns, grid, dyn, s);
+    if ((size_t)128 * g.R * g.S * sizeof(int) > 25 * 1024) return LBT_ERR_UNSUPPORTED;  // up to 7x7
+    dyn += (size_t)bn * g.R * g.S * sizeof(int);
+    a_uns = b_uns = false;
   }
+  if (dyn > kMaxDynLds) return LBT_ERR_UNSUPPORTED;
+  int rc = LBT_ERR_UNSUPPORTED;
+#define LBT_GEMM_CASE(BM_, BN_)                                                             \
+  if (bm == BM_ && bn == BN_) {                                                             \
+    rc = (mode == 0) ? launch_variant<BM_, BN_, 0>(g, a_uns, b_uns, grid, dyn, s)           \
+                     : launch_variant<BM_, BN_, 1>(g, a_uns, b_uns, grid, dyn, s);          \
+  }
+  LBT_GEMM_CASE(128, 128)
+  LBT_GEMM_CASE(64, 128)
+  LBT_GEMM_CASE(128, 64)
+  LBT_GEMM_CASE(64, 64)
+#undef LBT_GEMM_CASE
+  if (rc) return rc;
   LBT_LAUNCH_CHECK();
   return LBT_OK;
 }
 
+// Tile shape: the largest of 128x128, 64x128 / 128x64, 64x64 that still yields one
+// workgroup per compute unit (measured on the ResNet-50 shapes: below that the smaller
+// tile wins, above it the larger one does).
+void pick_tile(int M, int NJ, int splits, int* bm, int* bn) {
+  const int cand[4][2] = {{128, 128}, {64, 128}, {128, 64}, {64, 64}};
+  for (int i = 0; i < 4; ++i) {
+    const int m = cand[i][0], n = cand[i][1];
+    if (M <= 64 && m == 128) continue;
+    if (NJ <= 64 && n == 128) continue;
+    const long long blocks = (long long)((M + m - 1) / m) * ((NJ + n - 1) / n) * splits;
+    *bm = m;
+    *bn = n;
+    if (blocks >= 256) return;
+  }
+}
+
 // Direct (no split) product with signed operands: |sum| <= chunks*16 * 112 * 112 < 2^31.
 int run_direct(GemmArgs& g, int mode, hipStream_t s) {
-  g.chunks_per_split = g.chunks;
+  g.steps = (g.chunks + BKC - 1) / BKC;
+  g.steps_per_split = g.steps;
   g.shift = 8;
   g.scale_kind = 0;
   if ((long long)g.chunks * 16 * 12544 >= (1ll << 31)) return LBT_ERR_OVERFLOW;
-  return run_gemm(g, mode, false, false, g.M <= 64 ? 64 : 128, 1, KID_GEMM_DX, s);
+  int bm, bn;
+  pick_tile(g.M, g.NJ, 1, &bm, &bn);
+  return run_gemm(g, mode, false, false, bm, bn, 1, KID_GEMM_DX, s);
 }
 
 int run_splitk(GemmArgs& g, bool a_uns, bool b_uns, long long true_k, int32_t* acc, int32_t* partial,
@@ -400,17 +517,18 @@ int run_splitk(GemmArgs& g, bool a_uns, bool b_uns, long long true_k, int32_t* a
   // the exact sum must fit int32
   if (true_k * (x_unsigned ? 105 : 49) >= (1ll << 31)) return LBT_ERR_OVERFLOW;
   const SplitPlan plan = plan_split_k(g.M, g.NJ, g.chunks);
-  g.chunks_per_split = plan.chunks_per_split;
+  g.steps = (g.chunks + BKC - 1) / BKC;
+  g.steps_per_split = plan.chunks_per_split / BKC;
   int rc;
   if (plan.splits == 1) {
     g.epi = 2;
     g.acc = acc;
-    return run_gemm(g, 1, a_uns, b_uns, plan.bm, 1, KID_GEMM_DW, s);
+    return run_gemm(g, 1, a_uns, b_uns, plan.bm, 128, 1, KID_GEMM_DW, s);
   }
   g.epi = 1;
   g.acc = nullptr;
   g.partial = partial;
-  if ((rc = run_gemm(g, 1, a_uns, b_uns, plan.bm, plan.splits, KID_GEMM_DW, s))) return rc;
+  if ((rc = run_gemm(g, 1, a_uns, b_uns, plan.bm, 128, plan.splits, KID_GEMM_DW, s))) return rc;
   const long long n_out = (long long)g.M * g.NJ;
   ProfScope prof(KID_FINALIZE, (double)n_out, s);
   g.acc = acc;
@@ -427,7 +545,7 @@ int run_splitk(GemmArgs& g, bool a_uns, bool b_uns, long long true_k, int32_t* a
 SplitPlan plan_split_k(int M, int NJ, int chunks) {
   SplitPlan p;
   p.bm = M <= 64 ? 64 : 128;
-  const long long tiles = (long long)((M + p.bm - 1) / p.bm) * ((NJ + BN - 1) / BN);
+  const long long tiles = (long long)((M + p.bm - 1) / p.bm) * ((NJ + 127) / 128);
   const int iters = (chunks + BKC - 1) / BKC;
   long long splits = 512 / tiles;           // aim at about two workgroups per compute unit
   if (splits < 1) splits = 1;
@@ -451,11 +569,26 @@ int launch_conv_dx(const ConvGeom& c, const uint8_t* w_codes, const uint8_t* g_c
   g.B = g_codes;
   g.groups = c.Kp / kGranule;
   g.inner = c.R * c.S;
-  g.chunks = g.groups * g.inner;
-  g.lda = (long long)g.chunks * 8;
-  g.M = c.C;
+  // group count padded so that a K step of 8 chunks covers whole taps or part of one tap
+  if (g.groups <= 4) {
+    g.gp = g.groups == 3 ? 4 : g.groups;
+    g.gp_log2 = g.gp == 1 ? 0 : (g.gp == 2 ? 1 : 2);
+  } else {
+    g.gp = (g.groups + BKC - 1) / BKC * BKC;
+    g.gp_log2 = -1;
+  }
+  const long long padded = (long long)g.gp * g.inner;
+  const long long a_bytes = (long long)c.C * g.groups * g.inner * 8;
+  const long long b_bytes = (long long)c.N * g.groups * c.P * c.Q * 8;
   const long long nj = (long long)c.N * c.H * c.W;
-  if (nj > 0x7fffffffll) return LBT_ERR_UNSUPPORTED;
+  if (nj > 0x7fffffffll || padded > 0x7fffffffll / 16 || a_bytes >= (1ll << 31) ||
+      b_bytes >= (1ll << 31))
+    return LBT_ERR_UNSUPPORTED;
+  g.chunks = (int)padded;
+  g.lda = (unsigned)(g.groups * g.inner * 8);
+  g.a_bytes = (unsigned)a_bytes;
+  g.b_bytes = (unsigned)b_bytes;
+  g.M = c.C;
   g.NJ = (int)nj;
   g.epi = 0;
   g.st = st; g.sc = sc;
@@ -473,9 +606,14 @@ int launch_conv_dw(const ConvGeom& c, const uint8_t* g_codes, const uint8_t* x_c
   g.groups = c.Np / kGranule;
   g.inner = c.P * c.Q;
   const long long chunks = (long long)g.inner * g.groups;
-  if (chunks > 0x7fffffffll / 16) return LBT_ERR_UNSUPPORTED;
+  const long long a_bytes = chunks * 8 * c.K;
+  const long long b_bytes = (long long)c.C * g.groups * c.H * c.W * 8;
+  if (chunks > 0x7fffffffll / 16 || a_bytes >= (1ll << 31) || b_bytes >= (1ll << 31))
+    return LBT_ERR_UNSUPPORTED;
   g.chunks = (int)chunks;
-  g.lda = chunks * 8;
+  g.lda = (unsigned)(chunks * 8);
+  g.a_bytes = (unsigned)a_bytes;
+  g.b_bytes = (unsigned)b_bytes;
   g.M = c.K;
   g.NJ = c.C * c.R * c.S;
   g.st = st; g.sc = sc;
@@ -495,7 +633,11 @@ int launch_linear_dx(const ConvGeom& c, const uint8_t* w_codes, const uint8_t* g
   g.groups = c.Kp / kGranule;
   g.inner = 1;
   g.chunks = g.groups;
-  g.lda = (long long)g.chunks * 8;
+  if ((long long)g.chunks * 8 * c.N >= (1ll << 31) || (long long)g.chunks * 8 * c.C >= (1ll << 31))
+    return LBT_ERR_UNSUPPORTED;
+  g.lda = (unsigned)(g.chunks * 8);
+  g.a_bytes = g.lda * (unsigned)c.N;
+  g.b_bytes = g.lda * (unsigned)c.C;
   g.M = c.N;
   g.NJ = c.C;
   g.epi = 2;
@@ -514,7 +656,11 @@ int launch_linear_dw(const ConvGeom& c, const uint8_t* g_codes, const uint8_t* x
   g.groups = c.Np / kGranule;
   g.inner = 1;
   g.chunks = g.groups;
-  g.lda = (long long)g.chunks * 8;
+  if ((long long)g.chunks * 8 * c.C >= (1ll << 31) || (long long)g.chunks * 8 * c.K >= (1ll << 31))
+    return LBT_ERR_UNSUPPORTED;
+  g.lda = (unsigned)(g.chunks * 8);
+  g.a_bytes = g.lda * (unsigned)c.C;
+  g.b_bytes = g.lda * (unsigned)c.K;
   g.M = c.C;
   g.NJ = c.K;
   g.st = st; g.sc = sc;

@@ -83,6 +83,7 @@ struct RelayoutIo {
   lbt_grad_state* st;
   uint8_t* out_b;
   uint8_t* out_a;
+  int a_lmajor;  // out_a as [B][L][A/16][16] instead of [B][A/16][L][16]
 };
 // Gradient flavour: clip value from gamma in *st and the maximum; statistics go to *st.
 int launch_quantize_relayout_grad(const float* g, int64_t A, int64_t B, int64_t L,
@@ -109,7 +110,7 @@ struct SplitPlan {
 };
 SplitPlan plan_split_k(int M, int NJ, int chunks);
 
-// dX: A = W codes [C][Kp/16][R*S][16], B = dY codes [N][Kp/16][P*Q][16]; out/acc [N][C][H][W].
+// dX: A = W codes [C][R*S][Kp/16][16], B = dY codes [N][Kp/16][P*Q][16]; out/acc [N][C][H][W].
 int launch_conv_dx(const ConvGeom& g, const uint8_t* w_codes, const uint8_t* g_codes,
                    const lbt_grad_state* st, const OperandScalars* sc, float* dX, int32_t* acc,
                    hipStream_t s);

@@ -359,7 +359,8 @@ __global__ __launch_bounds__(kThreads) void k_quantize_flat(
 // ---------------------------------------------------------------------------
 // quantize + re-layout of T[A][B][L] (L contiguous) into the GEMM layouts
 //   out_b [A][BG][L][16]  sixteen consecutive b per 8-byte granule (BG = Bp/16)
-//   out_a [B][AG][L][16]  sixteen consecutive a per 8-byte granule (AG = Ap/16)
+//   out_a [B][AG][L][16]  sixteen consecutive a per 8-byte granule (AG = Ap/16);
+//         [B][L][AG][16] when a_lmajor is set (the dX kernel reads weights tap by tap)
 // zero padded in the last granule.  A workgroup owns a 16(a) x 16(b) x TL(l)
 // tile: it quantizes into LDS (one byte per code, [a][b][l]), then each thread
 // gathers the sixteen codes of one granule and stores 8 bytes; consecutive
@@ -381,6 +382,7 @@ struct TileArgs {
   uint32_t* bad_out;
   uint2* out_b;
   uint2* out_a;
+  int a_lmajor;
 };
 
 // Phase B: gather granules out of the LDS tile.  `pitch` = bytes per (a,b) row.
@@ -413,7 +415,9 @@ __device__ __forceinline__ void store_granules(const TileArgs& t, const uint8_t*
         w0 |= (uint32_t)tile[(j * 16 + b) * pitch + l] << (4 * j);
         w1 |= (uint32_t)tile[((8 + j) * 16 + b) * pitch + l] << (4 * j);
       }
-      t.out_a[((long long)(b0 + b) * t.AG + ag) * t.L + l0 + l] = make_uint2(w0, w1);
+      const long long o = t.a_lmajor ? ((long long)(b0 + b) * t.L + l0 + l) * t.AG + ag
+                                     : ((long long)(b0 + b) * t.AG + ag) * t.L + l0 + l;
+      t.out_a[o] = make_uint2(w0, w1);
     }
   }
 }
@@ -473,9 +477,11 @@ __device__ __forceinline__ void store_granules_w4(const TileArgs& t, const uint8
       if (b0 + b >= t.B) continue;
       uint2 g4[4];
       granules4(tile, b * pitch + l, 16 * pitch, g4);
-      uint2* dst = t.out_a + ((long long)(b0 + b) * t.AG + ag) * t.L + l0 + l;
+      const long long o = t.a_lmajor ? ((long long)(b0 + b) * t.L + l0 + l) * t.AG + ag
+                                     : ((long long)(b0 + b) * t.AG + ag) * t.L + l0 + l;
+      const int step = t.a_lmajor ? t.AG : 1;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) dst[i] = g4[i];
+      for (int i = 0; i < 4; ++i) t.out_a[o + (long long)i * step] = g4[i];
     }
   }
 }
@@ -780,6 +786,7 @@ static void fill_tile_args(TileArgs& t, const float* x, int64_t A, int64_t B, in
   t.st = io.st;
   t.out_b = reinterpret_cast<uint2*>(io.out_b);
   t.out_a = reinterpret_cast<uint2*>(io.out_a);
+  t.a_lmajor = io.a_lmajor;
 }
 
 int launch_quantize_relayout_grad(const float* g, int64_t A, int64_t B, int64_t L,
