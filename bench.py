@@ -226,18 +226,22 @@ def main():
             out["roofline"] = {"kernel": dom, "bound": "hbm", "achieved": ach,
                                "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBPS,
                                "traffic": None}
-        # the gradient-quantize pass = its share of the maximum kernel + the quantize kernel,
-        # rated at the algorithmic 4.5 B per gradient element
-        q, am = kernels.get("k_quantize_relayout(grad)"), kernels.get("k_absmax")
+        # the quantize pass = the maximum kernel + the quantize kernel (gradient, activations
+        # and weights of a layer share both launches), rated at the algorithmic 4.5 B per
+        # quantized element
+        q, am = kernels.get("k_quantize_layer"), kernels.get("k_absmax3")
         if q and am:
             n_all = n_grad + sum(L.X.numel() + L.W.numel() for L in layers)
-            t_ms = q["ms_per_step"] + am["ms_per_step"] * n_grad / n_all
-            gbps = n_grad * BYTES_PER_GRAD_ELEMENT / (t_ms * 1e-3) / 1e9
+            t_ms = q["ms_per_step"] + am["ms_per_step"]
+            if "k_quantize_grad" in kernels:     # large gradients have a launch of their own
+                t_ms += kernels["k_quantize_grad"]["ms_per_step"]
+            gbps = n_all * BYTES_PER_GRAD_ELEMENT / (t_ms * 1e-3) / 1e9
             out["quantize_pass"] = {"GBps": gbps, "frac_of_hbm_peak": gbps / PEAK_HBM_GBPS,
-                                    "ms_per_step": t_ms, "bytes_per_element": BYTES_PER_GRAD_ELEMENT}
+                                    "ms_per_step": t_ms, "bytes_per_element": BYTES_PER_GRAD_ELEMENT,
+                                    "elements_per_step": n_all}
         # the two contractions against the int8 MFMA peak and against each layer's own
         # roofline min(compute, memory) with the algorithmic bytes of the packed operands
-        g = [kernels[n] for n in kernels if "gemm" in n or "finalize" in n]
+        g = [kernels[n] for n in kernels if "gemm" in n or "splitk" in n]
         if g:
             t_ms = sum(k["ms_per_step"] for k in g)
             tops = gemm_ops / (t_ms * 1e-3) / 1e12

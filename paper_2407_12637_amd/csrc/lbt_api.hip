@@ -86,26 +86,31 @@ int backward_common(const float* X, const float* W, const float* dY, const ConvG
   const int64_t wA = w_is_ck ? g.C : g.K, wB = w_is_ck ? g.K : g.C, wL = w_is_ck ? 1 : RS;
   // 1. maxima of dY, and of X / W where no clip value was given, in one launch
   if ((rc = launch_absmax3(dY, n_dy, 1, want_cx ? X : nullptr, n_x, x_unsigned ? 0 : 1,
-                           want_cw ? W : nullptr, n_w, 1, pmax, &nblocks, s)))
+                           want_cw ? W : nullptr, n_w, 1, pmax, &nblocks, st, s)))
     return rc;
-  // 2. gradient codes in the layouts the two products read
+  // 2. codes of all three tensors in the layouts the two products read, one launch:
+  //    gradient for both products, activations for dW, weights for dX (convolution weights
+  //    tap-major [C][R*S][Kp/16][16]: the dX kernel walks the contraction tap by tap)
   {
-    RelayoutIo io{pmax, nblocks, 0, st, dX ? g_npqk : nullptr, dW ? g_kpqn : nullptr, 0};
-    if ((rc = launch_quantize_relayout_grad(dY, g.N, g.K, PQ, io, seed, rounding, s))) return rc;
+    LayerTensors q{};
+    q.seed = seed;
+    q.rounding = rounding;
+    q.x_unsigned = x_unsigned;
+    q.tensor[0] = {dY, g.N, g.K, PQ,
+                   RelayoutIo{pmax, nblocks, 0, st, dX ? g_npqk : nullptr, dW ? g_kpqn : nullptr, 0},
+                   0.0f, nullptr, nullptr};
+    if (dW)
+      q.tensor[1] = {X, g.N, g.C, HW, RelayoutIo{pmax, nblocks, 1, st, nullptr, x_chwn, 0},
+                     c_x, &sc->c_x, &sc->bad_x};
+    if (dX)
+      q.tensor[2] = {W, wA, wB, wL,
+                     RelayoutIo{pmax, nblocks, 2, st, w_is_ck ? w_crsk : nullptr,
+                                w_is_ck ? nullptr : w_crsk, 1},
+                     c_w, &sc->c_w, &sc->bad_w};
+    if ((rc = launch_quantize_layer(q, s))) return rc;
   }
-  // 3. activation codes
-  if (dW) {
-    RelayoutIo io{pmax, nblocks, 1, st, nullptr, x_chwn, 0};
-    if ((rc = launch_quantize_relayout_operand(X, g.N, g.C, HW, io, c_x, x_unsigned, &sc->c_x,
-                                               &sc->bad_x, s)))
-      return rc;
-  }
-  // 4. weight codes, then the two products
+  // 3. the two products
   if (dX) {
-    // conv weights tap-major [C][R*S][Kp/16][16]: the dX kernel walks the contraction tap by tap
-    RelayoutIo io{pmax, nblocks, 2, st, w_is_ck ? w_crsk : nullptr, w_is_ck ? nullptr : w_crsk, 1};
-    if ((rc = launch_quantize_relayout_operand(W, wA, wB, wL, io, c_w, 0, &sc->c_w, &sc->bad_w, s)))
-      return rc;
     rc = w_is_ck ? launch_linear_dx(g, w_crsk, g_npqk, st, sc, dX, acc_dX, s)
                  : launch_conv_dx(g, w_crsk, g_npqk, st, sc, dX, acc_dX, s);
     if (rc) return rc;
@@ -193,7 +198,7 @@ int lbt_quantize_grad(const float* g, int64_t n, lbt_grad_state* st, uint64_t se
   uint32_t* pmax =
       reinterpret_cast<uint32_t*>(static_cast<uint8_t*>(ws) + kWsScalarsBytes);
   int rc, nblocks = 0;
-  if ((rc = launch_absmax3(g, n, 1, nullptr, 0, 0, nullptr, 0, 0, pmax, &nblocks, s))) return rc;
+  if ((rc = launch_absmax3(g, n, 1, nullptr, 0, 0, nullptr, 0, 0, pmax, &nblocks, st, s))) return rc;
   return launch_quantize_flat_grad(g, n, pmax, nblocks, st, seed, rounding, codes, s);
 }
 
@@ -212,7 +217,7 @@ int lbt_quantize_operand(const float* x, int64_t n, float c, int is_unsigned, in
   int rc, nblocks = 0;
   if (!(c > 0.0f))
     if ((rc = launch_absmax3(nullptr, 0, 0, x, n, is_unsigned ? 0 : 1, nullptr, 0, 0, pmax, &nblocks,
-                             s)))
+                             nullptr, s)))
       return rc;
   return launch_quantize_flat_operand(x, n, c, pmax, nblocks, is_unsigned, codes, &sc->c_x,
                                       clip_scale_out, s);

@@ -33,9 +33,9 @@ struct OperandScalars {
 
 // ---- profile.hip: optional event timing of every launch ------------------------
 enum KernelId {
-  KID_BEGIN = 0, KID_ABSMAX, KID_GRAD_PREPARE, KID_OPERAND_PREPARE, KID_FLAT_GRAD, KID_FLAT_OPERAND,
-  KID_RELAYOUT_GRAD, KID_RELAYOUT_OPERAND, KID_GEMM_DX, KID_GEMM_DW, KID_ZERO, KID_FINALIZE,
-  KID_UPDATE, KID_STATE, KID_COUNT
+  KID_ABSMAX = 0, KID_FLAT_GRAD, KID_FLAT_OPERAND, KID_QUANTIZE_GRAD, KID_QUANTIZE_LAYER, KID_GEMM_DX,
+  KID_GEMM_DW,
+  KID_FINALIZE, KID_UPDATE, KID_STATE, KID_COUNT
 };
 // Records a start event now and a stop event when it goes out of scope (after the
 // launch it brackets).  `work` is the algorithmic work of the launch: elements for
@@ -64,9 +64,10 @@ constexpr size_t kWsHeaderBytes = kWsScalarsBytes + (size_t)kMaxPartialBlocks * 
 
 // One launch for the maxima of up to three tensors (null pointer = absent); partial
 // maxima go to pmax[block][tensor].  *nblocks_out = number of partial rows written.
+// st (may be null): its status is reset to OK for the quantizer launches that follow.
 int launch_absmax3(const float* p0, int64_t n0, int abs0, const float* p1, int64_t n1, int abs1,
                    const float* p2, int64_t n2, int abs2, uint32_t* pmax, int* nblocks_out,
-                   hipStream_t s);
+                   lbt_grad_state* st, hipStream_t s);
 int launch_quantize_flat_grad(const float* g, int64_t n, const uint32_t* pmax, int nblocks,
                               lbt_grad_state* st, uint64_t seed, int rounding, uint8_t* codes,
                               hipStream_t s);
@@ -85,14 +86,24 @@ struct RelayoutIo {
   uint8_t* out_a;
   int a_lmajor;  // out_a as [B][L][A/16][16] instead of [B][A/16][L][16]
 };
-// Gradient flavour: clip value from gamma in *st and the maximum; statistics go to *st.
-int launch_quantize_relayout_grad(const float* g, int64_t A, int64_t B, int64_t L,
-                                  const RelayoutIo& io, uint64_t seed, int rounding,
-                                  hipStream_t s);
-// Operand flavour: clip value c_given (> 0), else the tensor maximum; written to *c_out.
-int launch_quantize_relayout_operand(const float* x, int64_t A, int64_t B, int64_t L,
-                                     const RelayoutIo& io, float c_given, int is_unsigned,
-                                     float* c_out, uint32_t* bad_out, hipStream_t s);
+// The tensors of one layer, quantized by ONE launch: [0] the output gradient (clip value
+// from gamma in *st and the maximum; statistics go to *st), [1] the activations, [2] the
+// weights (clip value c_given if > 0, else the tensor maximum; written to *c_out).  A null
+// x marks an absent tensor.
+struct LayerTensors {
+  struct One {
+    const float* x;
+    int64_t A, B, L;
+    RelayoutIo io;
+    float c_given;
+    float* c_out;
+    uint32_t* bad_out;
+  } tensor[3];
+  uint64_t seed;
+  int rounding;
+  int x_unsigned;
+};
+int launch_quantize_layer(const LayerTensors& q, hipStream_t s);
 int launch_update_interval(lbt_grad_state* st, hipStream_t s);
 int launch_state_init(lbt_grad_state* st, const lbt_grad_state& v, hipStream_t s);
 

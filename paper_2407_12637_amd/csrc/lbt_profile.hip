@@ -25,10 +25,9 @@ std::vector<Record> g_records;
 std::vector<hipEvent_t> g_pool;
 
 const char* const kNames[KID_COUNT] = {
-    "k_begin",           "k_absmax",          "k_grad_prepare",      "k_operand_prepare",
-    "k_quantize_flat(grad)", "k_quantize_flat(operand)", "k_quantize_relayout(grad)",
-    "k_quantize_relayout(operand)", "k_implicit_gemm(dX)", "k_implicit_gemm(dW)", "k_zero_i32",
-    "k_finalize_dw",     "k_update_interval", "k_state_set"};
+    "k_absmax3",           "k_quantize_flat(grad)", "k_quantize_flat(operand)",
+    "k_quantize_grad",     "k_quantize_layer",      "k_implicit_gemm(dX)",   "k_implicit_gemm(dW)",
+    "k_splitk_reduce",     "k_update_interval",     "k_state_set"};
 
 hipEvent_t take_event() {
   if (!g_pool.empty()) {

@@ -26,6 +26,8 @@ constexpr int kThreads = 256;
 constexpr uint32_t kInfBits = 0x7f800000u;
 constexpr unsigned long long kTicket = 1ull << 40;
 constexpr unsigned long long kCountMask = kTicket - 1;
+// gradient tensors of at least this many elements are quantized by a launch of their own
+constexpr double kOwnLaunchElements = 16.0 * 1024 * 1024;
 
 // ---------------------------------------------------------------------------
 // Philox4x32-10 (Salmon et al., SC'11): counter-based generator, 10 rounds.
@@ -184,10 +186,9 @@ __device__ __forceinline__ GradSetup grad_setup(const lbt_grad_state* st, const 
 // One atomic per workgroup carries the clip-out count and the arrival ticket; the
 // last workgroup to arrive publishes the statistics and clears the word.
 __device__ __forceinline__ void grad_finish(lbt_grad_state* st, const GradSetup& g, uint32_t cnt,
-                                            unsigned long long n_total) {
+                                            unsigned long long n_total, unsigned long long nblk) {
   const uint32_t tot = block_sum(cnt);
   if (threadIdx.x == 0) {
-    const unsigned long long nblk = (unsigned long long)gridDim.x * gridDim.y * gridDim.z;
     const unsigned long long old =
         atomicAdd(reinterpret_cast<unsigned long long*>(&st->sync_word), kTicket + tot);
     if ((old >> 40) == nblk - 1) {
@@ -196,7 +197,9 @@ __device__ __forceinline__ void grad_finish(lbt_grad_state* st, const GradSetup&
       st->gmax = g.gmax;
       st->clip = g.c;
       st->scale = (g.c > 0.0f) ? (float)((double)g.c / 7.0) : 0.0f;
-      st->status = g.status;
+      // k_absmax3 has reset the status to OK; an operand quantizer of the same launch
+      // may already have flagged a non-finite operand, which must stay
+      if (g.status != LBT_STATUS_OK) atomicCAS(&st->status, LBT_STATUS_OK, g.status);
       st->sync_word = 0;
     }
   }
@@ -206,7 +209,7 @@ __device__ __forceinline__ void grad_finish(lbt_grad_state* st, const GradSetup&
 __device__ __forceinline__ float operand_setup(float c_given, const uint32_t* pmax, int nblocks,
                                                int col, bool is_unsigned, float* c_out,
                                                uint32_t* bad_out, lbt_grad_state* st,
-                                               float* clip_scale_out) {
+                                               float* clip_scale_out, bool first_block) {
   float c = c_given;
   bool bad = false;
   if (!(c > 0.0f)) {
@@ -214,7 +217,7 @@ __device__ __forceinline__ float operand_setup(float c_given, const uint32_t* pm
     if (bits >= kInfBits) { bad = true; c = 0.0f; }
     else c = __uint_as_float(bits);
   }
-  if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0) {
+  if (first_block && threadIdx.x == 0) {
     if (c_out) *c_out = c;
     if (bad_out) *bad_out = bad ? 1u : 0u;
     if (bad && st) st->status = LBT_STATUS_NONFINITE;
@@ -270,8 +273,11 @@ __device__ __forceinline__ uint32_t max_key4(const float4& v, int use_abs) {
 }
 
 __global__ __launch_bounds__(kThreads) void k_absmax3(MaxSeg s0, MaxSeg s1, MaxSeg s2,
-                                                       long long per_block, uint32_t* pmax) {
+                                                       long long per_block, uint32_t* pmax,
+                                                       lbt_grad_state* st) {
   const int blk = blockIdx.x;
+  // every quantizer launch that follows reports into a fresh status
+  if (st && blk == 0 && threadIdx.x == 0) st->status = LBT_STATUS_OK;
   int t = 0;
   MaxSeg s = s0;
   if (blk >= s2.first_block) { s = s2; t = 2; }
@@ -312,7 +318,8 @@ __global__ __launch_bounds__(kThreads) void k_quantize_flat(
     gs = grad_setup(st, pmax, nblocks);
     c = gs.c;
   } else {
-    c = operand_setup(c_given, pmax, nblocks, 1, MODE == 1, c_out, nullptr, nullptr, clip_scale_out);
+    c = operand_setup(c_given, pmax, nblocks, 1, MODE == 1, c_out, nullptr, nullptr, clip_scale_out,
+                      blockIdx.x == 0);
   }
   const QConst qc = make_qconst(c, MODE == 1);
   const bool live = c > 0.0f;
@@ -353,7 +360,7 @@ __global__ __launch_bounds__(kThreads) void k_quantize_flat(
       for (int j = 0; j < nbytes; ++j) codes[gi * 4 + j] = (uint8_t)(word >> (8 * j));
     }
   }
-  if (kGrad) grad_finish(st, gs, cnt, (unsigned long long)n);
+  if (kGrad) grad_finish(st, gs, cnt, (unsigned long long)n, gridDim.x);
 }
 
 // ---------------------------------------------------------------------------
@@ -555,9 +562,16 @@ __host__ __device__ inline int window_len(int L) {
   return (L % 8 == 0) ? (per + 7) / 8 * 8 : (per + 3) / 4 * 4;
 }
 
+// Where a workgroup stands inside its tensor's grid of tiles.
+struct TileCoord {
+  int x, y, z;          // tile index along l, b, a
+  unsigned n_blocks;    // workgroups that work on this tensor
+  bool first;           // the tensor's first workgroup
+};
+
 template <int MODE, bool SMALL>
-__global__ __launch_bounds__(kThreads) void k_quantize_stream(const TileArgs t, int pitch, int tl) {
-  extern __shared__ __attribute__((aligned(8))) uint8_t dyn_tile[];
+__device__ __forceinline__ void stream_body(const TileArgs& t, int pitch, int tl, const TileCoord& bc,
+                                            uint8_t* dyn_tile) {
   constexpr bool kGrad = MODE >= 2;
   GradSetup gs{};
   float c;
@@ -568,15 +582,15 @@ __global__ __launch_bounds__(kThreads) void k_quantize_stream(const TileArgs t, 
     c = *t.c_ptr;
   } else {
     c = operand_setup(t.c_given, t.pmax, t.nblocks, t.pmax_col, MODE == 1, t.c_out, t.bad_out, t.st,
-                      nullptr);
+                      nullptr, bc.first);
   }
   const QConst qc = make_qconst(c, MODE == 1);
   const bool live = c > 0.0f;
   const unsigned long long step = (MODE == 3) ? t.st->step : 0ull;
-  const int l0 = blockIdx.x * tl, b0 = blockIdx.y * 16, a0 = blockIdx.z * 16;
+  const int l0 = bc.x * tl, b0 = bc.y * 16, a0 = bc.z * 16;
 
   uint32_t cnt = 0;
-  auto quantize_item = [&](const ItemPos& p, const float v[8]) {
+  auto quantize_item = [&](const ItemPos& p, const float v[8]) __attribute__((always_inline)) {
     // eight codes of one generator block -> LDS bytes
     Philox4 rnd{};
     if (MODE == 3 && live) rnd = philox_block((unsigned long long)p.e0 >> 3, step, t.seed);
@@ -618,15 +632,17 @@ __global__ __launch_bounds__(kThreads) void k_quantize_stream(const TileArgs t, 
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       p[i] = item_pos<SMALL>(t, a0, b0, l0, tl, base + i * kThreads + threadIdx.x);
-      if (live) load8(t.x, p[i], v[i]);
+      load8(t.x, p[i], v[i]);  // unconditional (also when every code is 0): no branch between loads
     }
+    // keep the eight loads together ahead of the arithmetic that consumes them
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int i = 0; i < 4; ++i) quantize_item(p[i], v[i]);
   }
   __syncthreads();
   if (SMALL) store_granules(t, dyn_tile, pitch, t.L, a0, b0, 0);
   else store_granules_w4(t, dyn_tile, pitch, min(tl, t.L - l0), a0, b0, l0);
-  if (kGrad) grad_finish(t.st, gs, cnt, (unsigned long long)t.A * t.B * t.L);
+  if (kGrad) grad_finish(t.st, gs, cnt, (unsigned long long)t.A * t.B * t.L, bc.n_blocks);
 }
 
 // ---------------------------------------------------------------------------
@@ -634,9 +650,8 @@ __global__ __launch_bounds__(kThreads) void k_quantize_stream(const TileArgs t, 
 // tile 16 x 16 x TL with one scalar load per element.  TL = 1 serves matrices.
 // ---------------------------------------------------------------------------
 template <int MODE, int TL>
-__global__ __launch_bounds__(kThreads) void k_quantize_tile_generic(const TileArgs t) {
+__device__ __forceinline__ void generic_body(const TileArgs& t, const TileCoord& bc, uint8_t* tile) {
   constexpr int PITCH = (TL == 1) ? 1 : TL + 4;
-  __shared__ __attribute__((aligned(8))) uint8_t tile[256 * PITCH];
   GradSetup gs{};
   float c;
   if (MODE >= 2) {
@@ -646,12 +661,12 @@ __global__ __launch_bounds__(kThreads) void k_quantize_tile_generic(const TileAr
     c = *t.c_ptr;
   } else {
     c = operand_setup(t.c_given, t.pmax, t.nblocks, t.pmax_col, MODE == 1, t.c_out, t.bad_out, t.st,
-                      nullptr);
+                      nullptr, bc.first);
   }
   const QConst qc = make_qconst(c, MODE == 1);
   const bool live = c > 0.0f;
   const unsigned long long step = (MODE == 3) ? t.st->step : 0ull;
-  const int l0 = blockIdx.x * TL, b0 = blockIdx.y * 16, a0 = blockIdx.z * 16;
+  const int l0 = bc.x * TL, b0 = bc.y * 16, a0 = bc.z * 16;
   uint32_t cnt = 0;
   for (int idx = threadIdx.x; idx < 256 * TL; idx += kThreads) {
     const int l = idx % TL, row = idx / TL;
@@ -667,7 +682,73 @@ __global__ __launch_bounds__(kThreads) void k_quantize_tile_generic(const TileAr
   }
   __syncthreads();
   store_granules(t, tile, PITCH, TL, a0, b0, l0);
-  if (MODE >= 2) grad_finish(t.st, gs, cnt, (unsigned long long)t.A * t.B * t.L);
+  if (MODE >= 2) grad_finish(t.st, gs, cnt, (unsigned long long)t.A * t.B * t.L, bc.n_blocks);
+}
+
+// ---------------------------------------------------------------------------
+// One launch quantizes up to three tensors of a layer (output gradient, activations,
+// weights): workgroups [first, first + n_blocks) belong to a tensor and walk its tiles in
+// the order l fastest, then b, then a.
+// ---------------------------------------------------------------------------
+enum TileKind { kGenericTile = 0, kGenericColumn, kWindowed, kWholeRow };
+
+struct Segment {
+  TileArgs t;
+  int kind;             // TileKind
+  int pitch, tl;        // LDS row pitch and tile length along l (streaming kinds)
+  unsigned gx, gy;      // tiles along l and b
+  unsigned first, n_blocks;
+};
+
+template <int MODE>
+__device__ __forceinline__ void run_segment(const Segment& sg, unsigned blk, uint8_t* lds) {
+  const unsigned local = blk - sg.first;
+  TileCoord bc;
+  bc.x = (int)(local % sg.gx);
+  const unsigned rest = local / sg.gx;
+  bc.y = (int)(rest % sg.gy);
+  bc.z = (int)(rest / sg.gy);
+  bc.n_blocks = sg.n_blocks;
+  bc.first = local == 0;
+  switch (sg.kind) {
+    case kWindowed: stream_body<MODE, false>(sg.t, sg.pitch, sg.tl, bc, lds); break;
+    case kWholeRow: stream_body<MODE, true>(sg.t, sg.pitch, sg.tl, bc, lds); break;
+    case kGenericColumn: generic_body<MODE, 1>(sg.t, bc, lds); break;
+    default: generic_body<MODE, 32>(sg.t, bc, lds);
+  }
+}
+
+// One tensor per launch, one tile kind per kernel: the large gradient tensors go through
+// these (measured: inside the multi-tensor kernel below the same loop runs at less than
+// half the speed on tensors of 25 M elements and more, while for small tensors the saved
+// launches matter more).
+template <int MODE, int KIND>
+__global__ __launch_bounds__(kThreads) void k_quantize_grad(const Segment sg) {
+  extern __shared__ __attribute__((aligned(16))) uint8_t dyn_tile[];
+  const unsigned local = blockIdx.x;
+  TileCoord bc;
+  bc.x = (int)(local % sg.gx);
+  const unsigned rest = local / sg.gx;
+  bc.y = (int)(rest % sg.gy);
+  bc.z = (int)(rest / sg.gy);
+  bc.n_blocks = sg.n_blocks;
+  bc.first = local == 0;
+  if (KIND == kWindowed) stream_body<MODE, false>(sg.t, sg.pitch, sg.tl, bc, dyn_tile);
+  else if (KIND == kWholeRow) stream_body<MODE, true>(sg.t, sg.pitch, sg.tl, bc, dyn_tile);
+  else if (KIND == kGenericColumn) generic_body<MODE, 1>(sg.t, bc, dyn_tile);
+  else generic_body<MODE, 32>(sg.t, bc, dyn_tile);
+}
+
+// GMODE: 2 nearest / 3 stochastic gradient quantizer; XMODE: 0 signed / 1 unsigned activations;
+// weights are always signed nearest.  A tensor with n_blocks == 0 is absent.
+template <int GMODE, int XMODE>
+__global__ __launch_bounds__(kThreads) void k_quantize_layer(const Segment sg, const Segment sx,
+                                                              const Segment sw) {
+  extern __shared__ __attribute__((aligned(16))) uint8_t dyn_tile[];
+  const unsigned blk = blockIdx.x;
+  if (blk < sx.first) run_segment<GMODE>(sg, blk, dyn_tile);
+  else if (blk < sw.first) run_segment<XMODE>(sx, blk, dyn_tile);
+  else run_segment<0>(sw, blk, dyn_tile);
 }
 
 inline int flat_grid(long long work_items) {
@@ -678,51 +759,50 @@ inline int flat_grid(long long work_items) {
   return (int)blocks;
 }
 
-enum TileKind { kGenericTile = 0, kWindowed, kWholeRow };
-
 TileKind tile_kind(const float* x, long long B, long long L) {
-  if (reinterpret_cast<uintptr_t>(x) % 16 != 0) return kGenericTile;
-  if (L >= 16 && L % 4 == 0) return kWindowed;
-  if (L >= 2 && L <= 248 && B % 16 == 0 && (B * L) % 8 == 0) return kWholeRow;
-  return kGenericTile;
+  if (reinterpret_cast<uintptr_t>(x) % 16 == 0) {
+    if (L >= 16 && L % 4 == 0) return kWindowed;
+    if (L >= 2 && L <= 248 && B % 16 == 0 && (B * L) % 8 == 0) return kWholeRow;
+  }
+  return L == 1 ? kGenericColumn : kGenericTile;
 }
 
-template <int MODE>
-int tile_dispatch(const TileArgs& t, hipStream_t s) {
-  if (t.AG > 65535 || t.BG > 65535) return LBT_ERR_UNSUPPORTED;
-  switch (tile_kind(t.x, t.B, t.L)) {
-    case kWindowed: {
-      const int tl = window_len(t.L), pitch = 72;
-      dim3 grid((unsigned)((t.L + tl - 1) / tl), (unsigned)t.BG, (unsigned)t.AG);
-      LBT_LAUNCH((k_quantize_stream<MODE, false>), grid, dim3(kThreads), (size_t)256 * pitch,
-                         s, t, pitch, tl);
+// Tile grid, LDS need and kernel variant of one tensor; returns the dynamic LDS bytes.
+size_t plan_segment(Segment& sg) {
+  const TileArgs& t = sg.t;
+  sg.kind = tile_kind(t.x, t.B, t.L);
+  sg.gy = (unsigned)t.BG;
+  size_t lds;
+  switch (sg.kind) {
+    case kWindowed:
+      sg.tl = window_len(t.L);
+      sg.pitch = 72;
+      sg.gx = (unsigned)((t.L + sg.tl - 1) / sg.tl);
+      lds = (size_t)256 * sg.pitch;
       break;
-    }
-    case kWholeRow: {
-      const int pitch = (t.L + 3) / 4 * 4 + 4;
-      dim3 grid(1, (unsigned)t.BG, (unsigned)t.AG);
-      LBT_LAUNCH((k_quantize_stream<MODE, true>), grid, dim3(kThreads), (size_t)256 * pitch,
-                         s, t, pitch, t.L);
+    case kWholeRow:
+      sg.tl = t.L;
+      sg.pitch = (t.L + 3) / 4 * 4 + 4;
+      sg.gx = 1;
+      lds = (size_t)256 * sg.pitch;
       break;
-    }
+    case kGenericColumn:
+      sg.tl = 1; sg.pitch = 1; sg.gx = 1;
+      lds = 256;
+      break;
     default:
-      if (t.L == 1) {
-        dim3 grid(1, (unsigned)t.BG, (unsigned)t.AG);
-        LBT_LAUNCH((k_quantize_tile_generic<MODE, 1>), grid, dim3(kThreads), 0, s, t);
-      } else {
-        dim3 grid((unsigned)((t.L + 31) / 32), (unsigned)t.BG, (unsigned)t.AG);
-        LBT_LAUNCH((k_quantize_tile_generic<MODE, 32>), grid, dim3(kThreads), 0, s, t);
-      }
+      sg.tl = 32; sg.pitch = 36;
+      sg.gx = (unsigned)((t.L + 31) / 32);
+      lds = (size_t)256 * 36;
   }
-  LBT_LAUNCH_CHECK();
-  return LBT_OK;
+  return lds;
 }
 
 }  // namespace
 
 int launch_absmax3(const float* p0, int64_t n0, int abs0, const float* p1, int64_t n1, int abs1,
                    const float* p2, int64_t n2, int abs2, uint32_t* pmax, int* nblocks_out,
-                   hipStream_t s) {
+                   lbt_grad_state* st, hipStream_t s) {
   if (!p0) n0 = 0;
   if (!p1) n1 = 0;
   if (!p2) n2 = 0;
@@ -738,7 +818,7 @@ int launch_absmax3(const float* p0, int64_t n0, int abs0, const float* p1, int64
   if (nb == 0) return LBT_OK;
   if (nb > kMaxPartialBlocks) return LBT_ERR_UNSUPPORTED;
   MaxSeg s0{p0, n0, abs0, 0}, s1{p1, n1, abs1, (int)nb0}, s2{p2, n2, abs2, (int)(nb0 + nb1)};
-  LBT_LAUNCH(k_absmax3, dim3((unsigned)nb), dim3(kThreads), 0, s, s0, s1, s2, per, pmax);
+  LBT_LAUNCH(k_absmax3, dim3((unsigned)nb), dim3(kThreads), 0, s, s0, s1, s2, per, pmax, st);
   LBT_LAUNCH_CHECK();
   return LBT_OK;
 }
@@ -789,27 +869,66 @@ static void fill_tile_args(TileArgs& t, const float* x, int64_t A, int64_t B, in
   t.a_lmajor = io.a_lmajor;
 }
 
-int launch_quantize_relayout_grad(const float* g, int64_t A, int64_t B, int64_t L,
-                                  const RelayoutIo& io, uint64_t seed, int rounding,
-                                  hipStream_t s) {
-  ProfScope prof(KID_RELAYOUT_GRAD, (double)A * (double)B * (double)L, s);
-  TileArgs t{};
-  fill_tile_args(t, g, A, B, L, io);
-  t.seed = seed;
-  if (rounding == LBT_ROUND_STOCHASTIC) return tile_dispatch<3>(t, s);
-  return tile_dispatch<2>(t, s);
-}
-
-int launch_quantize_relayout_operand(const float* x, int64_t A, int64_t B, int64_t L,
-                                     const RelayoutIo& io, float c_given, int is_unsigned,
-                                     float* c_out, uint32_t* bad_out, hipStream_t s) {
-  ProfScope prof(KID_RELAYOUT_OPERAND, (double)A * (double)B * (double)L, s);
-  TileArgs t{};
-  fill_tile_args(t, x, A, B, L, io);
-  t.c_given = c_given;
-  t.c_out = c_out; t.bad_out = bad_out;
-  if (is_unsigned) return tile_dispatch<1>(t, s);
-  return tile_dispatch<0>(t, s);
+int launch_quantize_layer(const LayerTensors& q, hipStream_t s) {
+  double work = 0.0;
+  Segment seg[3] = {};
+  size_t lds = 0;
+  unsigned long long next = 0;
+  for (int i = 0; i < 3; ++i) {
+    const LayerTensors::One& o = q.tensor[i];
+    Segment& sg = seg[i];
+    sg.first = (unsigned)next;
+    if (!o.x) continue;
+    fill_tile_args(sg.t, o.x, o.A, o.B, o.L, o.io);
+    sg.t.seed = q.seed;
+    sg.t.c_given = o.c_given;
+    sg.t.c_out = o.c_out;
+    sg.t.bad_out = o.bad_out;
+    const size_t need = plan_segment(sg);
+    if (need > lds) lds = need;
+    const unsigned long long nb = (unsigned long long)sg.gx * sg.gy * (unsigned long long)sg.t.AG;
+    if (nb == 0 || next + nb > 0x7fffffffull) return LBT_ERR_UNSUPPORTED;
+    sg.n_blocks = (unsigned)nb;
+    next += nb;
+    work += (double)o.A * (double)o.B * (double)o.L;
+  }
+  if (next == 0) return LBT_OK;
+  const dim3 block(kThreads);
+  const bool sr = q.rounding == LBT_ROUND_STOCHASTIC;
+  // a large gradient tensor gets a launch (and a lean kernel) of its own
+  const double n_grad = (double)q.tensor[0].A * (double)q.tensor[0].B * (double)q.tensor[0].L;
+  if (seg[0].n_blocks && n_grad >= kOwnLaunchElements) {
+    ProfScope prof(KID_QUANTIZE_GRAD, n_grad, s);
+    Segment one = seg[0];
+    const dim3 grid(one.n_blocks);
+    const size_t need = plan_segment(one);
+#define LBT_GRAD_CASE(KIND_)                                                              \
+    if (one.kind == KIND_) {                                                                \
+      if (sr) LBT_LAUNCH((k_quantize_grad<3, KIND_>), grid, block, need, s, one);           \
+      else LBT_LAUNCH((k_quantize_grad<2, KIND_>), grid, block, need, s, one);              \
+    }
+    LBT_GRAD_CASE(kWindowed)
+    LBT_GRAD_CASE(kWholeRow)
+    LBT_GRAD_CASE(kGenericColumn)
+    LBT_GRAD_CASE(kGenericTile)
+#undef LBT_GRAD_CASE
+    LBT_LAUNCH_CHECK();
+    // the others move up: the multi-tensor kernel sees an absent gradient
+    work -= n_grad;
+    next -= one.n_blocks;
+    seg[1].first -= one.n_blocks;
+    seg[2].first -= one.n_blocks;
+    seg[0] = Segment{};
+    if (next == 0) return LBT_OK;
+  }
+  ProfScope prof(KID_QUANTIZE_LAYER, work, s);
+  const dim3 grid((unsigned)next);
+  if (sr && q.x_unsigned) LBT_LAUNCH((k_quantize_layer<3, 1>), grid, block, lds, s, seg[0], seg[1], seg[2]);
+  else if (sr) LBT_LAUNCH((k_quantize_layer<3, 0>), grid, block, lds, s, seg[0], seg[1], seg[2]);
+  else if (q.x_unsigned) LBT_LAUNCH((k_quantize_layer<2, 1>), grid, block, lds, s, seg[0], seg[1], seg[2]);
+  else LBT_LAUNCH((k_quantize_layer<2, 0>), grid, block, lds, s, seg[0], seg[1], seg[2]);
+  LBT_LAUNCH_CHECK();
+  return LBT_OK;
 }
 
 int launch_update_interval(lbt_grad_state* st, hipStream_t s) {
