@@ -172,6 +172,9 @@ CONV_CASES = [
     (8, 64, 14, 14, 160, 1, 1, 1, 0),      # bottleneck 1x1, several tiles
     (4, 130, 14, 14, 140, 3, 3, 1, 1),     # ragged channel counts across tile edges
     (20, 32, 12, 12, 48, 3, 3, 2, 1),      # batch not a multiple of 16
+    (2, 24, 9, 9, 136, 3, 3, 2, 1),        # 9 channel groups, padded to 16 in the dX walk
+    (3, 16, 5, 5, 80, 3, 3, 1, 1),         # 5 channel groups, padded to 8
+    (2, 16, 6, 6, 128, 3, 3, 1, 1),        # exactly 8 channel groups: one tap per K step
 ]
 
 
@@ -232,8 +235,27 @@ def test_backward_skips_and_degenerate():
     assert lbt.lbt_state_read(st).status == lbt.STATUS_NONFINITE
 
 
+def test_nonfinite_operand_is_reported():
+    # a non-finite activation or weight (maximum taken on the device) must show in the status,
+    # whichever of the layer's quantizers finishes last
+    N, Cc, H, W, K, R, S, stride, pad = 4, 16, 12, 12, 32, 3, 3, 1, 1
+    r = synth.rng(0, 19, 0, 0)
+    X, Wt = synth.relu_normal(r, (N, Cc, H, W)), synth.kaiming_normal(r, (K, Cc, R, S))
+    dY = synth.dense_grad(r, (N, K, H, W))
+    st = lbt.new_state(gamma0=1.0)
+    gu.backward_conv2d(X, Wt, dY, stride, pad, st)
+    assert lbt.lbt_state_read(st).status == lbt.STATUS_OK
+    for which in ("x", "w"):
+        Xb, Wb = X.copy(), Wt.copy()
+        (Xb if which == "x" else Wb).reshape(-1)[5] = np.inf
+        gu.backward_conv2d(Xb, Wb, dY, stride, pad, st)
+        assert lbt.lbt_state_read(st).status == lbt.STATUS_NONFINITE, which
+        gu.backward_conv2d(X, Wt, dY, stride, pad, st)      # and a clean call resets it
+        assert lbt.lbt_state_read(st).status == lbt.STATUS_OK
+
+
 def test_backward_is_deterministic():
-    # split-K uses integer atomics: any order gives the same bits
+    # split-K sums int32 partial tiles in a fixed order: run to run the same bits
     N, Cc, H, W, K, R, S, stride, pad = 16, 32, 16, 16, 32, 3, 3, 1, 1
     r = synth.rng(0, 18, 0, 0)
     X, Wt = synth.relu_normal(r, (N, Cc, H, W)), synth.kaiming_normal(r, (K, Cc, R, S))
