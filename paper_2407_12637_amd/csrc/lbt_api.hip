@@ -19,13 +19,13 @@ ConvWorkspace conv_workspace(const ConvGeom& g, bool is_linear) {
   w.off_scalars = o;
   o += kWsHeaderBytes;
   w.off_g_npqk = o;
-  o += pad256((size_t)g.N * g.P * g.Q * g.Kp / 2);
+  o += pad256((size_t)g.N * g.P * g.Q * g.Kp);
   w.off_g_kpqn = o;
-  o += pad256((size_t)g.K * g.P * g.Q * g.Np / 2);
+  o += pad256((size_t)g.K * g.P * g.Q * g.Np);
   w.off_x_chwn = o;
-  o += pad256((size_t)g.C * g.H * g.W * g.Np / 2);
+  o += pad256((size_t)g.C * g.H * g.W * g.Np);
   w.off_w_crsk = o;
-  o += pad256((size_t)g.C * g.R * g.S * g.Kp / 2);
+  o += pad256((size_t)g.C * g.R * g.S * g.Kp);
   w.off_partial = o;
   const SplitPlan plan = is_linear
       ? plan_split_k(g.C, g.K, g.Np / kGranule)

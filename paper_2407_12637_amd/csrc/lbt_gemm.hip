@@ -3,8 +3,8 @@
 // Both gradients of a convolution (and of a linear layer, which is the 1x1 case
 // on a 1x1 image) are computed by one implicit-GEMM kernel
 //     D[m][j] = sum_k A[m][k] * B[j][k]
-// whose operands are 4-bit codes packed two per byte along the contraction axis,
-// in granules ("chunks") of 16 codes = 8 bytes:
+// whose operands are 4-bit codes held one per int8 byte, in granules ("chunks") of 16
+// codes = 16 bytes along the contraction axis:
 //   dX: A = weights  [C][R*S][Kp/16][16] (dense rows, tap-major), B row j = input pixel
 //       (n,h,w), gathered from the gradient codes [N][Kp/16][P*Q][16] tap by tap;
 //   dW: A = gradient [K][Np/16][P*Q][16] (dense rows), B row j = (c,r,s), gathered
@@ -16,15 +16,20 @@
 // over t = sample_group * P*Q + output pixel.
 //
 // A workgroup (4 waves) owns a BM x BN tile of D (64 or 128 each; smaller tiles when the
-// problem would otherwise not fill the chip).  Per K step of 8 chunks (128 codes) it
-// reads the packed granules with buffer loads (out-of-range offsets return zero, which
-// is how padding, ragged edges and the K tail are masked), widens them to int8 ONCE and
-// stores them in LDS (double buffered, 16 bytes per granule); the waves then feed
-// v_mfma_i32_32x32x32_i8 straight from 16-byte LDS reads.  Global loads run two steps
-// ahead of the matrix cores.  Widening: a signed nibble is moved to the top of its byte
-// (value * 16, exact two's complement), an unsigned nibble is masked in place; the
-// accumulators therefore carry a factor 256 or 16 that the epilogue shifts out exactly.
-// int32 accumulation, exact.
+// problem would otherwise not fill the chip).  Per K step of 8 chunks (128 codes) the
+// operand tiles go from global memory straight into LDS (buffer loads with the LDS
+// destination, 16 bytes per lane, no registers and no ALU work in between; an offset
+// outside the tensor writes zeros, which is how padding, ragged edges and the K tail
+// are masked).  A wave's load lands as 1 KiB of consecutive LDS bytes in lane order, so
+// the lane -> (row, chunk) assignment fixes the tile layout:
+//   dense rows (A; B of dW): [row][8 chunks], eight lanes read 128 consecutive bytes of
+//       one row; chunk c of row r sits in slot c ^ (r & 7) so that the 32 rows a
+//       fragment read touches fall into different banks;
+//   gathered pixels (B of dX): [chunk][row], 64 lanes read the granules of 64
+//       consecutive pixels (consecutive in memory) and a fragment read is contiguous.
+// Two LDS stages: while the matrix cores work on step s (fragments already in
+// registers), the loads of step s + 1 are in flight.  v_mfma_i32_32x32x32_i8, int32
+// accumulation, exact.
 //
 // dW has a small output and a very long contraction: the contraction is split
 // over workgroups, each writes its partial tile with plain stores, and a second
@@ -37,12 +42,12 @@ namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
-typedef unsigned v2u __attribute__((ext_vector_type(2)));
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
 
 constexpr int kThreads = 256;
-constexpr int BKC = 8;                  // chunks (of 16 codes) per K step
-constexpr int PITCH = BKC * 16 + 16;    // LDS bytes per tile row: 128 int8 codes + 16 pad
-constexpr int kXcds = 8;                // workgroups are dealt round-robin to 8 dies, each with its own L2
+constexpr int BKC = 8;             // chunks (of 16 codes) per K step
+constexpr int ROWB = BKC * 16;     // bytes of one tile row per K step
+constexpr int kXcds = 8;           // workgroups are dealt round-robin to 8 dies, each with its own L2
 
 struct GemmArgs {
   const uint8_t* A;
@@ -60,7 +65,6 @@ struct GemmArgs {
   int inner;          // MODE 1: chunk t = group * inner + pos, inner = P*Q (1 for linear)
   int groups;         // granule groups per row of the gathered tensor (Kp/16 or Np/16)
   int gp, gp_log2;    // MODE 0: padded group count; gp_log2 >= 0 when gp is 1, 2 or 4, else -1
-  int shift;          // log2 of the factor carried by the accumulators
   const lbt_grad_state* st;
   const OperandScalars* sc;
   float* out;
@@ -68,26 +72,20 @@ struct GemmArgs {
   int32_t* partial;   // [splits][M][NJ] for epi 1
 };
 
-// Packed granule (16 nibbles) -> 16 int8 values.  Byte i of a packed word holds codes
-// 2i (low nibble) and 2i+1 (high nibble); the result keeps the evens of each word together
-// and the odds together, the same permutation for both operands of a product.
-//   signed:   value * 16 (nibble in the top half of the byte)
-//   unsigned: value
-template <bool UNS>
-__device__ __forceinline__ v4i widen(v2u p) {
-  v4i r;
-  if (UNS) {
-    r[0] = (int)(p[0] & 0x0F0F0F0Fu);
-    r[1] = (int)((p[0] >> 4) & 0x0F0F0F0Fu);
-    r[2] = (int)(p[1] & 0x0F0F0F0Fu);
-    r[3] = (int)((p[1] >> 4) & 0x0F0F0F0Fu);
-  } else {
-    r[0] = (int)((p[0] << 4) & 0xF0F0F0F0u);
-    r[1] = (int)(p[0] & 0xF0F0F0F0u);
-    r[2] = (int)((p[1] << 4) & 0xF0F0F0F0u);
-    r[3] = (int)(p[1] & 0xF0F0F0F0u);
-  }
-  return r;
+// 16 bytes per lane from a buffer straight into LDS: lane l of the wave writes LDS byte
+// dst + 16 * l (dst uniform across the wave); an offset outside the buffer writes zeros.
+// Issued as an instruction the compiler does not track, so that the kernel can wait for
+// the loads of one K step while those of later steps stay in flight (wait_loads below);
+// every read of the tile is ordered after such a wait and a workgroup barrier.
+__device__ __forceinline__ void load16_to_lds(__amdgpu_buffer_rsrc_t rsrc, unsigned dst,
+                                              unsigned offset) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+               :: "s"(dst), "v"(offset), "s"(rsrc) : "memory", "m0");
+}
+// Wait until at most N of this wave's buffer loads are outstanding.
+template <int N>
+__device__ __forceinline__ void wait_loads() {
+  asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
 }
 
 __device__ __forceinline__ float output_scale(const GemmArgs& g) {
@@ -101,19 +99,20 @@ __device__ __forceinline__ float output_scale(const GemmArgs& g) {
 // MODE 0: B rows are input pixels (dX of a convolution)
 // MODE 1: B rows are (c,r,s) triples read with the tap's shift (dW; also every
 //         linear-layer product, where the image is 1x1)
-template <int BM, int BN, bool A_UNSIGNED, bool B_UNSIGNED, int MODE>
+template <int BM, int BN, int MODE, int STAGES>
 __global__ __launch_bounds__(kThreads) void k_implicit_gemm(const GemmArgs g) {
   // wave grid WGM x WGN: 128x128 -> 2x2, 64x128 -> 1x4, 128x64 -> 4x1, 64x64 -> 2x2
   constexpr int WGM = (BM == BN) ? 2 : (BM > BN ? 4 : 1);
   constexpr int WGN = 4 / WGM;
   constexpr int WM = BM / WGM, WN = BN / WGN;  // wave tile
   constexpr int TM = WM / 32, TN = WN / 32;    // 32x32 MFMA blocks per wave
-  constexpr int NA = BM * BKC / kThreads, NB = BN * BKC / kThreads;  // granules per thread per step
-  // dynamic LDS: two stages of the A tile, two of the B tile, then (MODE 0) the tap table
+  constexpr int NA = BM * BKC / kThreads, NB = BN * BKC / kThreads;  // loads per thread per step
+  constexpr int STAGE = (BM + BN) * ROWB;      // bytes of one LDS stage (A tile, then B tile)
+  constexpr int LPS = NA + NB;                 // buffer loads of a wave per K step
+  // dynamic LDS: STAGES stages, then (MODE 0) the tap table
   extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
-  uint8_t* const sA0 = lds;
-  uint8_t* const sB0 = lds + 2 * BM * PITCH;
-  int* const s_tap = reinterpret_cast<int*>(lds + 2 * (BM + BN) * PITCH);  // [BN][R*S]
+  int* const s_tap = reinterpret_cast<int*>(lds + STAGES * STAGE);  // [BN][R*S]
+  const unsigned lds_base = (unsigned)(uintptr_t)(lds_ptr_t)lds;    // LDS byte address of lds[0]
 
   // workgroup id -> tile, so that the workgroups sharing a B tile run on one die
   const int per_xcd = gridDim.x / kXcds;
@@ -123,7 +122,8 @@ __global__ __launch_bounds__(kThreads) void k_implicit_gemm(const GemmArgs g) {
   const int n_tile = (lid / g.tiles_m) % g.tiles_n;
   const int split = lid / (g.tiles_m * g.tiles_n);
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = (wave / WGN) * WM, wn = (wave % WGN) * WN;
   const int m0 = m_tile * BM, j0 = n_tile * BN;
   const int s_begin = split * g.steps_per_split;
@@ -137,11 +137,14 @@ __global__ __launch_bounds__(kThreads) void k_implicit_gemm(const GemmArgs g) {
       __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(g.B), 0, g.b_bytes, 0x00020000);
   const unsigned oob_a = g.a_bytes, oob_b = g.b_bytes;
 
-  // ---- A staging: chunk-fastest; a thread owns chunk column `col` of NA rows ------------
-  const int col = tid & (BKC - 1);
+  // ---- dense-row staging ([row][slot] tiles): load i of a wave covers tile rows
+  // (4 i + wave) * 8 .. + 8; lane -> row (lane / 8) of them and slot (lane % 8), which
+  // holds chunk slot ^ (row & 7).  The chunk is the same for all loads of a thread.
+  const int col = (lane & 7) ^ (lane >> 3);
+  const int sub = lane >> 3;
   unsigned a_row[NA];
 #pragma unroll
-  for (int i = 0; i < NA; ++i) a_row[i] = (unsigned)(m0 + (tid >> 3) + 32 * i) * g.lda;
+  for (int i = 0; i < NA; ++i) a_row[i] = (unsigned)(m0 + (4 * i + wave) * 8 + sub) * g.lda;
   // MODE 0 walks (tap, group); all threads of the workgroup share (tap_base, kg_base)
   const bool small = g.gp_log2 >= 0;
   int tap_base = 0, kg_base = 0;
@@ -150,24 +153,25 @@ __global__ __launch_bounds__(kThreads) void k_implicit_gemm(const GemmArgs g) {
   int t_cur = s_begin * BKC + col;
 
   // ---- B staging ---------------------------------------------------------------------------
-  // MODE 1: chunk-fastest like A; row i is a (c,r,s) triple; the thread's running output
-  // position (group, p, q) belongs to its chunk column.
+  // MODE 1: dense-row scheme like A; row i is a (c,r,s) triple; the thread's running output
+  // position (group, p, q) belongs to its chunk.
   unsigned b_row[NB];
   int b_dh[NB], b_dw[NB];
   int b_grp = 0, b_p = 0, b_q = 0;
-  // MODE 0: row-fastest; the thread owns ONE pixel row and NB chunk columns.
-  const int x_row = tid % BN;
-  unsigned x_const[NB];
-  int x_dt[NB];
+  // MODE 0: [chunk][row] tile; load i of a wave covers chunk x_chunk(i) and 64 consecutive
+  // pixel rows, lane -> pixel row x_row (the same for all loads of a thread).
+  constexpr int HALVES = BN / 64;
+  const int x_row = (wave % HALVES) * 64 + lane;
+  unsigned x_const = 0;
   if (MODE == 1) {
 #pragma unroll
     for (int i = 0; i < NB; ++i) {
-      const int j = j0 + (tid >> 3) + 32 * i;
+      const int j = j0 + (4 * i + wave) * 8 + sub;
       const int c_ = j / RS, rs = j - c_ * RS;
       const int r_ = rs / g.S, s_ = rs - r_ * g.S;
       b_dh[i] = r_ - g.pad;
       b_dw[i] = s_ - g.pad;
-      b_row[i] = j < g.NJ ? (unsigned)(c_ * g.groups * HW + b_dh[i] * g.W + b_dw[i]) * 8u : oob_b;
+      b_row[i] = j < g.NJ ? (unsigned)(c_ * g.groups * HW + b_dh[i] * g.W + b_dw[i]) * 16u : oob_b;
     }
     b_grp = t_cur / g.inner;
     const int pos = t_cur - b_grp * g.inner;
@@ -183,21 +187,22 @@ __global__ __launch_bounds__(kThreads) void k_implicit_gemm(const GemmArgs g) {
       tap_base = t0 / g.gp;
       kg_base = t0 - tap_base * g.gp;
     }
-    const int j = j0 + x_row;
-    const bool x_ok = j < g.NJ;
-    const int n_ = j / HW, hw = j - n_ * HW;
-    const int h_ = hw / g.W, w_ = hw - h_ * g.W;
-    // tap table of this row: byte offset of output pixel (p,q) inside one channel group, or
-    // -1 when the tap falls outside the output / between strides.  The 256 / BN threads
-    // that share the row split the taps.
+    // tap table: byte offset of output pixel (p,q) inside one channel group, or -1 when
+    // the tap falls outside the output / between strides.  Row tid % BN; the 256 / BN
+    // threads that share a row split its taps.
     {
       constexpr int SUB = kThreads / BN;
+      const int t_row = tid % BN;
+      const int j = j0 + t_row;
+      const bool ok = j < g.NJ;
+      const int n_ = j / HW, hw = j - n_ * HW;
+      const int h_ = hw / g.W, w_ = hw - h_ * g.W;
       int fr = 0, fs = tid / BN;
       while (fs >= g.S) { fs -= g.S; ++fr; }
       for (int tap = tid / BN; tap < RS; tap += SUB) {
         const int hp = h_ + g.pad - fr, wq = w_ + g.pad - fs;
         int off = -1;
-        if (x_ok && hp >= 0 && wq >= 0) {
+        if (ok && hp >= 0 && wq >= 0) {
           int p, q;
           bool on_grid;
           if (g.stride == 1) {
@@ -208,48 +213,57 @@ __global__ __launch_bounds__(kThreads) void k_implicit_gemm(const GemmArgs g) {
             p = hp / g.stride; q = wq / g.stride;
             on_grid = p * g.stride == hp && q * g.stride == wq;
           }
-          if (on_grid && p < g.P && q < g.Q) off = (p * g.Q + q) * 8;
+          if (on_grid && p < g.P && q < g.Q) off = (p * g.Q + q) * 16;
         }
-        s_tap[x_row * RS + tap] = off;
+        s_tap[t_row * RS + tap] = off;
         fs += SUB;
         while (fs >= g.S) { fs -= g.S; ++fr; }
       }
     }
-#pragma unroll
-    for (int i = 0; i < NB; ++i) {
-      const int c = tid / BN + i * (kThreads / BN);
-      const int dt = small ? c >> g.gp_log2 : 0;
-      const int kgo = small ? c & (g.gp - 1) : c;
-      x_dt[i] = dt;
-      x_const[i] = (unsigned)((n_ * g.groups + kgo) * PQ) * 8u;
+    {
+      const int j = j0 + x_row;
+      const int n_ = j / HW;
+      x_const = (unsigned)(n_ * g.groups * PQ) * 16u;   // rows past the end have no valid tap
     }
     __syncthreads();
   }
 
-  // Issue the global loads of the next K step into (xa, xb) and advance the walk.  Steps
-  // past the end of this workgroup's K range load zero A columns, so the pipeline below
-  // can run them unconditionally.
+  // MODE 0, group count >= 8: every K step lies inside one tap; x_cur holds the byte offset
+  // of this lane's pixel at the current tap (x_const + table entry), or an offset beyond
+  // every buffer when the tap does not reach the pixel.
+  constexpr unsigned kNoTap = 0x80000000u;
+  unsigned x_cur = kNoTap;
+  auto load_tap = [&](int tap) {
+    const int off = s_tap[x_row * RS + min(tap, RS - 1)];
+    x_cur = off >= 0 ? x_const + (unsigned)off : kNoTap;
+  };
+  if (MODE == 0 && !small) load_tap(tap_base);
+  const unsigned pq16 = (unsigned)PQ * 16u;
+
+  // Issue the loads of the next K step into LDS stage `st` and advance the walk.  A step
+  // past the end of this workgroup's K range loads zero A chunks (its tile is never read).
   int ld_step = 0;
-  auto load_step = [&](v2u (&xa)[NA], v2u (&xb)[NB]) {
+  auto issue = [&](int st) {
+    const unsigned sa = lds_base + st * STAGE;
+    const unsigned sb = sa + BM * ROWB;
     const bool live = ld_step < n_steps;
     ++ld_step;
     if (MODE == 1) {
-      const unsigned a_col = (live && t_cur < g.chunks) ? (unsigned)t_cur * 8u : oob_a;
+      const unsigned a_col = (live && t_cur < g.chunks) ? (unsigned)t_cur * 16u : oob_a;
 #pragma unroll
       for (int i = 0; i < NA; ++i)
-        xa[i] = __builtin_amdgcn_raw_buffer_load_b64(rsrc_a, min(a_row[i] + a_col, oob_a), 0, 0);
+        load16_to_lds(rsrc_a, sa + (4 * i + wave) * 1024, min(a_row[i] + a_col, oob_a));
       const int ph = b_p * g.stride, qw = b_q * g.stride;
-      const unsigned pos = (unsigned)(b_grp * HW + ph * g.W + qw) * 8u;
+      const unsigned pos = (unsigned)(b_grp * HW + ph * g.W + qw) * 16u;
       if (g.pad == 0) {
 #pragma unroll
-        for (int i = 0; i < NB; ++i)
-          xb[i] = __builtin_amdgcn_raw_buffer_load_b64(rsrc_b, b_row[i] + pos, 0, 0);
+        for (int i = 0; i < NB; ++i) load16_to_lds(rsrc_b, sb + (4 * i + wave) * 1024, b_row[i] + pos);
       } else {
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
           const bool in = (unsigned)(ph + b_dh[i]) < (unsigned)g.H &&
                           (unsigned)(qw + b_dw[i]) < (unsigned)g.W;
-          xb[i] = __builtin_amdgcn_raw_buffer_load_b64(rsrc_b, in ? b_row[i] + pos : oob_b, 0, 0);
+          load16_to_lds(rsrc_b, sb + (4 * i + wave) * 1024, in ? b_row[i] + pos : oob_b);
         }
       }
       t_cur += BKC;
@@ -262,45 +276,36 @@ __global__ __launch_bounds__(kThreads) void k_implicit_gemm(const GemmArgs g) {
       }
     } else {
       const int tap_a = tap_base + a_dt, kg_a = kg_base + a_kgo;
-      const unsigned a_col =
-          (live && tap_a < RS && kg_a < g.groups) ? (unsigned)(tap_a * g.groups + kg_a) * 8u : oob_a;
+      const unsigned a_col = (live && tap_a < RS && kg_a < g.groups)
+                                 ? (unsigned)(tap_a * g.groups + kg_a) * 16u : oob_a;
 #pragma unroll
       for (int i = 0; i < NA; ++i)
-        xa[i] = __builtin_amdgcn_raw_buffer_load_b64(rsrc_a, min(a_row[i] + a_col, oob_a), 0, 0);
-      const unsigned kg_off = (unsigned)(kg_base * PQ) * 8u;
-#pragma unroll
-      for (int i = 0; i < NB; ++i) {
-        // columns past the last tap or group meet zero A columns: any in-table tap will do
-        const int tap = min(tap_base + x_dt[i], RS - 1);
-        const int off = s_tap[x_row * RS + tap];
-        xb[i] = __builtin_amdgcn_raw_buffer_load_b64(
-            rsrc_b, off >= 0 ? x_const[i] + kg_off + (unsigned)off : oob_b, 0, 0);
-      }
+        load16_to_lds(rsrc_a, sa + (4 * i + wave) * 1024, min(a_row[i] + a_col, oob_a));
       if (small) {
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+          // load i of this wave: chunk (4 i + wave) / HALVES of the step, all lanes alike
+          const int c = (4 * i + wave) / HALVES;
+          const int kg = c & (g.gp - 1);
+          // chunks past the last tap or group meet zero A chunks: any in-table tap will do
+          const int tap = min(tap_base + (c >> g.gp_log2), RS - 1);
+          const int off = s_tap[x_row * RS + tap];
+          load16_to_lds(rsrc_b, sb + (4 * i + wave) * 1024,
+                        off >= 0 ? x_const + (unsigned)kg * pq16 + (unsigned)off : oob_b);
+        }
         tap_base += BKC >> g.gp_log2;
       } else {
+        const unsigned k0 = (unsigned)(kg_base + wave / HALVES) * pq16;   // uniform
+#pragma unroll
+        for (int i = 0; i < NB; ++i)
+          load16_to_lds(rsrc_b, sb + (4 * i + wave) * 1024, x_cur + k0 + (unsigned)(4 * i / HALVES) * pq16);
         kg_base += BKC;
-        if (kg_base >= g.gp) { kg_base = 0; ++tap_base; }
+        if (kg_base >= g.gp) {
+          kg_base = 0;
+          ++tap_base;
+          load_tap(tap_base);
+        }
       }
-    }
-  };
-  // Widen a loaded step and put it into LDS stage `buf`.
-  auto store_step = [&](const v2u (&xa)[NA], const v2u (&xb)[NB], int buf) {
-#pragma unroll
-    for (int i = 0; i < NA; ++i)
-      *reinterpret_cast<v4i*>(&sA0[buf * BM * PITCH + ((tid >> 3) + 32 * i) * PITCH + col * 16]) =
-          widen<A_UNSIGNED>(xa[i]);
-    if (MODE == 1) {
-#pragma unroll
-      for (int i = 0; i < NB; ++i)
-        *reinterpret_cast<v4i*>(&sB0[buf * BN * PITCH + ((tid >> 3) + 32 * i) * PITCH + col * 16]) =
-            widen<B_UNSIGNED>(xb[i]);
-    } else {
-#pragma unroll
-      for (int i = 0; i < NB; ++i)
-        *reinterpret_cast<v4i*>(
-            &sB0[buf * BN * PITCH + x_row * PITCH + (tid / BN + i * (kThreads / BN)) * 16]) =
-            widen<B_UNSIGNED>(xb[i]);
     }
   };
 
@@ -312,52 +317,62 @@ __global__ __launch_bounds__(kThreads) void k_implicit_gemm(const GemmArgs g) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
-  // One K step on the matrix cores: four 32x32x32 products per accumulator block; a lane
-  // feeds row (lane % 32) and chunk 2*kk + lane/32.
-  auto compute = [&](int buf) {
+  // Fragment addresses inside a stage: one 32x32x32 product takes, per lane, row (lane % 32)
+  // and chunk 2*kk + lane/32 of each operand.
+  unsigned fa_off[BKC / 2][TM], fb_off[BKC / 2][TN];
+#pragma unroll
+  for (int kk = 0; kk < BKC / 2; ++kk) {
+    const int c = 2 * kk + (lane >> 5);
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      const int r = wm + i * 32 + (lane & 31);
+      fa_off[kk][i] = (unsigned)(r * ROWB + ((c ^ (r & 7)) * 16));
+    }
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int r = wn + j * 32 + (lane & 31);
+      fb_off[kk][j] = (unsigned)(BM * ROWB) +
+                      (MODE == 1 ? (unsigned)(r * ROWB + ((c ^ (r & 7)) * 16)) : (unsigned)((c * BN + r) * 16));
+    }
+  }
+
+  // Pipeline with STAGES LDS stages.  Every step issues the loads of step s + STAGES - 1
+  // (zero tiles past the end), so exactly STAGES - 2 later steps are in flight whenever a
+  // step is waited for.  After the barrier every wave pulls the step's fragments into
+  // registers, then the new loads go into the stage that step s - 1 used (all waves have
+  // read it: they passed this barrier), then the matrix cores run on the fragments.
+  constexpr int AHEAD = STAGES - 1;
+#pragma unroll
+  for (int d = 0; d < AHEAD; ++d) issue(d);
+  int st_read = 0, st_load = AHEAD % STAGES;
+  for (int s = 0; s < n_steps; ++s) {
+    wait_loads<(AHEAD - 1) * LPS>();
+    __syncthreads();
+    const uint8_t* const stage = lds + st_read * STAGE;
+    v4i fa[BKC / 2][TM], fb[BKC / 2][TN];
 #pragma unroll
     for (int kk = 0; kk < BKC / 2; ++kk) {
-      const int coff = (2 * kk + (lane >> 5)) * 16;
-      v4i fa[TM], fb[TN];
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
-        fa[i] = *reinterpret_cast<const v4i*>(
-            &sA0[buf * BM * PITCH + (wm + i * 32 + (lane & 31)) * PITCH + coff]);
+      for (int i = 0; i < TM; ++i) fa[kk][i] = *reinterpret_cast<const v4i*>(stage + fa_off[kk][i]);
 #pragma unroll
-      for (int j = 0; j < TN; ++j)
-        fb[j] = *reinterpret_cast<const v4i*>(
-            &sB0[buf * BN * PITCH + (wn + j * 32 + (lane & 31)) * PITCH + coff]);
+      for (int j = 0; j < TN; ++j) fb[kk][j] = *reinterpret_cast<const v4i*>(stage + fb_off[kk][j]);
+    }
+    issue(st_load);
+    st_read = st_read + 1 == STAGES ? 0 : st_read + 1;
+    st_load = st_load + 1 == STAGES ? 0 : st_load + 1;
+#pragma unroll
+    for (int kk = 0; kk < BKC / 2; ++kk)
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], acc[i][j], 0, 0, 0);
-    }
-  };
-
-  // Software pipeline: while step s runs out of LDS stage s % 2, step s + 1 sits in one
-  // register set (its loads issued a whole step ago) and step s + 2 is being loaded into
-  // the other.  No branch inside the loop touches memory, so the loads of one step are
-  // only waited for a full step after they were issued.
-  v2u ra0[NA], rb0[NB], ra1[NA], rb1[NB];
-  load_step(ra0, rb0);
-  load_step(ra1, rb1);
-  store_step(ra0, rb0, 0);
-  __syncthreads();
-  for (int s = 0; s < n_steps; s += 2) {
-    load_step(ra0, rb0);
-    compute(0);
-    store_step(ra1, rb1, 1);
-    __syncthreads();
-    load_step(ra1, rb1);
-    compute(1);
-    store_step(ra0, rb0, 0);
-    __syncthreads();
+          acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[kk][i], fb[kk][j], acc[i][j], 0, 0, 0);
   }
+  // the zero tiles requested past the end must have landed before the LDS is given back
+  wait_loads<0>();
 
   // ---- epilogue.  32x32 accumulator block: lane holds column (lane % 32) and rows
   // 8*(r/4) + 4*(lane/32) + r%4 for r = 0..15, so 32 lanes store 32 consecutive columns.
-  const int shift = g.shift;
   const float scale = (g.epi == 1) ? 0.0f : output_scale(g);
 #pragma unroll
   for (int j = 0; j < TN; ++j) {
@@ -379,7 +394,7 @@ __global__ __launch_bounds__(kThreads) void k_implicit_gemm(const GemmArgs g) {
       for (int r = 0; r < 16; ++r) {
         const int row = m0 + wm + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
         if (row >= g.M) continue;
-        const int v = acc[i][j][r] >> shift;
+        const int v = acc[i][j][r];
         const long long o = base + (long long)row * row_stride;
         if (g.epi == 1) {
           g.partial[(long long)split * g.M * g.NJ + o] = v;
@@ -415,11 +430,13 @@ void fill_geom(GemmArgs& g, const ConvGeom& c) {
   g.P = c.P; g.Q = c.Q; g.stride = c.stride; g.pad = c.pad;
 }
 
-constexpr size_t kMaxDynLds = 100 * 1024;
+constexpr size_t kMaxDynLds = 128 * 1024;
 
-template <int BM, int BN, bool A_UNS, bool B_UNS, int MODE>
-int launch_one(const GemmArgs& g, unsigned grid, size_t dyn, hipStream_t s) {
-  const auto kernel = k_implicit_gemm<BM, BN, A_UNS, B_UNS, MODE>;
+template <int BM, int BN, int MODE, int STAGES>
+int launch_one(const GemmArgs& g, unsigned grid, size_t tap_bytes, hipStream_t s) {
+  void (*kernel)(const GemmArgs) = &k_implicit_gemm<BM, BN, MODE, STAGES>;
+  const size_t dyn = (size_t)STAGES * (BM + BN) * ROWB + tap_bytes;
+  if (dyn > kMaxDynLds) return LBT_ERR_UNSUPPORTED;
   // more than 64 KiB of dynamic LDS has to be allowed once per kernel
   static bool raised = false;
   if (!raised) {
@@ -433,20 +450,10 @@ int launch_one(const GemmArgs& g, unsigned grid, size_t dyn, hipStream_t s) {
   return LBT_OK;
 }
 
-template <int BM, int BN, int MODE>
-int launch_variant(const GemmArgs& g, bool a_uns, bool b_uns, unsigned grid, size_t dyn,
-                   hipStream_t s) {
-  if (a_uns) return launch_one<BM, BN, true, false, MODE>(g, grid, dyn, s);
-  if (b_uns) return launch_one<BM, BN, false, true, MODE>(g, grid, dyn, s);
-  return launch_one<BM, BN, false, false, MODE>(g, grid, dyn, s);
-}
-
-int run_gemm(GemmArgs& g, int mode, bool a_uns, bool b_uns, int bm, int bn, int splits, int kid,
-             hipStream_t s) {
+int run_gemm(GemmArgs& g, int mode, int bm, int bn, int splits, int kid, hipStream_t s) {
   // algorithmic work: the convolution's multiply-adds, padding taps included
   const double work = 2.0 * g.N * g.P * g.Q * (double)g.K * g.C * g.R * g.S;
   ProfScope prof(kid, work, s);
-  if (a_uns && b_uns) return LBT_ERR_UNSUPPORTED;
   // 32-bit buffer offsets: both code tensors below 2 GiB, with room for the rows of a
   // ragged last tile
   if ((unsigned long long)g.a_bytes >= (1ull << 31) || (unsigned long long)g.b_bytes >= (1ull << 31) ||
@@ -458,23 +465,36 @@ int run_gemm(GemmArgs& g, int mode, bool a_uns, bool b_uns, int bm, int bn, int 
   if (total > (1ll << 30)) return LBT_ERR_UNSUPPORTED;
   g.total_blocks = (int)total;
   const unsigned grid = (unsigned)((total + kXcds - 1) / kXcds * kXcds);
-  size_t dyn = (size_t)2 * (bm + bn) * PITCH;
+  size_t tap_bytes = 0;
   if (mode == 0) {
     if ((size_t)128 * g.R * g.S * sizeof(int) > 25 * 1024) return LBT_ERR_UNSUPPORTED;  // up to 7x7
-    dyn += (size_t)bn * g.R * g.S * sizeof(int);
-    a_uns = b_uns = false;
+    tap_bytes = (size_t)bn * g.R * g.S * sizeof(int);
   }
-  if (dyn > kMaxDynLds) return LBT_ERR_UNSUPPORTED;
+  // LDS stages (= K steps of loads in flight + 1).  Measured on the ResNet-50 shapes:
+  // workgroups sharing a compute unit hide each other's latency better than a deeper
+  // pipeline does, so the deep variants (3 stages, 4 for 64x64) are used only when the
+  // whole grid still fits the chip in one go with their larger LDS footprint.
+  const int deep_stages = (bm == 64 && bn == 64) ? 4 : 3;
+  const size_t deep_lds = (size_t)deep_stages * (bm + bn) * ROWB + tap_bytes;
+  const long long deep_capacity = 256ll * (long long)((160 * 1024) / deep_lds);
+  const bool deep = total <= deep_capacity;
   int rc = LBT_ERR_UNSUPPORTED;
-#define LBT_GEMM_CASE(BM_, BN_)                                                             \
+#define LBT_GEMM_CASE(BM_, BN_, ST_)                                                        \
   if (bm == BM_ && bn == BN_) {                                                             \
-    rc = (mode == 0) ? launch_variant<BM_, BN_, 0>(g, a_uns, b_uns, grid, dyn, s)           \
-                     : launch_variant<BM_, BN_, 1>(g, a_uns, b_uns, grid, dyn, s);          \
+    rc = (mode == 0) ? launch_one<BM_, BN_, 0, ST_>(g, grid, tap_bytes, s)                  \
+                     : launch_one<BM_, BN_, 1, ST_>(g, grid, tap_bytes, s);                 \
   }
-  LBT_GEMM_CASE(128, 128)
-  LBT_GEMM_CASE(64, 128)
-  LBT_GEMM_CASE(128, 64)
-  LBT_GEMM_CASE(64, 64)
+  if (deep) {
+    LBT_GEMM_CASE(128, 128, 3)
+    LBT_GEMM_CASE(64, 128, 3)
+    LBT_GEMM_CASE(128, 64, 3)
+    LBT_GEMM_CASE(64, 64, 4)
+  } else {
+    LBT_GEMM_CASE(128, 128, 2)
+    LBT_GEMM_CASE(64, 128, 2)
+    LBT_GEMM_CASE(128, 64, 2)
+    LBT_GEMM_CASE(64, 64, 2)
+  }
 #undef LBT_GEMM_CASE
   if (rc) return rc;
   LBT_LAUNCH_CHECK();
@@ -497,22 +517,19 @@ void pick_tile(int M, int NJ, int splits, int* bm, int* bn) {
   }
 }
 
-// Direct (no split) product with signed operands: |sum| <= chunks*16 * 112 * 112 < 2^31.
+// Direct (no split) product with signed operands: |sum| <= chunks * 16 * 7 * 7 < 2^31.
 int run_direct(GemmArgs& g, int mode, hipStream_t s) {
   g.steps = (g.chunks + BKC - 1) / BKC;
   g.steps_per_split = g.steps;
-  g.shift = 8;
   g.scale_kind = 0;
-  if ((long long)g.chunks * 16 * 12544 >= (1ll << 31)) return LBT_ERR_OVERFLOW;
+  if ((long long)g.chunks * 16 * 49 >= (1ll << 31)) return LBT_ERR_OVERFLOW;
   int bm, bn;
   pick_tile(g.M, g.NJ, 1, &bm, &bn);
-  return run_gemm(g, mode, false, false, bm, bn, 1, KID_GEMM_DX, s);
+  return run_gemm(g, mode, bm, bn, 1, KID_GEMM_DX, s);
 }
 
-int run_splitk(GemmArgs& g, bool a_uns, bool b_uns, long long true_k, int32_t* acc, int32_t* partial,
+int run_splitk(GemmArgs& g, bool x_unsigned, long long true_k, int32_t* acc, int32_t* partial,
                hipStream_t s) {
-  const bool x_unsigned = a_uns || b_uns;
-  g.shift = x_unsigned ? 4 : 8;
   g.scale_kind = x_unsigned ? 2 : 1;
   // the exact sum must fit int32
   if (true_k * (x_unsigned ? 105 : 49) >= (1ll << 31)) return LBT_ERR_OVERFLOW;
@@ -523,12 +540,12 @@ int run_splitk(GemmArgs& g, bool a_uns, bool b_uns, long long true_k, int32_t* a
   if (plan.splits == 1) {
     g.epi = 2;
     g.acc = acc;
-    return run_gemm(g, 1, a_uns, b_uns, plan.bm, 128, 1, KID_GEMM_DW, s);
+    return run_gemm(g, 1, plan.bm, 128, 1, KID_GEMM_DW, s);
   }
   g.epi = 1;
   g.acc = nullptr;
   g.partial = partial;
-  if ((rc = run_gemm(g, 1, a_uns, b_uns, plan.bm, 128, plan.splits, KID_GEMM_DW, s))) return rc;
+  if ((rc = run_gemm(g, 1, plan.bm, 128, plan.splits, KID_GEMM_DW, s))) return rc;
   const long long n_out = (long long)g.M * g.NJ;
   ProfScope prof(KID_FINALIZE, (double)n_out, s);
   g.acc = acc;
@@ -553,7 +570,6 @@ SplitPlan plan_split_k(int M, int NJ, int chunks) {
   const long long out_bytes = (long long)M * NJ * 4;
   while (splits > 1 && splits * out_bytes > (48ll << 20)) --splits;
   int per = (int)((iters + splits - 1) / splits) * BKC;
-  if (per > 8192) per = 8192;               // 8192 chunks * 16 codes * 112 * 112 < 2^31
   p.chunks_per_split = per;
   p.splits = (chunks + per - 1) / per;
   p.partial_bytes = p.splits > 1 ? (size_t)p.splits * (size_t)out_bytes : 0;
@@ -578,14 +594,14 @@ int launch_conv_dx(const ConvGeom& c, const uint8_t* w_codes, const uint8_t* g_c
     g.gp_log2 = -1;
   }
   const long long padded = (long long)g.gp * g.inner;
-  const long long a_bytes = (long long)c.C * g.groups * g.inner * 8;
-  const long long b_bytes = (long long)c.N * g.groups * c.P * c.Q * 8;
+  const long long a_bytes = (long long)c.C * g.groups * g.inner * 16;
+  const long long b_bytes = (long long)c.N * g.groups * c.P * c.Q * 16;
   const long long nj = (long long)c.N * c.H * c.W;
   if (nj > 0x7fffffffll || padded > 0x7fffffffll / 16 || a_bytes >= (1ll << 31) ||
       b_bytes >= (1ll << 31))
     return LBT_ERR_UNSUPPORTED;
   g.chunks = (int)padded;
-  g.lda = (unsigned)(g.groups * g.inner * 8);
+  g.lda = (unsigned)(g.groups * g.inner * 16);
   g.a_bytes = (unsigned)a_bytes;
   g.b_bytes = (unsigned)b_bytes;
   g.M = c.C;
@@ -606,19 +622,19 @@ int launch_conv_dw(const ConvGeom& c, const uint8_t* g_codes, const uint8_t* x_c
   g.groups = c.Np / kGranule;
   g.inner = c.P * c.Q;
   const long long chunks = (long long)g.inner * g.groups;
-  const long long a_bytes = chunks * 8 * c.K;
-  const long long b_bytes = (long long)c.C * g.groups * c.H * c.W * 8;
+  const long long a_bytes = chunks * 16 * c.K;
+  const long long b_bytes = (long long)c.C * g.groups * c.H * c.W * 16;
   if (chunks > 0x7fffffffll / 16 || a_bytes >= (1ll << 31) || b_bytes >= (1ll << 31))
     return LBT_ERR_UNSUPPORTED;
   g.chunks = (int)chunks;
-  g.lda = (unsigned)(chunks * 8);
+  g.lda = (unsigned)(chunks * 16);
   g.a_bytes = (unsigned)a_bytes;
   g.b_bytes = (unsigned)b_bytes;
   g.M = c.K;
   g.NJ = c.C * c.R * c.S;
   g.st = st; g.sc = sc;
   g.out = dW;
-  return run_splitk(g, false, x_unsigned != 0, (long long)c.N * c.P * c.Q, acc, partial, s);
+  return run_splitk(g, x_unsigned != 0, (long long)c.N * c.P * c.Q, acc, partial, s);
 }
 
 // Linear layer (1x1 image): operands swap roles so that the row-major outputs
@@ -633,9 +649,9 @@ int launch_linear_dx(const ConvGeom& c, const uint8_t* w_codes, const uint8_t* g
   g.groups = c.Kp / kGranule;
   g.inner = 1;
   g.chunks = g.groups;
-  if ((long long)g.chunks * 8 * c.N >= (1ll << 31) || (long long)g.chunks * 8 * c.C >= (1ll << 31))
+  if ((long long)g.chunks * 16 * c.N >= (1ll << 31) || (long long)g.chunks * 16 * c.C >= (1ll << 31))
     return LBT_ERR_UNSUPPORTED;
-  g.lda = (unsigned)(g.chunks * 8);
+  g.lda = (unsigned)(g.chunks * 16);
   g.a_bytes = g.lda * (unsigned)c.N;
   g.b_bytes = g.lda * (unsigned)c.C;
   g.M = c.N;
@@ -656,16 +672,16 @@ int launch_linear_dw(const ConvGeom& c, const uint8_t* g_codes, const uint8_t* x
   g.groups = c.Np / kGranule;
   g.inner = 1;
   g.chunks = g.groups;
-  if ((long long)g.chunks * 8 * c.C >= (1ll << 31) || (long long)g.chunks * 8 * c.K >= (1ll << 31))
+  if ((long long)g.chunks * 16 * c.C >= (1ll << 31) || (long long)g.chunks * 16 * c.K >= (1ll << 31))
     return LBT_ERR_UNSUPPORTED;
-  g.lda = (unsigned)(g.chunks * 8);
+  g.lda = (unsigned)(g.chunks * 16);
   g.a_bytes = g.lda * (unsigned)c.C;
   g.b_bytes = g.lda * (unsigned)c.K;
   g.M = c.C;
   g.NJ = c.K;
   g.st = st; g.sc = sc;
   g.out = dW;
-  return run_splitk(g, x_unsigned != 0, false, (long long)c.N, acc, partial, s);
+  return run_splitk(g, x_unsigned != 0, (long long)c.N, acc, partial, s);
 }
 
 }  // namespace lbt

@@ -365,8 +365,8 @@ __global__ __launch_bounds__(kThreads) void k_quantize_flat(
 
 // ---------------------------------------------------------------------------
 // quantize + re-layout of T[A][B][L] (L contiguous) into the GEMM layouts
-//   out_b [A][BG][L][16]  sixteen consecutive b per 8-byte granule (BG = Bp/16)
-//   out_a [B][AG][L][16]  sixteen consecutive a per 8-byte granule (AG = Ap/16);
+//   out_b [A][BG][L][16]  sixteen consecutive b per 16-byte granule (BG = Bp/16)
+//   out_a [B][AG][L][16]  sixteen consecutive a per 16-byte granule (AG = Ap/16);
 //         [B][L][AG][16] when a_lmajor is set (the dX kernel reads weights tap by tap)
 // zero padded in the last granule.  A workgroup owns a 16(a) x 16(b) x TL(l)
 // tile: it quantizes into LDS (one byte per code, [a][b][l]), then each thread
@@ -387,12 +387,13 @@ struct TileArgs {
   unsigned long long seed;
   float* c_out;
   uint32_t* bad_out;
-  uint2* out_b;
-  uint2* out_a;
+  uint4* out_b;
+  uint4* out_a;
   int a_lmajor;
 };
 
-// Phase B: gather granules out of the LDS tile.  `pitch` = bytes per (a,b) row.
+// Phase B: gather granules out of the LDS tile.  `pitch` = bytes per (a,b) row.  A granule
+// is sixteen int8 codes (16 bytes), element j in byte j.
 // Byte-wise version (any tile length): one LDS byte read per code.
 __device__ __forceinline__ void store_granules(const TileArgs& t, const uint8_t* tile, int pitch,
                                                int tl, int a0, int b0, int l0) {
@@ -402,13 +403,10 @@ __device__ __forceinline__ void store_granules(const TileArgs& t, const uint8_t*
     for (int it = threadIdx.x; it < n_items; it += blockDim.x) {
       const int a = it / tl, l = it - a * tl;
       if (a0 + a >= t.A || l0 + l >= t.L) continue;
-      uint32_t w0 = 0, w1 = 0;
+      uint32_t w[4] = {0, 0, 0, 0};
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        w0 |= (uint32_t)tile[(a * 16 + j) * pitch + l] << (4 * j);
-        w1 |= (uint32_t)tile[(a * 16 + 8 + j) * pitch + l] << (4 * j);
-      }
-      t.out_b[((long long)(a0 + a) * t.BG + bg) * t.L + l0 + l] = make_uint2(w0, w1);
+      for (int j = 0; j < 16; ++j) w[j >> 2] |= (uint32_t)tile[(a * 16 + j) * pitch + l] << (8 * (j & 3));
+      t.out_b[((long long)(a0 + a) * t.BG + bg) * t.L + l0 + l] = make_uint4(w[0], w[1], w[2], w[3]);
     }
   }
   if (t.out_a) {
@@ -416,50 +414,41 @@ __device__ __forceinline__ void store_granules(const TileArgs& t, const uint8_t*
     for (int it = threadIdx.x; it < n_items; it += blockDim.x) {
       const int b = it / tl, l = it - b * tl;
       if (b0 + b >= t.B || l0 + l >= t.L) continue;
-      uint32_t w0 = 0, w1 = 0;
+      uint32_t w[4] = {0, 0, 0, 0};
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        w0 |= (uint32_t)tile[(j * 16 + b) * pitch + l] << (4 * j);
-        w1 |= (uint32_t)tile[((8 + j) * 16 + b) * pitch + l] << (4 * j);
-      }
+      for (int j = 0; j < 16; ++j) w[j >> 2] |= (uint32_t)tile[(j * 16 + b) * pitch + l] << (8 * (j & 3));
       const long long o = t.a_lmajor ? ((long long)(b0 + b) * t.L + l0 + l) * t.AG + ag
                                      : ((long long)(b0 + b) * t.AG + ag) * t.L + l0 + l;
-      t.out_a[o] = make_uint2(w0, w1);
+      t.out_a[o] = make_uint4(w[0], w[1], w[2], w[3]);
     }
   }
 }
 
 // Word-wise version for tile lengths that are multiples of 4: a thread takes the 16 LDS
-// words that hold four consecutive l of the sixteen rows of one granule column, merges
-// row pairs into bytes (two nibbles) and transposes 8 x 4 bytes with byte permutes,
-// producing the four granules l .. l+3 (32 contiguous bytes of output).
+// words that hold four consecutive l of the sixteen rows of one granule column and
+// transposes 16 x 4 bytes with byte permutes, producing the four granules l .. l+3
+// (64 contiguous bytes of output).
 //   base: LDS byte offset of row 0 of the group; stride: bytes between its rows
-__device__ __forceinline__ void granules4(const uint8_t* tile, int base, int stride, uint2 out[4]) {
-  uint32_t d[8];
-#pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    const uint32_t lo = *reinterpret_cast<const uint32_t*>(tile + base + (2 * j) * stride);
-    const uint32_t hi = *reinterpret_cast<const uint32_t*>(tile + base + (2 * j + 1) * stride);
-    d[j] = lo | (hi << 4);  // byte i: rows 2j (low nibble) and 2j+1 (high nibble) at l + i
-  }
+__device__ __forceinline__ void granules4(const uint8_t* tile, int base, int stride, uint4 out[4]) {
   // __builtin_amdgcn_perm(hi, lo, sel): result byte k = byte sel[k] of the 8-byte {hi:lo}
-  uint32_t p01[2], p23[2], p45[2], p67[2];
-  p01[0] = __builtin_amdgcn_perm(d[1], d[0], 0x05010400u);  // [d0.b0, d1.b0, d0.b1, d1.b1]
-  p01[1] = __builtin_amdgcn_perm(d[1], d[0], 0x07030602u);  // [d0.b2, d1.b2, d0.b3, d1.b3]
-  p23[0] = __builtin_amdgcn_perm(d[3], d[2], 0x05010400u);
-  p23[1] = __builtin_amdgcn_perm(d[3], d[2], 0x07030602u);
-  p45[0] = __builtin_amdgcn_perm(d[5], d[4], 0x05010400u);
-  p45[1] = __builtin_amdgcn_perm(d[5], d[4], 0x07030602u);
-  p67[0] = __builtin_amdgcn_perm(d[7], d[6], 0x05010400u);
-  p67[1] = __builtin_amdgcn_perm(d[7], d[6], 0x07030602u);
+  uint32_t q[4][4];  // q[g][l]: rows 4g .. 4g+3 at position l
 #pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    // l + 2h uses the low halves of the pair words, l + 2h + 1 the high halves
-    out[2 * h].x = __builtin_amdgcn_perm(p23[h], p01[h], 0x05040100u);
-    out[2 * h].y = __builtin_amdgcn_perm(p67[h], p45[h], 0x05040100u);
-    out[2 * h + 1].x = __builtin_amdgcn_perm(p23[h], p01[h], 0x07060302u);
-    out[2 * h + 1].y = __builtin_amdgcn_perm(p67[h], p45[h], 0x07060302u);
+  for (int g = 0; g < 4; ++g) {
+    uint32_t d[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      d[j] = *reinterpret_cast<const uint32_t*>(tile + base + (4 * g + j) * stride);
+    const uint32_t p01l = __builtin_amdgcn_perm(d[1], d[0], 0x05010400u);  // [d0.b0, d1.b0, d0.b1, d1.b1]
+    const uint32_t p01h = __builtin_amdgcn_perm(d[1], d[0], 0x07030602u);  // [d0.b2, d1.b2, d0.b3, d1.b3]
+    const uint32_t p23l = __builtin_amdgcn_perm(d[3], d[2], 0x05010400u);
+    const uint32_t p23h = __builtin_amdgcn_perm(d[3], d[2], 0x07030602u);
+    q[g][0] = __builtin_amdgcn_perm(p23l, p01l, 0x05040100u);  // [d0.b0, d1.b0, d2.b0, d3.b0]
+    q[g][1] = __builtin_amdgcn_perm(p23l, p01l, 0x07060302u);
+    q[g][2] = __builtin_amdgcn_perm(p23h, p01h, 0x05040100u);
+    q[g][3] = __builtin_amdgcn_perm(p23h, p01h, 0x07060302u);
   }
+#pragma unroll
+  for (int l = 0; l < 4; ++l) out[l] = make_uint4(q[0][l], q[1][l], q[2][l], q[3][l]);
 }
 
 __device__ __forceinline__ void store_granules_w4(const TileArgs& t, const uint8_t* tile, int pitch,
@@ -470,9 +459,9 @@ __device__ __forceinline__ void store_granules_w4(const TileArgs& t, const uint8
     for (int it = threadIdx.x; it < n_items; it += blockDim.x) {
       const int a = it / quads, l = (it - a * quads) * 4;
       if (a0 + a >= t.A) continue;
-      uint2 g4[4];
+      uint4 g4[4];
       granules4(tile, (a * 16) * pitch + l, pitch, g4);
-      uint2* dst = t.out_b + ((long long)(a0 + a) * t.BG + bg) * t.L + l0 + l;
+      uint4* dst = t.out_b + ((long long)(a0 + a) * t.BG + bg) * t.L + l0 + l;
 #pragma unroll
       for (int i = 0; i < 4; ++i) dst[i] = g4[i];
     }
@@ -482,7 +471,7 @@ __device__ __forceinline__ void store_granules_w4(const TileArgs& t, const uint8
     for (int it = threadIdx.x; it < n_items; it += blockDim.x) {
       const int b = it / quads, l = (it - b * quads) * 4;
       if (b0 + b >= t.B) continue;
-      uint2 g4[4];
+      uint4 g4[4];
       granules4(tile, b * pitch + l, 16 * pitch, g4);
       const long long o = t.a_lmajor ? ((long long)(b0 + b) * t.L + l0 + l) * t.AG + ag
                                      : ((long long)(b0 + b) * t.AG + ag) * t.L + l0 + l;
@@ -602,7 +591,7 @@ __device__ __forceinline__ void stream_body(const TileArgs& t, int pitch, int tl
       for (int u = 0; u < 8; ++u) {
         int k = 0;
         if (have) k = quantize_one<MODE>(v[u], qc, rnd, u, cnt);
-        dyn_tile[(p.row * 16 + b) * pitch + l] = (uint8_t)(k & 0xF);
+        dyn_tile[(p.row * 16 + b) * pitch + l] = (uint8_t)k;
         if (++l == t.L) { l = 0; ++b; }
       }
     } else {
@@ -611,12 +600,12 @@ __device__ __forceinline__ void stream_body(const TileArgs& t, int pitch, int tl
         if (p.v0) {
 #pragma unroll
           for (int u = 0; u < 4; ++u)
-            w0 |= ((uint32_t)quantize_one<MODE>(v[u], qc, rnd, u, cnt) & 0xFu) << (8 * u);
+            w0 |= ((uint32_t)quantize_one<MODE>(v[u], qc, rnd, u, cnt) & 0xFFu) << (8 * u);
         }
         if (p.v1) {
 #pragma unroll
           for (int u = 0; u < 4; ++u)
-            w1 |= ((uint32_t)quantize_one<MODE>(v[4 + u], qc, rnd, 4 + u, cnt) & 0xFu) << (8 * u);
+            w1 |= ((uint32_t)quantize_one<MODE>(v[4 + u], qc, rnd, 4 + u, cnt) & 0xFFu) << (8 * u);
         }
       }
       uint8_t* dst = dyn_tile + p.row * pitch + p.off;
@@ -678,7 +667,7 @@ __device__ __forceinline__ void generic_body(const TileArgs& t, const TileCoord&
       if (MODE == 3) rnd = philox_block((unsigned long long)e >> 3, step, t.seed);
       k = quantize_one<MODE>(t.x[e], qc, rnd, (uint32_t)e & 7u, cnt);
     }
-    tile[row * PITCH + l] = (uint8_t)(k & 0xF);
+    tile[row * PITCH + l] = (uint8_t)k;
   }
   __syncthreads();
   store_granules(t, tile, PITCH, TL, a0, b0, l0);
@@ -864,8 +853,8 @@ static void fill_tile_args(TileArgs& t, const float* x, int64_t A, int64_t B, in
   t.BG = (int)(round_up(B, kGranule) / kGranule);
   t.pmax = io.pmax; t.nblocks = io.nblocks; t.pmax_col = io.pmax_col;
   t.st = io.st;
-  t.out_b = reinterpret_cast<uint2*>(io.out_b);
-  t.out_a = reinterpret_cast<uint2*>(io.out_a);
+  t.out_b = reinterpret_cast<uint4*>(io.out_b);
+  t.out_a = reinterpret_cast<uint4*>(io.out_a);
   t.a_lmajor = io.a_lmajor;
 }
 

@@ -81,8 +81,8 @@ def test_workspace_formula(lib):
     N, Cc, H, W, K, R, S, st, pad = 64, 256, 14, 14, 256, 3, 3, 1, 1
     P = Q = 14
     pad256 = lambda b: (b + 255) // 256 * 256
-    want = 256 + 2048 * 16 + pad256(N * P * Q * K // 2) + pad256(K * P * Q * N // 2) \
-        + pad256(Cc * H * W * N // 2) + pad256(Cc * R * S * K // 2)
+    want = 256 + 2048 * 16 + pad256(N * P * Q * K) + pad256(K * P * Q * N) \
+        + pad256(Cc * H * W * N) + pad256(Cc * R * S * K)
     got = lib.lbt_workspace_bytes_conv2d(N, Cc, H, W, K, R, S, st, pad)
     partial = got - want
     # dW is [256][2304] int32; the contraction is cut into at most 512/36 slices
