@@ -74,7 +74,7 @@ int launch_quantize_flat_grad(const float* g, int64_t n, const uint32_t* pmax, i
 int launch_quantize_flat_operand(const float* x, int64_t n, float c_given, const uint32_t* pmax,
                                  int nblocks, int is_unsigned, uint8_t* codes, float* c_out,
                                  float* clip_scale_out, hipStream_t s);
-// Quantize T[A][B][L] (L contiguous) into GEMM layouts of 8-byte granules (16 codes):
+// Quantize T[A][B][L] (L contiguous) into GEMM layouts of 16-byte granules (16 int8 codes):
 // out_b [A][ceil(B/16)][L][16] and out_a [B][ceil(A/16)][L][16] (either may be null).
 // The tensor maximum, where needed, comes from the partial maxima of launch_absmax3.
 struct RelayoutIo {

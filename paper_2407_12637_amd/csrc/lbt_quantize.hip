@@ -1,7 +1,7 @@
 // Quantizer kernels: tensor maximum, uniform b=4 quantizer (Eq. 1-4 of the paper)
 // with nearest or stochastic rounding, clip-out count (Sec. 3.3, Alg. 1 step 5),
-// nibble packing in the flat format of the C ABI and in the two GEMM layouts,
-// and the one-thread clipping-factor update (Eq. 15-16).
+// nibble packing in the flat format of the C ABI, byte-per-code granules in the two
+// GEMM layouts, and the one-thread clipping-factor update (Eq. 15-16).
 //
 // Arithmetic contract (decides integer codes, so it is fixed to the last bit):
 //   c      = (float)(gamma * (double)g_max)
@@ -370,7 +370,7 @@ __global__ __launch_bounds__(kThreads) void k_quantize_flat(
 //         [B][L][AG][16] when a_lmajor is set (the dX kernel reads weights tap by tap)
 // zero padded in the last granule.  A workgroup owns a 16(a) x 16(b) x TL(l)
 // tile: it quantizes into LDS (one byte per code, [a][b][l]), then each thread
-// gathers the sixteen codes of one granule and stores 8 bytes; consecutive
+// gathers the sixteen codes of one granule and stores its 16 bytes; consecutive
 // threads store consecutive l, so the stores are contiguous.
 // ---------------------------------------------------------------------------
 struct TileArgs {
