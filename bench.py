@@ -34,7 +34,7 @@ BYTES_PER_GRAD_ELEMENT = 4.5    # algorithmic: 4 B fp32 read + 0.5 B code writte
 # measured live on the one-thread clipping-factor update kernel, whose own duration is
 # known from rocprofv3 (profiles/bench_resnet50_b64_kernel_stats.txt), and removed:
 #   kernel time = bracket(kernel) - (bracket(update kernel) - UPDATE_KERNEL_US)
-UPDATE_KERNEL_US = 3.7
+UPDATE_KERNEL_US = 4.1
 
 
 def parse():
@@ -47,6 +47,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
     ap.add_argument("--layer", default=None, help="run only layers whose name contains this")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="only run three plain 256 MiB device copies (calibrates the HBM byte "
+                         "counters of a rocprofv3 --pmc run) and exit")
     return ap.parse_args()
 
 
@@ -99,7 +102,10 @@ def cpu_baseline(layers, rounding):
     import numpy as np
 
     import oracle
-    pick = ["l3.3x3.256-256@14", "l2.1x1.128-512@28", "l4.1x1.512-2048@7", "l1.3x3.64-64@56"]
+    # a bounded sample (about 10 s of host time on the GPU machine) that spans the sweep's stages
+    pick = ["l1.3x3.64-64@56", "l1.1x1.64-256@56", "l2.1x1.128-512@28", "l2.3x3.128-128@28",
+            "l2.3x3s2.128-128@56", "l3.1x1.256-1024@14", "l3.3x3.256-256@14", "l3.1x1.1024-256@14",
+            "l4.1x1.512-2048@7", "l4.3x3.512-512@7", "l4.1x1.2048-512@7", "l3.3x3s2.256-256@28"]
     chosen = [L for L in layers if not L.is_linear and L.spec.name in pick]
     seen, sample = set(), []
     for L in chosen:
@@ -126,10 +132,25 @@ def cpu_baseline(layers, rounding):
     return {
         "value": ops / t_total / 1e12, "unit": "TOPS", "cores": oracle.num_threads(),
         "kind": "oracle",
-        "sample": "full backward (quantize dY/X/W + dX + dW + update) of %d layers: %s; %.1f s"
+        "sample": "full backward (quantize dY/X/W + dX + dW + update) of %d layers of the sweep: %s; %.1f s"
                   % (len(sample), ", ".join(L.spec.name for L in sample), t_total),
         "quantize_GBps": n_grad * BYTES_PER_GRAD_ELEMENT / t_quant / 1e9,
     }
+
+
+def measured_traffic(kernel_class):
+    """HBM bytes per launch (fetched + written) of a kernel class, from the committed summary
+    of the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this benchmark; None if absent."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles",
+                        "bench_resnet50_b64_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            f = line.split()
+            if len(f) == 4 and f[0] == "TRAFFIC" and f[1] == kernel_class:
+                return float(f[2].split("=")[1]) + float(f[3].split("=")[1])
+    except OSError:
+        pass
+    return None
 
 
 def main():
@@ -145,6 +166,15 @@ def main():
 
     lbt.load()
     torch.cuda.set_device(0)
+    if args.copy_probe:
+        n = 256 << 20
+        src = torch.full((n,), 7, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe_bytes_each_way": n, "copies": 3}))
+        return
     rounding = lbt.ROUND_STOCHASTIC if args.rounding == "stochastic" else lbt.ROUND_NEAREST
     gen = torch.Generator(device="cuda")
     gen.manual_seed(0)
@@ -216,16 +246,17 @@ def main():
             kernels[name] = k
         out["kernels"] = kernels
         dom = max(kernels, key=lambda n: kernels[n]["ms_per_step"])
+        traffic = measured_traffic(dom)
         if "gemm" in dom:
             ach = kernels[dom]["TOPS"]
             out["roofline"] = {"kernel": dom, "bound": "mfma", "achieved": ach,
                                "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
-                               "frac": ach / PEAK_INT8_TOPS, "traffic": None}
+                               "frac": ach / PEAK_INT8_TOPS, "traffic": traffic}
         else:
             ach = kernels[dom].get("GBps", 0.0)
             out["roofline"] = {"kernel": dom, "bound": "hbm", "achieved": ach,
                                "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBPS,
-                               "traffic": None}
+                               "traffic": traffic}
         # the quantize pass = the maximum kernel + the quantize kernel (gradient, activations
         # and weights of a layer share both launches), rated at the algorithmic 4.5 B per
         # quantized element
