@@ -309,6 +309,9 @@ __global__ __launch_bounds__(kThreads) void k_implicit_gemm(const GemmArgs g) {
     }
   };
 
+  // the output scale's inputs are fetched now, long before the epilogue needs them
+  const float scale = (g.epi == 1) ? 0.0f : output_scale(g);
+
   v16i acc[TM][TN];
 #pragma unroll
   for (int i = 0; i < TM; ++i)
@@ -373,7 +376,6 @@ __global__ __launch_bounds__(kThreads) void k_implicit_gemm(const GemmArgs g) {
 
   // ---- epilogue.  32x32 accumulator block: lane holds column (lane % 32) and rows
   // 8*(r/4) + 4*(lane/32) + r%4 for r = 0..15, so 32 lanes store 32 consecutive columns.
-  const float scale = (g.epi == 1) ? 0.0f : output_scale(g);
 #pragma unroll
   for (int j = 0; j < TN; ++j) {
     const int col_j = j0 + wn + j * 32 + (lane & 31);
@@ -407,21 +409,45 @@ __global__ __launch_bounds__(kThreads) void k_implicit_gemm(const GemmArgs g) {
 }
 
 // Sum the split-K partial tiles and apply the scale: out = (sum_s partial[s]) * s_a * s_b.
+// A workgroup takes 256 / SL consecutive outputs; SL groups of threads share the slices
+// (group w sums slices w, w + SL, ..., eight loads in flight per thread) and meet in LDS.
+// SL = 4 for many slices of a small output, SL = 1 for few slices of a large one.
+// Integer adds: the result does not depend on how the slices are grouped.
+template <int SL>
 __global__ __launch_bounds__(kThreads) void k_splitk_reduce(const int32_t* __restrict__ partial,
                                                              int splits, long long n, GemmArgs g) {
+  constexpr int OUTS = kThreads / SL;
+  __shared__ int red[SL][OUTS];
   const float scale = output_scale(g);
-  const long long stride = (long long)gridDim.x * kThreads;
-  for (long long i = (long long)blockIdx.x * kThreads + threadIdx.x; i < n; i += stride) {
+  const int io = threadIdx.x % OUTS, sl = threadIdx.x / OUTS;
+  for (long long base = (long long)blockIdx.x * OUTS; base < n; base += (long long)gridDim.x * OUTS) {
+    const long long i = base + io;
     int sum = 0;
-    int s = 0;
-    for (; s + 4 <= splits; s += 4) {
-      const int v0 = partial[(long long)s * n + i], v1 = partial[(long long)(s + 1) * n + i];
-      const int v2 = partial[(long long)(s + 2) * n + i], v3 = partial[(long long)(s + 3) * n + i];
-      sum += (v0 + v1) + (v2 + v3);
+    if (i < n) {
+      for (int s0 = sl; s0 < splits; s0 += 8 * SL) {
+        int v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int sp = s0 + SL * u;
+          v[u] = sp < splits ? partial[(long long)sp * n + i] : 0;
+        }
+        sum += ((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7]));
+      }
     }
-    for (; s < splits; ++s) sum += partial[(long long)s * n + i];
-    g.out[i] = (float)sum * scale;
-    if (g.acc) g.acc[i] = sum;
+    if (SL > 1) {
+      red[sl][io] = sum;
+      __syncthreads();
+      if (sl == 0) {
+        sum = 0;
+#pragma unroll
+        for (int w = 0; w < SL; ++w) sum += red[w][io];
+      }
+    }
+    if (sl == 0 && i < n) {
+      g.out[i] = (float)sum * scale;
+      if (g.acc) g.acc[i] = sum;
+    }
+    if (SL > 1) __syncthreads();
   }
 }
 
@@ -549,10 +575,15 @@ int run_splitk(GemmArgs& g, bool x_unsigned, long long true_k, int32_t* acc, int
   const long long n_out = (long long)g.M * g.NJ;
   ProfScope prof(KID_FINALIZE, (double)n_out, s);
   g.acc = acc;
-  long long blocks = (n_out + kThreads - 1) / kThreads;
+  const bool many = plan.splits >= 8;
+  long long blocks = (n_out + (many ? 63 : 255)) / (many ? 64 : 256);
   if (blocks > 4096) blocks = 4096;
-  LBT_LAUNCH(k_splitk_reduce, dim3((unsigned)blocks), dim3(kThreads), 0, s, partial,
-                     plan.splits, n_out, g);
+  if (many)
+    LBT_LAUNCH(k_splitk_reduce<4>, dim3((unsigned)blocks), dim3(kThreads), 0, s, partial, plan.splits,
+               n_out, g);
+  else
+    LBT_LAUNCH(k_splitk_reduce<1>, dim3((unsigned)blocks), dim3(kThreads), 0, s, partial, plan.splits,
+               n_out, g);
   LBT_LAUNCH_CHECK();
   return LBT_OK;
 }
