@@ -60,6 +60,10 @@ class ProfScope {
 constexpr int kMaxPartialBlocks = 2048;  // partial-maximum slots in the workspace header
 // Workspace header: OperandScalars (256 bytes), then pmax[kMaxPartialBlocks][4] uint32.
 constexpr size_t kWsScalarsBytes = 256;
+// Inside the scalars: 16 arrival counters (8 bytes each) of the gradient quantizer's
+// two-level ticket, zeroed by every launch of the maximum kernel.
+constexpr size_t kWsTicketOffset = 64;
+constexpr int kTicketSlots = 16;
 constexpr size_t kWsHeaderBytes = kWsScalarsBytes + (size_t)kMaxPartialBlocks * 16;
 
 // One launch for the maxima of up to three tensors (null pointer = absent); partial

@@ -13,10 +13,11 @@
 // A tensor is swept twice: k_absmax3 takes the maxima of up to three tensors in one
 // launch (one partial maximum per workgroup, no atomics), then a quantizer kernel
 // re-reduces those partials in its prologue and streams the tensor once more (the
-// second read mostly hits the memory-side cache).  The clip-out count travels in ONE
-// 64-bit atomic per workgroup (count in the low 40 bits, arrival ticket above) on a
-// word of the layer state that the last workgroup resets to zero; no scratch memory
-// has to be zero-initialised by anyone.
+// second read mostly hits the memory-side cache).  The clip-out count travels in one
+// 64-bit atomic per workgroup (count in the low 40 bits, arrival ticket above) on one of
+// 16 counters in the workspace, whose sums meet in a word of the layer state; k_absmax3
+// zeroes the counters and the last workgroup clears the word, so no scratch memory has to
+// be zero-initialised by the caller.
 #include "lbt_internal.h"
 
 namespace lbt {
@@ -183,16 +184,34 @@ __device__ __forceinline__ GradSetup grad_setup(const lbt_grad_state* st, const 
   return g;
 }
 
-// One atomic per workgroup carries the clip-out count and the arrival ticket; the
-// last workgroup to arrive publishes the statistics and clears the word.
+// The arrival counters of the two-level ticket sit in the workspace, a fixed distance in
+// front of the partial maxima.
+__device__ __forceinline__ unsigned long long* ticket_slots(const uint32_t* pmax) {
+  return reinterpret_cast<unsigned long long*>(
+      reinterpret_cast<uintptr_t>(pmax) - (kWsScalarsBytes - kWsTicketOffset));
+}
+
+// One atomic per workgroup carries the clip-out count and the arrival ticket.  Workgroup
+// `id` reports to counter id % 16 (atomics on one address complete at about 16 ns each;
+// with thousands of workgroups one counter would be the longest chain of the kernel); the
+// workgroup that completes a counter forwards its sum to the state's word, and the one
+// that completes that word publishes the statistics and clears it.  The 16 counters are
+// zeroed by k_absmax3, which runs before every gradient quantizer.
 __device__ __forceinline__ void grad_finish(lbt_grad_state* st, const GradSetup& g, uint32_t cnt,
-                                            unsigned long long n_total, unsigned long long nblk) {
+                                            unsigned long long n_total, unsigned nblk, unsigned id,
+                                            unsigned long long* slots) {
   const uint32_t tot = block_sum(cnt);
   if (threadIdx.x == 0) {
-    const unsigned long long old =
-        atomicAdd(reinterpret_cast<unsigned long long*>(&st->sync_word), kTicket + tot);
-    if ((old >> 40) == nblk - 1) {
-      st->n_out = (old + tot) & kCountMask;
+    const unsigned slot = id % kTicketSlots;
+    const unsigned in_slot = (nblk - slot + kTicketSlots - 1) / kTicketSlots;
+    const unsigned long long old = atomicAdd(&slots[slot], kTicket + tot);
+    if ((old >> 40) != in_slot - 1) return;
+    const unsigned long long sub = (old + tot) & kCountMask;
+    const unsigned n_slots = nblk < (unsigned)kTicketSlots ? nblk : (unsigned)kTicketSlots;
+    const unsigned long long old2 =
+        atomicAdd(reinterpret_cast<unsigned long long*>(&st->sync_word), kTicket + sub);
+    if ((old2 >> 40) == n_slots - 1) {
+      st->n_out = (old2 + sub) & kCountMask;
       st->n_total = n_total;
       st->gmax = g.gmax;
       st->clip = g.c;
@@ -276,8 +295,11 @@ __global__ __launch_bounds__(kThreads) void k_absmax3(MaxSeg s0, MaxSeg s1, MaxS
                                                        long long per_block, uint32_t* pmax,
                                                        lbt_grad_state* st) {
   const int blk = blockIdx.x;
-  // every quantizer launch that follows reports into a fresh status
-  if (st && blk == 0 && threadIdx.x == 0) st->status = LBT_STATUS_OK;
+  // every quantizer launch that follows reports into a fresh status and fresh counters
+  if (blk == 0) {
+    if (st && threadIdx.x == 0) st->status = LBT_STATUS_OK;
+    if (threadIdx.x < kTicketSlots) ticket_slots(pmax)[threadIdx.x] = 0ull;
+  }
   int t = 0;
   MaxSeg s = s0;
   if (blk >= s2.first_block) { s = s2; t = 2; }
@@ -360,7 +382,7 @@ __global__ __launch_bounds__(kThreads) void k_quantize_flat(
       for (int j = 0; j < nbytes; ++j) codes[gi * 4 + j] = (uint8_t)(word >> (8 * j));
     }
   }
-  if (kGrad) grad_finish(st, gs, cnt, (unsigned long long)n, gridDim.x);
+  if (kGrad) grad_finish(st, gs, cnt, (unsigned long long)n, gridDim.x, blockIdx.x, ticket_slots(pmax));
 }
 
 // ---------------------------------------------------------------------------
@@ -555,6 +577,7 @@ __host__ __device__ inline int window_len(int L) {
 struct TileCoord {
   int x, y, z;          // tile index along l, b, a
   unsigned n_blocks;    // workgroups that work on this tensor
+  unsigned id;          // this workgroup's index among them
   bool first;           // the tensor's first workgroup
 };
 
@@ -631,7 +654,8 @@ __device__ __forceinline__ void stream_body(const TileArgs& t, int pitch, int tl
   __syncthreads();
   if (SMALL) store_granules(t, dyn_tile, pitch, t.L, a0, b0, 0);
   else store_granules_w4(t, dyn_tile, pitch, min(tl, t.L - l0), a0, b0, l0);
-  if (kGrad) grad_finish(t.st, gs, cnt, (unsigned long long)t.A * t.B * t.L, bc.n_blocks);
+  if (kGrad) grad_finish(t.st, gs, cnt, (unsigned long long)t.A * t.B * t.L, bc.n_blocks, bc.id,
+                         ticket_slots(t.pmax));
 }
 
 // ---------------------------------------------------------------------------
@@ -671,7 +695,81 @@ __device__ __forceinline__ void generic_body(const TileArgs& t, const TileCoord&
   }
   __syncthreads();
   store_granules(t, tile, PITCH, TL, a0, b0, l0);
-  if (MODE >= 2) grad_finish(t.st, gs, cnt, (unsigned long long)t.A * t.B * t.L, bc.n_blocks);
+  if (MODE >= 2) grad_finish(t.st, gs, cnt, (unsigned long long)t.A * t.B * t.L, bc.n_blocks, bc.id,
+                             ticket_slots(t.pmax));
+}
+
+// ---------------------------------------------------------------------------
+// Matrices (L = 1, B % 8 == 0, 16-byte aligned): one 64(a) x 64(b) tile per workgroup.
+// A thread quantizes two runs of 8 consecutive b (one generator block each) into an [a][b]
+// LDS tile.  Granules along b are 16 consecutive tile bytes (one per thread); granules along a
+// come out of the 16 x 4 byte transpose also used by the streaming tiles (64 threads, four
+// granules each).  Four neighbouring threads store 64 contiguous bytes.
+// ---------------------------------------------------------------------------
+template <int MODE>
+__device__ __forceinline__ void matrix_body(const TileArgs& t, const TileCoord& bc, uint8_t* lds) {
+  constexpr int PITCH = 80;
+  uint8_t* const tile = lds;                 // [64 a][PITCH]
+  GradSetup gs{};
+  float c;
+  if (MODE >= 2) {
+    gs = grad_setup(t.st, t.pmax, t.nblocks);
+    c = gs.c;
+  } else if (!(t.c_given > 0.0f) && t.c_ptr) {
+    c = *t.c_ptr;
+  } else {
+    c = operand_setup(t.c_given, t.pmax, t.nblocks, t.pmax_col, MODE == 1, t.c_out, t.bad_out, t.st,
+                      nullptr, bc.first);
+  }
+  const QConst qc = make_qconst(c, MODE == 1);
+  const bool live = c > 0.0f;
+  const unsigned long long step = (MODE == 3) ? t.st->step : 0ull;
+  const int b0 = bc.x * 64, a0 = bc.z * 64;
+  uint32_t cnt = 0;
+  float v[2][8];
+  bool ok[2];
+  long long e0[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int it = threadIdx.x + kThreads * i;
+    const int row = it >> 3, col = (it & 7) * 8;
+    ok[i] = a0 + row < t.A && b0 + col < t.B;
+    e0[i] = ok[i] ? (long long)(a0 + row) * t.B + b0 + col : 0;
+    const float4 lo = *reinterpret_cast<const float4*>(t.x + e0[i]);
+    const float4 hi = *reinterpret_cast<const float4*>(t.x + e0[i] + 4);
+    v[i][0] = lo.x; v[i][1] = lo.y; v[i][2] = lo.z; v[i][3] = lo.w;
+    v[i][4] = hi.x; v[i][5] = hi.y; v[i][6] = hi.z; v[i][7] = hi.w;
+  }
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int it = threadIdx.x + kThreads * i;
+    const int row = it >> 3, col = (it & 7) * 8;
+    Philox4 rnd{};
+    if (MODE == 3 && live && ok[i]) rnd = philox_block((unsigned long long)e0[i] >> 3, step, t.seed);
+    uint32_t w0 = 0, w1 = 0;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      int k = 0;
+      if (live && ok[i]) k = quantize_one<MODE>(v[i][u], qc, rnd, u, cnt);
+      const uint32_t byte = (uint32_t)k & 0xFFu;
+      if (u < 4) w0 |= byte << (8 * u); else w1 |= byte << (8 * (u - 4));
+    }
+    *reinterpret_cast<uint2*>(tile + row * PITCH + col) = make_uint2(w0, w1);
+  }
+  __syncthreads();
+  const int r = threadIdx.x >> 2, gl = threadIdx.x & 3;
+  if (t.out_b && a0 + r < t.A && (b0 >> 4) + gl < t.BG)
+    t.out_b[(long long)(a0 + r) * t.BG + (b0 >> 4) + gl] =
+        *reinterpret_cast<const uint4*>(tile + r * PITCH + 16 * gl);
+  if (t.out_a && threadIdx.x < 64 && (a0 >> 4) + gl < t.AG) {
+    uint4 g4[4];
+    granules4(tile, (16 * gl) * PITCH + 4 * r, PITCH, g4);   // b = 4 r .. 4 r + 3, a = 16 gl .. + 15
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      if (b0 + 4 * r + i < t.B) t.out_a[(long long)(b0 + 4 * r + i) * t.AG + (a0 >> 4) + gl] = g4[i];
+  }
+  if (MODE >= 2) grad_finish(t.st, gs, cnt, (unsigned long long)t.A * t.B * t.L, bc.n_blocks, bc.id,
+                             ticket_slots(t.pmax));
 }
 
 // ---------------------------------------------------------------------------
@@ -679,13 +777,13 @@ __device__ __forceinline__ void generic_body(const TileArgs& t, const TileCoord&
 // weights): workgroups [first, first + n_blocks) belong to a tensor and walk its tiles in
 // the order l fastest, then b, then a.
 // ---------------------------------------------------------------------------
-enum TileKind { kGenericTile = 0, kGenericColumn, kWindowed, kWholeRow };
+enum TileKind { kGenericTile = 0, kGenericColumn, kWindowed, kWholeRow, kMatrix };
 
 struct Segment {
   TileArgs t;
   int kind;             // TileKind
   int pitch, tl;        // LDS row pitch and tile length along l (streaming kinds)
-  unsigned gx, gy;      // tiles along l and b
+  unsigned gx, gy, gz;  // tiles along l, b and a
   unsigned first, n_blocks;
 };
 
@@ -698,11 +796,13 @@ __device__ __forceinline__ void run_segment(const Segment& sg, unsigned blk, uin
   bc.y = (int)(rest % sg.gy);
   bc.z = (int)(rest / sg.gy);
   bc.n_blocks = sg.n_blocks;
+  bc.id = local;
   bc.first = local == 0;
   switch (sg.kind) {
     case kWindowed: stream_body<MODE, false>(sg.t, sg.pitch, sg.tl, bc, lds); break;
     case kWholeRow: stream_body<MODE, true>(sg.t, sg.pitch, sg.tl, bc, lds); break;
     case kGenericColumn: generic_body<MODE, 1>(sg.t, bc, lds); break;
+    case kMatrix: matrix_body<MODE>(sg.t, bc, lds); break;
     default: generic_body<MODE, 32>(sg.t, bc, lds);
   }
 }
@@ -721,10 +821,12 @@ __global__ __launch_bounds__(kThreads) void k_quantize_grad(const Segment sg) {
   bc.y = (int)(rest % sg.gy);
   bc.z = (int)(rest / sg.gy);
   bc.n_blocks = sg.n_blocks;
+  bc.id = local;
   bc.first = local == 0;
   if (KIND == kWindowed) stream_body<MODE, false>(sg.t, sg.pitch, sg.tl, bc, dyn_tile);
   else if (KIND == kWholeRow) stream_body<MODE, true>(sg.t, sg.pitch, sg.tl, bc, dyn_tile);
   else if (KIND == kGenericColumn) generic_body<MODE, 1>(sg.t, bc, dyn_tile);
+  else if (KIND == kMatrix) matrix_body<MODE>(sg.t, bc, dyn_tile);
   else generic_body<MODE, 32>(sg.t, bc, dyn_tile);
 }
 
@@ -750,6 +852,7 @@ inline int flat_grid(long long work_items) {
 
 TileKind tile_kind(const float* x, long long B, long long L) {
   if (reinterpret_cast<uintptr_t>(x) % 16 == 0) {
+    if (L == 1 && B % 8 == 0) return kMatrix;
     if (L >= 16 && L % 4 == 0) return kWindowed;
     if (L >= 2 && L <= 248 && B % 16 == 0 && (B * L) % 8 == 0) return kWholeRow;
   }
@@ -761,6 +864,7 @@ size_t plan_segment(Segment& sg) {
   const TileArgs& t = sg.t;
   sg.kind = tile_kind(t.x, t.B, t.L);
   sg.gy = (unsigned)t.BG;
+  sg.gz = (unsigned)t.AG;
   size_t lds;
   switch (sg.kind) {
     case kWindowed:
@@ -778,6 +882,13 @@ size_t plan_segment(Segment& sg) {
     case kGenericColumn:
       sg.tl = 1; sg.pitch = 1; sg.gx = 1;
       lds = 256;
+      break;
+    case kMatrix:
+      sg.tl = 1; sg.pitch = 80;
+      sg.gx = (unsigned)((t.B + 63) / 64);
+      sg.gy = 1;
+      sg.gz = (unsigned)((t.A + 63) / 64);
+      lds = (size_t)64 * 80;
       break;
     default:
       sg.tl = 32; sg.pitch = 36;
@@ -875,7 +986,7 @@ int launch_quantize_layer(const LayerTensors& q, hipStream_t s) {
     sg.t.bad_out = o.bad_out;
     const size_t need = plan_segment(sg);
     if (need > lds) lds = need;
-    const unsigned long long nb = (unsigned long long)sg.gx * sg.gy * (unsigned long long)sg.t.AG;
+    const unsigned long long nb = (unsigned long long)sg.gx * sg.gy * sg.gz;
     if (nb == 0 || next + nb > 0x7fffffffull) return LBT_ERR_UNSUPPORTED;
     sg.n_blocks = (unsigned)nb;
     next += nb;
@@ -899,6 +1010,7 @@ int launch_quantize_layer(const LayerTensors& q, hipStream_t s) {
     LBT_GRAD_CASE(kWindowed)
     LBT_GRAD_CASE(kWholeRow)
     LBT_GRAD_CASE(kGenericColumn)
+    LBT_GRAD_CASE(kMatrix)
     LBT_GRAD_CASE(kGenericTile)
 #undef LBT_GRAD_CASE
     LBT_LAUNCH_CHECK();
