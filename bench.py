@@ -47,6 +47,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
     ap.add_argument("--layer", default=None, help="run only layers whose name contains this")
+    ap.add_argument("--workload", choices=["resnet50", "vit-l"], default="resnet50",
+                    help="resnet50: the headline sweep (default); vit-l: the linear layers of one "
+                         "ViT-L encoder block at batch 64 x 197 tokens (signed activations)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="only run three plain 256 MiB device copies (calibrates the HBM byte "
                          "counters of a rocprofv3 --pmc run) and exit")
@@ -56,9 +59,9 @@ def parse():
 class LayerRun:
     """Device tensors and state of one layer occurrence."""
 
-    def __init__(self, spec, idx, torch, lbt, gen, is_linear):
+    def __init__(self, spec, idx, torch, lbt, gen, is_linear, x_unsigned=True):
         dev = "cuda"
-        self.spec, self.is_linear = spec, is_linear
+        self.spec, self.is_linear, self.x_unsigned = spec, is_linear, x_unsigned
         f32 = torch.float32
         if is_linear:
             xs, ws, gs = (spec.M, spec.K), (spec.K, spec.N), (spec.M, spec.N)
@@ -66,7 +69,9 @@ class LayerRun:
         else:
             xs, ws, gs = spec.x_shape, spec.w_shape, spec.dy_shape
             fan_in = spec.C * spec.R * spec.S
-        self.X = torch.randn(xs, generator=gen, device=dev, dtype=f32).clamp_(min=0)
+        self.X = torch.randn(xs, generator=gen, device=dev, dtype=f32)
+        if x_unsigned:
+            self.X.clamp_(min=0)        # post-ReLU activations, quantized with Eq. 3
         self.W = torch.randn(ws, generator=gen, device=dev, dtype=f32).mul_((2.0 / fan_in) ** 0.5)
         # Student-t(nu) = Z / sqrt(chi2_nu / nu), chi2_nu = 2 * Gamma(nu / 2)
         nu = 2.5
@@ -88,12 +93,12 @@ class LayerRun:
     def run(self, lbt, ws, rounding):
         s = self.spec
         if self.is_linear:
-            lbt.lbt_backward_linear(self.X, self.W, self.dY, s.M, s.K, s.N, 0.0, True, 0.0,
-                                    self.state, self.seed, rounding, self.dX, self.dW, ws)
+            lbt.lbt_backward_linear(self.X, self.W, self.dY, s.M, s.K, s.N, 0.0, self.x_unsigned,
+                                    0.0, self.state, self.seed, rounding, self.dX, self.dW, ws)
         else:
             lbt.lbt_backward_conv2d(self.X, self.W, self.dY, s.N, s.C, s.H, s.W, s.K, s.R, s.S,
-                                    s.stride, s.pad, 0.0, True, 0.0, self.state, self.seed,
-                                    rounding, self.dX, self.dW, ws)
+                                    s.stride, s.pad, 0.0, self.x_unsigned, 0.0, self.state,
+                                    self.seed, rounding, self.dX, self.dW, ws)
         lbt.lbt_update_interval(self.state)
 
 
@@ -107,6 +112,8 @@ def cpu_baseline(layers, rounding):
             "l2.3x3s2.128-128@56", "l3.1x1.256-1024@14", "l3.3x3.256-256@14", "l3.1x1.1024-256@14",
             "l4.1x1.512-2048@7", "l4.3x3.512-512@7", "l4.1x1.2048-512@7", "l3.3x3s2.256-256@28"]
     chosen = [L for L in layers if not L.is_linear and L.spec.name in pick]
+    if not chosen:      # a sweep of linear layers: its smallest layer
+        chosen = [min(layers, key=lambda L: L.spec.gemm_ops)]
     seen, sample = set(), []
     for L in chosen:
         if L.spec.name not in seen:
@@ -121,8 +128,12 @@ def cpu_baseline(layers, rounding):
         oracle.quantize_grad(dY, st, L.seed, rounding)
         t1 = time.perf_counter()
         st = oracle.GradState(gamma=1.0)
-        oracle.backward_conv2d(X, W, dY, s.stride, s.pad, st, x_unsigned=True, seed=L.seed,
-                               rounding=rounding)
+        if L.is_linear:
+            oracle.backward_linear(X, W, dY, st, x_unsigned=L.x_unsigned, seed=L.seed,
+                                   rounding=rounding)
+        else:
+            oracle.backward_conv2d(X, W, dY, s.stride, s.pad, st, x_unsigned=L.x_unsigned,
+                                   seed=L.seed, rounding=rounding)
         oracle.update_interval(st)
         t2 = time.perf_counter()
         ops += 2.0 * s.gemm_ops
@@ -179,13 +190,15 @@ def main():
     gen = torch.Generator(device="cuda")
     gen.manual_seed(0)
 
+    vit = args.workload == "vit-l"
+    table = synth.vit_l_layers(64) if vit else synth.resnet50_layers(64)
     layers = []
-    for spec in synth.resnet50_layers(64):
+    for spec in table:
         if args.layer and args.layer not in spec.name:
             continue
         for _ in range(spec.count):
             layers.append(LayerRun(spec, len(layers), torch, lbt, gen,
-                                   isinstance(spec, synth.LinearLayer)))
+                                   isinstance(spec, synth.LinearLayer), x_unsigned=not vit))
     for L in layers:
         L.state = lbt.new_state(gamma0=args.gamma0)
     ws = torch.zeros(max(L.ws_bytes(lbt) for L in layers), dtype=torch.uint8, device="cuda")
@@ -211,8 +224,10 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8",
         "data": "synthetic",
-        "config": {"workload": "ResNet-50 bottleneck sweep, batch 64, %d layers, INT4 W/A/G, "
-                               "%s rounding, gamma0=%g" % (len(layers), args.rounding, args.gamma0),
+        "config": {"workload": "%s, batch 64, %d layers, INT4 W/A/G, %s rounding, gamma0=%g"
+                               % ("ViT-L encoder block linear layers (197 tokens)" if vit
+                                  else "ResNet-50 bottleneck sweep", len(layers), args.rounding,
+                                  args.gamma0),
                    "gemm_GOP_per_step": gemm_ops / 1e9, "grad_elements_per_step": n_grad},
     }
 
@@ -246,7 +261,7 @@ def main():
             kernels[name] = k
         out["kernels"] = kernels
         dom = max(kernels, key=lambda n: kernels[n]["ms_per_step"])
-        traffic = measured_traffic(dom)
+        traffic = None if vit else measured_traffic(dom)     # counters were taken on the default sweep
         if "gemm" in dom:
             ach = kernels[dom]["TOPS"]
             out["roofline"] = {"kernel": dom, "bound": "mfma", "achieved": ach,

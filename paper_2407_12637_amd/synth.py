@@ -177,6 +177,20 @@ def sr_layers(batch: int = 16, patch: int = 96):
     ]
 
 
+def vit_l_layers(batch: int = 64, tokens: int = 197):
+    """Linear layers of one ViT-L/16 encoder block (width 1024, MLP 4096) at batch x tokens
+    rows; the network has 24 such blocks.  ViT-L is the transformer of the paper's
+    supplement (Table C); the attention products themselves are not linear layers and are
+    not part of the sweep."""
+    m = batch * tokens
+    return [
+        LinearLayer("vit.qkv.1024-3072", 1, m, 1024, 3072),
+        LinearLayer("vit.proj.1024-1024", 1, m, 1024, 1024),
+        LinearLayer("vit.fc1.1024-4096", 1, m, 1024, 4096),
+        LinearLayer("vit.fc2.4096-1024", 1, m, 4096, 1024),
+    ]
+
+
 def linear_case():
     return LinearLayer("linear.512-512", 1, 256, 512, 512)
 

@@ -123,3 +123,30 @@ def test_full_size_linear():
     assert np.array_equal(res.acc_dx, ref.acc_dx) and np.array_equal(res.acc_dw, ref.acc_dw)
     gu.assert_outputs_close(res.dX, ref.dX)
     gu.assert_outputs_close(res.dW, ref.dW)
+
+
+def test_full_size_vit_linear():
+    # the largest linear layer of a ViT-L encoder block (supplement, Table C) at batch 64:
+    # 12608 token rows, 1024 -> 4096; signed activations; sampled rows of dX, columns of dW
+    L = [x for x in synth.vit_l_layers(64) if x.name == "vit.fc1.1024-4096"][0]
+    r = synth.rng(0, 43, 0, 0)
+    X, W = synth.normal(r, (L.M, L.K), 1.0), synth.normal(r, (L.K, L.N), 0.02)
+    dY = synth.grad_cfg4(r, (L.M, L.N))
+    st = lbt.new_state(gamma0=0.05)
+    res = gu.backward_linear(X, W, dY, st, x_unsigned=False, seed=11, rounding=1)
+    ost = oracle.GradState(gamma=0.05)
+    qG = oracle.quantize_grad(dY, ost, 11, 1)
+    gu.assert_state_equal(lbt.lbt_state_read(st), ost)
+    qX, c_x, s_x, _ = oracle.quantize_operand(X, 0.0, False)
+    qW, c_w, s_w, _ = oracle.quantize_operand(W, 0.0, False)
+    s_g = oracle.scale(ost.clip, 4)
+    pick = np.random.default_rng(9)
+    rows = np.unique(np.concatenate([pick.integers(0, L.M, 24), [0, L.M - 1]]))
+    want_dx = oracle.linear_dx(qG[rows], qW)
+    assert np.array_equal(res.acc_dx[rows], want_dx), "dX accumulators differ"
+    gu.assert_outputs_close(res.dX[rows], oracle.dequant(want_dx, s_g, s_w))
+    cols = np.unique(np.concatenate([pick.integers(0, L.N, 24), [0, L.N - 1]]))
+    want_dw = oracle.linear_dw(qX, np.ascontiguousarray(qG[:, cols]))
+    assert np.array_equal(res.acc_dw[:, cols], want_dw), "dW accumulators differ"
+    gu.assert_outputs_close(res.dW[:, cols], oracle.dequant(want_dw, s_x, s_g))
+    assert np.abs(want_dx).max() > 0 and np.abs(want_dw).max() > 0
