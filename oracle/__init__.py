@@ -171,14 +171,22 @@ class GradState:
     scale: np.float32 = field(default_factory=lambda: np.float32(0))
 
 
-def quantize_grad(g, st: GradState, seed: int = 0, rounding: int = NEAREST):
+def quantize_grad(g, st: GradState, seed: int = 0, rounding: int = NEAREST,
+                  hindsight: bool = False):
     """Gradient quantizer of one layer: g_max, c_g = gamma*g_max, codes, N(G_out).
 
     Writes gmax, clip, scale, n_total, n_out, status into ``st``; gamma and step
     are left alone (the update is a separate call, as in Alg. 1 whose input is
     the clip-out set of the quantization just done).  Returns int32 codes.
+
+    hindsight=True is NOT the paper's quantizer (Sec. 3.1 takes the maximum of the tensor
+    being quantized): the interval comes from the maximum of the PREVIOUS tensor of this
+    layer, st.gmax, so that one sweep over the tensor suffices; this tensor's maximum is
+    recorded in st.gmax for the next call.  A separate, explicitly requested mode.
     """
     g = _f32(g)
+    if hindsight:
+        return _quantize_grad_hindsight(g, st, seed, rounding)
     gmax, status = tensor_max(g, use_abs=True)
     st.status = status
     st.n_total = int(g.size)
@@ -194,6 +202,26 @@ def quantize_grad(g, st: GradState, seed: int = 0, rounding: int = NEAREST):
     code, n_out = quantize(g, c, st.bits, False, rounding, seed, st.step)
     st.gmax, st.clip, st.n_out = gmax, c, n_out
     st.scale = np.float32(scale(c, st.bits, False))
+    return code
+
+
+def _quantize_grad_hindsight(g, st: GradState, seed: int, rounding: int):
+    gmax_now, status_now = tensor_max(g, use_abs=True)
+    st.n_total = int(g.size)
+    prev = np.float32(st.gmax)
+    if np.isfinite(prev) and prev > 0:
+        c = clip_value(st.gamma, prev)
+        code, n_out = quantize(g, c, st.bits, False, rounding, seed, st.step)
+        status = OK
+    else:                       # no usable previous maximum: everything is clipped to 0
+        c, n_out, status = np.float32(0), 0, ZERO_GRAD
+        code = np.zeros(g.shape, dtype=np.int32)
+    if status_now == NONFINITE:
+        status = NONFINITE      # and the recorded maximum stays what it was
+    else:
+        st.gmax = np.float32(gmax_now)
+    st.clip, st.n_out, st.status = np.float32(c), int(n_out), status
+    st.scale = np.float32(scale(c, st.bits, False)) if c > 0 else np.float32(0)
     return code
 
 
@@ -322,8 +350,8 @@ class BackwardResult:
     dW: np.ndarray | None
 
 
-def _operands(X, W, dY, c_x, x_unsigned, c_w, st, seed, rounding):
-    qG = quantize_grad(dY, st, seed, rounding)
+def _operands(X, W, dY, c_x, x_unsigned, c_w, st, seed, rounding, hindsight=False):
+    qG = quantize_grad(dY, st, seed, rounding, hindsight)
     if st.status == NONFINITE:
         return None
     s_g = scale(st.clip, st.bits, False)
@@ -337,9 +365,9 @@ def _operands(X, W, dY, c_x, x_unsigned, c_w, st, seed, rounding):
 
 def backward_linear(X, W, dY, st: GradState, c_x: float = 0.0, x_unsigned: bool = False,
                     c_w: float = 0.0, seed: int = 0, rounding: int = NEAREST,
-                    want_dx: bool = True, want_dw: bool = True):
+                    want_dx: bool = True, want_dw: bool = True, hindsight: bool = False):
     """X[M,K], W[K,N], dY[M,N]: dX = Q(dY).Q(W)^T, dW = Q(X)^T.Q(dY)."""
-    ops = _operands(X, W, dY, c_x, x_unsigned, c_w, st, seed, rounding)
+    ops = _operands(X, W, dY, c_x, x_unsigned, c_w, st, seed, rounding, hindsight)
     if ops is None:
         return None
     qG, qX, qW, s_g, s_x, s_w = ops
@@ -354,9 +382,10 @@ def backward_linear(X, W, dY, st: GradState, c_x: float = 0.0, x_unsigned: bool 
 
 def backward_conv2d(X, W, dY, stride: int, pad: int, st: GradState, c_x: float = 0.0,
                     x_unsigned: bool = True, c_w: float = 0.0, seed: int = 0,
-                    rounding: int = NEAREST, want_dx: bool = True, want_dw: bool = True):
+                    rounding: int = NEAREST, want_dx: bool = True, want_dw: bool = True,
+                    hindsight: bool = False):
     """X[N,C,H,W], W[K,C,R,S], dY[N,K,P,Q]: both gradients of the convolution."""
-    ops = _operands(X, W, dY, c_x, x_unsigned, c_w, st, seed, rounding)
+    ops = _operands(X, W, dY, c_x, x_unsigned, c_w, st, seed, rounding, hindsight)
     if ops is None:
         return None
     qG, qX, qW, s_g, s_x, s_w = ops

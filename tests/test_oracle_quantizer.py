@@ -290,3 +290,48 @@ def test_operand_quantizers():
                                                   * (7 / float(c2))), -7, 7))
     z, cz, sz, status = oracle.quantize_operand(np.zeros(6, np.float32), 0.0, False)
     assert status == oracle.OK and not z.any() and sz == 0.0
+
+
+# -- the hindsight-maximum variant (not the paper's quantizer; an explicit extra mode) --------
+def test_hindsight_equals_two_sweeps_when_the_maximum_repeats():
+    # fed the same tensor again, the previous maximum IS this tensor's maximum
+    r = synth.rng(0, 31, 0, 0)
+    g = synth.grad_cfg4(r, (4097,))
+    for rounding in (0, 1):
+        a = oracle.GradState(gamma=0.3, step=2)
+        want = oracle.quantize_grad(g, a, 5, rounding)
+        b = oracle.GradState(gamma=0.3, step=2)
+        oracle.quantize_grad(g, b, 5, rounding)
+        got = oracle.quantize_grad(g, b, 5, rounding, hindsight=True)
+        assert np.array_equal(got, want)
+        assert (b.clip, b.scale, b.n_out, b.gmax, b.status) == (a.clip, a.scale, a.n_out, a.gmax, a.status)
+
+
+def test_hindsight_uses_the_previous_maximum():
+    # g2 = 2 g1: the interval gamma * max|g1| is what two sweeps over g2 give at gamma / 2
+    # (scaling by 2 is exact in fp32)
+    r = synth.rng(0, 32, 0, 0)
+    g1 = synth.grad_cfg4(r, (3000,))
+    g2 = (2.0 * g1).astype(np.float32)
+    st = oracle.GradState(gamma=0.5)
+    oracle.quantize_grad(g1, st, 1, 0)
+    got = oracle.quantize_grad(g2, st, 1, 0, hindsight=True)
+    ref = oracle.GradState(gamma=0.25)
+    want = oracle.quantize_grad(g2, ref, 1, 0)
+    assert np.array_equal(got, want) and st.clip == ref.clip and st.n_out == ref.n_out
+    assert st.gmax == ref.gmax == np.abs(g2).max()       # recorded for the next call
+    assert st.n_out > 0                                    # the doubled tail is clipped out
+
+
+def test_hindsight_degenerate_cases():
+    g = np.linspace(-1, 1, 64, dtype=np.float32)
+    st = oracle.GradState(gamma=1.0)                       # no previous maximum yet
+    q = oracle.quantize_grad(g, st, 0, 0, hindsight=True)
+    assert st.status == oracle.ZERO_GRAD and not q.any() and st.clip == 0 and st.n_out == 0
+    assert st.gmax == np.float32(1.0)                      # but this maximum is recorded
+    q = oracle.quantize_grad(g, st, 0, 0, hindsight=True)
+    assert st.status == oracle.OK and q.max() == 7 and q.min() == -7
+    bad = g.copy()
+    bad[3] = np.inf
+    oracle.quantize_grad(bad, st, 0, 0, hindsight=True)
+    assert st.status == oracle.NONFINITE and st.gmax == np.float32(1.0)   # maximum kept
