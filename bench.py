@@ -44,6 +44,10 @@ def parse():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--rounding", choices=["stochastic", "nearest"], default="stochastic")
     ap.add_argument("--gamma0", type=float, default=1.0)
+    ap.add_argument("--single-sweep", action="store_true",
+                    help="extra mode, not the paper's quantizer: the gradient interval comes "
+                         "from the previous step's maximum, so dY is read once (needs "
+                         "--warmup >= 1; reported separately, never the headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
     ap.add_argument("--layer", default=None, help="run only layers whose name contains this")
@@ -187,6 +191,12 @@ def main():
         print(json.dumps({"copy_probe_bytes_each_way": n, "copies": 3}))
         return
     rounding = lbt.ROUND_STOCHASTIC if args.rounding == "stochastic" else lbt.ROUND_NEAREST
+    if args.single_sweep:
+        if args.warmup < 1:
+            print("bench.py: --single-sweep needs --warmup >= 1 (the first step has no previous "
+                  "maximum and quantizes everything to 0)", file=sys.stderr)
+            sys.exit(2)
+        rounding |= lbt.HINDSIGHT_MAX
     gen = torch.Generator(device="cuda")
     gen.manual_seed(0)
 
@@ -230,6 +240,8 @@ def main():
                                   args.gamma0),
                    "gemm_GOP_per_step": gemm_ops / 1e9, "grad_elements_per_step": n_grad},
     }
+    if args.single_sweep:
+        out["config"]["workload"] += ", single-sweep mode (interval from the previous step's maximum)"
 
     if not args.no_kernel_timing:
         # same steps again with the library's event timing on: per-kernel durations
@@ -301,7 +313,7 @@ def main():
                                    "ms_per_step": t_ms, "roofline_ms_per_step": t_roof * 1e3,
                                    "frac_of_layer_rooflines": t_roof * 1e3 / t_ms}
 
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not args.single_sweep:   # the oracle is timed on the paper's mode
         out["cpu_baseline"] = cpu_baseline(layers, rounding)
 
     print(json.dumps(out))

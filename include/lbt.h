@@ -49,6 +49,16 @@ extern "C" {
 
 #define LBT_ROUND_NEAREST 0      /* round half to even                              */
 #define LBT_ROUND_STOCHASTIC 1   /* (floor(x_n*2^16) + r16) >> 16, r16 from Philox  */
+/*
+ * May be OR-ed into `rounding`: take the interval from the maximum of the PREVIOUS gradient
+ * tensor of this layer (st->gmax as left by the last call) instead of this tensor's own, so
+ * that the tensor is swept once; this tensor's maximum is recorded in st->gmax for the next
+ * call.  NOT the quantizer of Sec. 3.1 (which uses the tensor's own maximum): a separate,
+ * explicitly requested mode.  With st->gmax == 0 (no previous call) all codes are 0 and the
+ * status is LBT_STATUS_ZERO_GRAD; a non-finite value in this tensor gives
+ * LBT_STATUS_NONFINITE, leaves st->gmax unchanged, and the codes are unspecified.
+ */
+#define LBT_HINDSIGHT_MAX 2
 
 /*
  * Per-layer state of the gradient quantizer: the scalars of Alg. 1 plus the
@@ -74,7 +84,7 @@ typedef struct lbt_grad_state {
   float gmax;        /* g_max = max|G|                                              */
   float clip;        /* c_g = (float)(gamma * (double)g_max)                        */
   float scale;       /* s = c_g / (2^(b-1) - 1), Eq. (2)                            */
-  uint32_t reserved;
+  uint32_t sync_max; /* internal: running maximum of the hindsight mode; zero between calls */
 } lbt_grad_state;
 
 const char* lbt_version(void);

@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_HERE, "liblbt.so")
 
 OK = 0
 ROUND_NEAREST, ROUND_STOCHASTIC = 0, 1
+HINDSIGHT_MAX = 2  # may be OR-ed into `rounding`: interval from the previous tensor's maximum
 STATUS_OK, STATUS_NONFINITE, STATUS_ZERO_GRAD = 0, 1, 2
 
 
@@ -35,7 +36,7 @@ class GradState(C.Structure):
         ("step", C.c_uint64), ("n_total", C.c_uint64), ("n_out", C.c_uint64),
         ("sync_word", C.c_uint64),
         ("gmax", C.c_float), ("clip", C.c_float), ("scale", C.c_float),
-        ("reserved", C.c_uint32),
+        ("sync_max", C.c_uint32),
     ]
 
 

@@ -60,7 +60,9 @@ int backward_common(const float* X, const float* W, const float* dY, const ConvG
   if (!W || !dY || !st || !ws) return LBT_ERR_NULL;
   if (dW && !X) return LBT_ERR_NULL;
   if ((acc_dX && !dX) || (acc_dW && !dW)) return LBT_ERR_NULL;
-  if (rounding != LBT_ROUND_NEAREST && rounding != LBT_ROUND_STOCHASTIC) return LBT_ERR_UNSUPPORTED;
+  if (rounding & ~(LBT_ROUND_STOCHASTIC | LBT_HINDSIGHT_MAX)) return LBT_ERR_UNSUPPORTED;
+  const int hindsight = (rounding & LBT_HINDSIGHT_MAX) ? 1 : 0;
+  rounding &= LBT_ROUND_STOCHASTIC;
   if (!aligned(dY, 16) || !aligned(W, 16) || (X && !aligned(X, 16)) || !aligned(ws, 256) ||
       (dX && !aligned(dX, 16)) || (dW && !aligned(dW, 16)) || !aligned(st, 8))
     return LBT_ERR_ALIGN;
@@ -84,8 +86,9 @@ int backward_common(const float* X, const float* W, const float* dY, const ConvG
   const bool want_cw = dX && !(c_w > 0.0f), want_cx = dW && !(c_x > 0.0f);
   // Tensor shapes as the re-layout sees them: T[A][B][L], L contiguous
   const int64_t wA = w_is_ck ? g.C : g.K, wB = w_is_ck ? g.K : g.C, wL = w_is_ck ? 1 : RS;
-  // 1. maxima of dY, and of X / W where no clip value was given, in one launch
-  if ((rc = launch_absmax3(dY, n_dy, 1, want_cx ? X : nullptr, n_x, x_unsigned ? 0 : 1,
+  // 1. maxima of dY (unless the previous tensor's maximum is to be used), and of X / W where
+  //    no clip value was given, in one launch
+  if ((rc = launch_absmax3(hindsight ? nullptr : dY, n_dy, 1, want_cx ? X : nullptr, n_x, x_unsigned ? 0 : 1,
                            want_cw ? W : nullptr, n_w, 1, pmax, &nblocks, st, s)))
     return rc;
   // 2. codes of all three tensors in the layouts the two products read, one launch:
@@ -95,6 +98,7 @@ int backward_common(const float* X, const float* W, const float* dY, const ConvG
     LayerTensors q{};
     q.seed = seed;
     q.rounding = rounding;
+    q.hindsight = hindsight;
     q.x_unsigned = x_unsigned;
     q.tensor[0] = {dY, g.N, g.K, PQ,
                    RelayoutIo{pmax, nblocks, 0, st, dX ? g_npqk : nullptr, dW ? g_kpqn : nullptr, 0},
@@ -173,6 +177,7 @@ int lbt_state_write(lbt_grad_state* st, const lbt_grad_state* host_in, void* str
   if (host_in->bits != 4) return LBT_ERR_UNSUPPORTED;
   lbt_grad_state v = *host_in;
   v.sync_word = 0;
+  v.sync_max = 0;
   return launch_state_init(st, v, reinterpret_cast<hipStream_t>(stream));
 }
 
@@ -190,7 +195,9 @@ int lbt_quantize_grad(const float* g, int64_t n, lbt_grad_state* st, uint64_t se
                       uint8_t* codes, void* ws, size_t ws_bytes, void* stream) {
   if (!g || !st || !codes || !ws) return LBT_ERR_NULL;
   if (n <= 0) return LBT_ERR_SHAPE;
-  if (rounding != LBT_ROUND_NEAREST && rounding != LBT_ROUND_STOCHASTIC) return LBT_ERR_UNSUPPORTED;
+  if (rounding & ~(LBT_ROUND_STOCHASTIC | LBT_HINDSIGHT_MAX)) return LBT_ERR_UNSUPPORTED;
+  const int hindsight = (rounding & LBT_HINDSIGHT_MAX) ? 1 : 0;
+  rounding &= LBT_ROUND_STOCHASTIC;
   if (!aligned(g, 16) || !aligned(codes, 4) || !aligned(st, 8) || !aligned(ws, 256))
     return LBT_ERR_ALIGN;
   if (ws_bytes < lbt_workspace_bytes_quantize(n)) return LBT_ERR_WORKSPACE;
@@ -198,8 +205,10 @@ int lbt_quantize_grad(const float* g, int64_t n, lbt_grad_state* st, uint64_t se
   uint32_t* pmax =
       reinterpret_cast<uint32_t*>(static_cast<uint8_t*>(ws) + kWsScalarsBytes);
   int rc, nblocks = 0;
-  if ((rc = launch_absmax3(g, n, 1, nullptr, 0, 0, nullptr, 0, 0, pmax, &nblocks, st, s))) return rc;
-  return launch_quantize_flat_grad(g, n, pmax, nblocks, st, seed, rounding, codes, s);
+  if ((rc = launch_absmax3(hindsight ? nullptr : g, n, 1, nullptr, 0, 0, nullptr, 0, 0, pmax,
+                           &nblocks, st, s)))
+    return rc;
+  return launch_quantize_flat_grad(g, n, pmax, nblocks, st, seed, rounding, hindsight, codes, s);
 }
 
 int lbt_quantize_operand(const float* x, int64_t n, float c, int is_unsigned, int bits,

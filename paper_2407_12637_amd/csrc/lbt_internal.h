@@ -61,20 +61,22 @@ constexpr int kMaxPartialBlocks = 2048;  // partial-maximum slots in the workspa
 // Workspace header: OperandScalars (256 bytes), then pmax[kMaxPartialBlocks][4] uint32.
 constexpr size_t kWsScalarsBytes = 256;
 // Inside the scalars: 16 arrival counters (8 bytes each) of the gradient quantizer's
-// two-level ticket, zeroed by every launch of the maximum kernel.
+// two-level ticket, then 16 running maxima (4 bytes each) of its hindsight mode; all zeroed
+// by every launch of the maximum kernel.
 constexpr size_t kWsTicketOffset = 64;
 constexpr int kTicketSlots = 16;
 constexpr size_t kWsHeaderBytes = kWsScalarsBytes + (size_t)kMaxPartialBlocks * 16;
 
 // One launch for the maxima of up to three tensors (null pointer = absent); partial
 // maxima go to pmax[block][tensor].  *nblocks_out = number of partial rows written.
-// st (may be null): its status is reset to OK for the quantizer launches that follow.
+// st (may be null): its status is reset to OK for the quantizer launches that follow; with a
+// state the kernel is launched even when every tensor is absent.
 int launch_absmax3(const float* p0, int64_t n0, int abs0, const float* p1, int64_t n1, int abs1,
                    const float* p2, int64_t n2, int abs2, uint32_t* pmax, int* nblocks_out,
                    lbt_grad_state* st, hipStream_t s);
 int launch_quantize_flat_grad(const float* g, int64_t n, const uint32_t* pmax, int nblocks,
-                              lbt_grad_state* st, uint64_t seed, int rounding, uint8_t* codes,
-                              hipStream_t s);
+                              lbt_grad_state* st, uint64_t seed, int rounding, int hindsight,
+                              uint8_t* codes, hipStream_t s);
 int launch_quantize_flat_operand(const float* x, int64_t n, float c_given, const uint32_t* pmax,
                                  int nblocks, int is_unsigned, uint8_t* codes, float* c_out,
                                  float* clip_scale_out, hipStream_t s);
@@ -105,6 +107,7 @@ struct LayerTensors {
   } tensor[3];
   uint64_t seed;
   int rounding;
+  int hindsight;  // gradient interval from the maximum left in *st by the previous call
   int x_unsigned;
 };
 int launch_quantize_layer(const LayerTensors& q, hipStream_t s);

@@ -167,12 +167,22 @@ __device__ __forceinline__ uint32_t reduce_partials(const uint32_t* pmax, int nb
 struct GradSetup {
   float gmax, c;
   int status;
+  bool hindsight;
 };
 
+// hindsight: the interval comes from the maximum the previous call left in the state; this
+// tensor's own maximum is gathered during the sweep (grad_finish).
 __device__ __forceinline__ GradSetup grad_setup(const lbt_grad_state* st, const uint32_t* pmax,
-                                                int nblocks) {
+                                                int nblocks, bool hindsight = false) {
   GradSetup g;
-  const uint32_t bits = reduce_partials(pmax, nblocks, 0);
+  g.hindsight = hindsight;
+  uint32_t bits;
+  if (hindsight) {
+    bits = __float_as_uint(st->gmax) & 0x7fffffffu;
+    if (bits >= kInfBits) bits = 0;      // unusable: treated like "no previous maximum"
+  } else {
+    bits = reduce_partials(pmax, nblocks, 0);
+  }
   g.gmax = __uint_as_float(bits);
   g.c = 0.0f;
   if (bits >= kInfBits) g.status = LBT_STATUS_NONFINITE;
@@ -199,26 +209,52 @@ __device__ __forceinline__ unsigned long long* ticket_slots(const uint32_t* pmax
 // zeroed by k_absmax3, which runs before every gradient quantizer.
 __device__ __forceinline__ void grad_finish(lbt_grad_state* st, const GradSetup& g, uint32_t cnt,
                                             unsigned long long n_total, unsigned nblk, unsigned id,
-                                            unsigned long long* slots) {
+                                            unsigned long long* slots, uint32_t my_max = 0) {
   const uint32_t tot = block_sum(cnt);
+  uint32_t blk_max = 0;
+  if (g.hindsight) blk_max = block_max(my_max);
   if (threadIdx.x == 0) {
     const unsigned slot = id % kTicketSlots;
     const unsigned in_slot = (nblk - slot + kTicketSlots - 1) / kTicketSlots;
-    const unsigned long long old = atomicAdd(&slots[slot], kTicket + tot);
+    uint32_t* const max_slots = reinterpret_cast<uint32_t*>(slots + kTicketSlots);
+    unsigned long long carry = 0;
+    if (g.hindsight) {
+      // the maximum must be in its counter before the ticket that announces it: the ticket
+      // is made to depend on the value the first atomic returns
+      uint32_t seen = atomicMax(&max_slots[slot], blk_max), copy = seen;
+      asm volatile("" : "+v"(copy));
+      carry = seen ^ copy;
+    }
+    const unsigned long long old = atomicAdd(&slots[slot], kTicket + tot + carry);
     if ((old >> 40) != in_slot - 1) return;
     const unsigned long long sub = (old + tot) & kCountMask;
     const unsigned n_slots = nblk < (unsigned)kTicketSlots ? nblk : (unsigned)kTicketSlots;
+    carry = 0;
+    if (g.hindsight) {
+      const uint32_t slot_max = atomicMax(&max_slots[slot], 0u);   // every member has reported
+      uint32_t seen = atomicMax(&st->sync_max, slot_max), copy = seen;
+      asm volatile("" : "+v"(copy));
+      carry = seen ^ copy;
+    }
     const unsigned long long old2 =
-        atomicAdd(reinterpret_cast<unsigned long long*>(&st->sync_word), kTicket + sub);
+        atomicAdd(reinterpret_cast<unsigned long long*>(&st->sync_word), kTicket + sub + carry);
     if ((old2 >> 40) == n_slots - 1) {
+      int status = g.status;
       st->n_out = (old2 + sub) & kCountMask;
       st->n_total = n_total;
-      st->gmax = g.gmax;
+      if (g.hindsight) {
+        const uint32_t now = atomicMax(&st->sync_max, 0u);
+        if (now >= kInfBits) status = LBT_STATUS_NONFINITE;   // and the recorded maximum stays
+        else st->gmax = __uint_as_float(now);
+        st->sync_max = 0;
+      } else {
+        st->gmax = g.gmax;
+      }
       st->clip = g.c;
       st->scale = (g.c > 0.0f) ? (float)((double)g.c / 7.0) : 0.0f;
       // k_absmax3 has reset the status to OK; an operand quantizer of the same launch
       // may already have flagged a non-finite operand, which must stay
-      if (g.status != LBT_STATUS_OK) atomicCAS(&st->status, LBT_STATUS_OK, g.status);
+      if (status != LBT_STATUS_OK) atomicCAS(&st->status, LBT_STATUS_OK, status);
       st->sync_word = 0;
     }
   }
@@ -298,7 +334,11 @@ __global__ __launch_bounds__(kThreads) void k_absmax3(MaxSeg s0, MaxSeg s1, MaxS
   // every quantizer launch that follows reports into a fresh status and fresh counters
   if (blk == 0) {
     if (st && threadIdx.x == 0) st->status = LBT_STATUS_OK;
-    if (threadIdx.x < kTicketSlots) ticket_slots(pmax)[threadIdx.x] = 0ull;
+    if (threadIdx.x < kTicketSlots) {
+      unsigned long long* slots = ticket_slots(pmax);
+      slots[threadIdx.x] = 0ull;
+      reinterpret_cast<uint32_t*>(slots + kTicketSlots)[threadIdx.x] = 0u;
+    }
   }
   int t = 0;
   MaxSeg s = s0;
@@ -324,6 +364,14 @@ __global__ __launch_bounds__(kThreads) void k_absmax3(MaxSeg s0, MaxSeg s1, MaxS
   if (threadIdx.x < 4) pmax[blk * 4 + threadIdx.x] = ((int)threadIdx.x == t) ? m : 0u;
 }
 
+// Largest |v| of eight values as an fp32 bit pattern (NaN/Inf sort on top).
+__device__ __forceinline__ uint32_t max_abs_bits8(const float v[8]) {
+  uint32_t m = 0;
+#pragma unroll
+  for (int u = 0; u < 8; ++u) m = max(m, __float_as_uint(v[u]) & 0x7fffffffu);
+  return m;
+}
+
 // ---------------------------------------------------------------------------
 // flat quantizer (C-ABI code format): 8 consecutive elements per thread -> one
 // 32-bit word of codes
@@ -332,12 +380,12 @@ template <int MODE>
 __global__ __launch_bounds__(kThreads) void k_quantize_flat(
     const float* __restrict__ x, long long n, float c_given, const uint32_t* pmax, int nblocks,
     lbt_grad_state* st, unsigned long long seed, uint8_t* __restrict__ codes, float* c_out,
-    float* clip_scale_out) {
+    float* clip_scale_out, int hindsight) {
   constexpr bool kGrad = (MODE >= 2);
   GradSetup gs{};
   float c;
   if (kGrad) {
-    gs = grad_setup(st, pmax, nblocks);
+    gs = grad_setup(st, pmax, nblocks, hindsight != 0);
     c = gs.c;
   } else {
     c = operand_setup(c_given, pmax, nblocks, 1, MODE == 1, c_out, nullptr, nullptr, clip_scale_out,
@@ -348,7 +396,7 @@ __global__ __launch_bounds__(kThreads) void k_quantize_flat(
   const unsigned long long step = (MODE == 3) ? st->step : 0ull;
   const long long groups = (n + 7) / 8;
   const long long stride = (long long)gridDim.x * kThreads;
-  uint32_t cnt = 0;
+  uint32_t cnt = 0, seen_max = 0;
   for (long long gi = (long long)blockIdx.x * kThreads + threadIdx.x; gi < groups; gi += stride) {
     const long long e0 = gi * 8;
     const int valid = (int)min(8ll, n - e0);
@@ -362,6 +410,7 @@ __global__ __launch_bounds__(kThreads) void k_quantize_flat(
 #pragma unroll
       for (int j = 0; j < 8; ++j) v[j] = (j < valid) ? x[e0 + j] : 0.0f;
     }
+    if (kGrad && gs.hindsight) seen_max = max(seen_max, max_abs_bits8(v));
     uint32_t word = 0;
     if (live) {
       Philox4 rnd{};
@@ -382,7 +431,8 @@ __global__ __launch_bounds__(kThreads) void k_quantize_flat(
       for (int j = 0; j < nbytes; ++j) codes[gi * 4 + j] = (uint8_t)(word >> (8 * j));
     }
   }
-  if (kGrad) grad_finish(st, gs, cnt, (unsigned long long)n, gridDim.x, blockIdx.x, ticket_slots(pmax));
+  if (kGrad) grad_finish(st, gs, cnt, (unsigned long long)n, gridDim.x, blockIdx.x, ticket_slots(pmax),
+                         seen_max);
 }
 
 // ---------------------------------------------------------------------------
@@ -412,6 +462,7 @@ struct TileArgs {
   uint4* out_b;
   uint4* out_a;
   int a_lmajor;
+  int hindsight;  // gradient only: interval from the previous call's maximum
 };
 
 // Phase B: gather granules out of the LDS tile.  `pitch` = bytes per (a,b) row.  A granule
@@ -588,7 +639,7 @@ __device__ __forceinline__ void stream_body(const TileArgs& t, int pitch, int tl
   GradSetup gs{};
   float c;
   if (kGrad) {
-    gs = grad_setup(t.st, t.pmax, t.nblocks);
+    gs = grad_setup(t.st, t.pmax, t.nblocks, t.hindsight != 0);
     c = gs.c;
   } else if (!(t.c_given > 0.0f) && t.c_ptr) {
     c = *t.c_ptr;
@@ -601,7 +652,7 @@ __device__ __forceinline__ void stream_body(const TileArgs& t, int pitch, int tl
   const unsigned long long step = (MODE == 3) ? t.st->step : 0ull;
   const int l0 = bc.x * tl, b0 = bc.y * 16, a0 = bc.z * 16;
 
-  uint32_t cnt = 0;
+  uint32_t cnt = 0, seen_max = 0;
   auto quantize_item = [&](const ItemPos& p, const float v[8]) __attribute__((always_inline)) {
     // eight codes of one generator block -> LDS bytes
     Philox4 rnd{};
@@ -648,6 +699,11 @@ __device__ __forceinline__ void stream_body(const TileArgs& t, int pitch, int tl
     }
     // keep the eight loads together ahead of the arithmetic that consumes them
     __builtin_amdgcn_sched_barrier(0);
+    if (kGrad && gs.hindsight) {
+      // a load outside the tile has fetched the tensor's first elements: harmless for a maximum
+#pragma unroll
+      for (int i = 0; i < 4; ++i) seen_max = max(seen_max, max_abs_bits8(v[i]));
+    }
 #pragma unroll
     for (int i = 0; i < 4; ++i) quantize_item(p[i], v[i]);
   }
@@ -655,7 +711,7 @@ __device__ __forceinline__ void stream_body(const TileArgs& t, int pitch, int tl
   if (SMALL) store_granules(t, dyn_tile, pitch, t.L, a0, b0, 0);
   else store_granules_w4(t, dyn_tile, pitch, min(tl, t.L - l0), a0, b0, l0);
   if (kGrad) grad_finish(t.st, gs, cnt, (unsigned long long)t.A * t.B * t.L, bc.n_blocks, bc.id,
-                         ticket_slots(t.pmax));
+                         ticket_slots(t.pmax), seen_max);
 }
 
 // ---------------------------------------------------------------------------
@@ -668,7 +724,7 @@ __device__ __forceinline__ void generic_body(const TileArgs& t, const TileCoord&
   GradSetup gs{};
   float c;
   if (MODE >= 2) {
-    gs = grad_setup(t.st, t.pmax, t.nblocks);
+    gs = grad_setup(t.st, t.pmax, t.nblocks, t.hindsight != 0);
     c = gs.c;
   } else if (!(t.c_given > 0.0f) && t.c_ptr) {
     c = *t.c_ptr;
@@ -680,23 +736,28 @@ __device__ __forceinline__ void generic_body(const TileArgs& t, const TileCoord&
   const bool live = c > 0.0f;
   const unsigned long long step = (MODE == 3) ? t.st->step : 0ull;
   const int l0 = bc.x * TL, b0 = bc.y * 16, a0 = bc.z * 16;
-  uint32_t cnt = 0;
+  uint32_t cnt = 0, seen_max = 0;
+  const bool scan = live || (MODE >= 2 && gs.hindsight);
   for (int idx = threadIdx.x; idx < 256 * TL; idx += kThreads) {
     const int l = idx % TL, row = idx / TL;
     const int ga = a0 + (row >> 4), gb = b0 + (row & 15), gl = l0 + l;
     int k = 0;
-    if (live && ga < t.A && gb < t.B && gl < t.L) {
+    if (scan && ga < t.A && gb < t.B && gl < t.L) {
       const long long e = ((long long)ga * t.B + gb) * t.L + gl;
-      Philox4 rnd{};
-      if (MODE == 3) rnd = philox_block((unsigned long long)e >> 3, step, t.seed);
-      k = quantize_one<MODE>(t.x[e], qc, rnd, (uint32_t)e & 7u, cnt);
+      const float v = t.x[e];
+      seen_max = max(seen_max, __float_as_uint(v) & 0x7fffffffu);
+      if (live) {
+        Philox4 rnd{};
+        if (MODE == 3) rnd = philox_block((unsigned long long)e >> 3, step, t.seed);
+        k = quantize_one<MODE>(v, qc, rnd, (uint32_t)e & 7u, cnt);
+      }
     }
     tile[row * PITCH + l] = (uint8_t)k;
   }
   __syncthreads();
   store_granules(t, tile, PITCH, TL, a0, b0, l0);
   if (MODE >= 2) grad_finish(t.st, gs, cnt, (unsigned long long)t.A * t.B * t.L, bc.n_blocks, bc.id,
-                             ticket_slots(t.pmax));
+                             ticket_slots(t.pmax), seen_max);
 }
 
 // ---------------------------------------------------------------------------
@@ -713,7 +774,7 @@ __device__ __forceinline__ void matrix_body(const TileArgs& t, const TileCoord& 
   GradSetup gs{};
   float c;
   if (MODE >= 2) {
-    gs = grad_setup(t.st, t.pmax, t.nblocks);
+    gs = grad_setup(t.st, t.pmax, t.nblocks, t.hindsight != 0);
     c = gs.c;
   } else if (!(t.c_given > 0.0f) && t.c_ptr) {
     c = *t.c_ptr;
@@ -725,7 +786,7 @@ __device__ __forceinline__ void matrix_body(const TileArgs& t, const TileCoord& 
   const bool live = c > 0.0f;
   const unsigned long long step = (MODE == 3) ? t.st->step : 0ull;
   const int b0 = bc.x * 64, a0 = bc.z * 64;
-  uint32_t cnt = 0;
+  uint32_t cnt = 0, seen_max = 0;
   float v[2][8];
   bool ok[2];
   long long e0[2];
@@ -740,6 +801,8 @@ __device__ __forceinline__ void matrix_body(const TileArgs& t, const TileCoord& 
     v[i][0] = lo.x; v[i][1] = lo.y; v[i][2] = lo.z; v[i][3] = lo.w;
     v[i][4] = hi.x; v[i][5] = hi.y; v[i][6] = hi.z; v[i][7] = hi.w;
   }
+  // (a run outside the matrix has fetched the tensor's first elements: harmless for a maximum)
+  if (MODE >= 2 && gs.hindsight) seen_max = max(max_abs_bits8(v[0]), max_abs_bits8(v[1]));
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
     const int it = threadIdx.x + kThreads * i;
@@ -769,7 +832,7 @@ __device__ __forceinline__ void matrix_body(const TileArgs& t, const TileCoord& 
       if (b0 + 4 * r + i < t.B) t.out_a[(long long)(b0 + 4 * r + i) * t.AG + (a0 >> 4) + gl] = g4[i];
   }
   if (MODE >= 2) grad_finish(t.st, gs, cnt, (unsigned long long)t.A * t.B * t.L, bc.n_blocks, bc.id,
-                             ticket_slots(t.pmax));
+                             ticket_slots(t.pmax), seen_max);
 }
 
 // ---------------------------------------------------------------------------
@@ -913,9 +976,10 @@ int launch_absmax3(const float* p0, int64_t n0, int abs0, const float* p1, int64
   per = (per + 8191) / 8192 * 8192;  // 256 threads x 8 float4
   if (per < 8192) per = 8192;
   const long long nb0 = (n0 + per - 1) / per, nb1 = (n1 + per - 1) / per, nb2 = (n2 + per - 1) / per;
-  const long long nb = nb0 + nb1 + nb2;
+  long long nb = nb0 + nb1 + nb2;
+  if (nb == 0 && !st) { *nblocks_out = 0; return LBT_OK; }
+  if (nb == 0) nb = 1;  // the state and the counters are still reset; the one partial row is zero
   *nblocks_out = (int)nb;
-  if (nb == 0) return LBT_OK;
   if (nb > kMaxPartialBlocks) return LBT_ERR_UNSUPPORTED;
   MaxSeg s0{p0, n0, abs0, 0}, s1{p1, n1, abs1, (int)nb0}, s2{p2, n2, abs2, (int)(nb0 + nb1)};
   LBT_LAUNCH(k_absmax3, dim3((unsigned)nb), dim3(kThreads), 0, s, s0, s1, s2, per, pmax, st);
@@ -924,18 +988,18 @@ int launch_absmax3(const float* p0, int64_t n0, int abs0, const float* p1, int64
 }
 
 int launch_quantize_flat_grad(const float* g, int64_t n, const uint32_t* pmax, int nblocks,
-                              lbt_grad_state* st, uint64_t seed, int rounding, uint8_t* codes,
-                              hipStream_t s) {
+                              lbt_grad_state* st, uint64_t seed, int rounding, int hindsight,
+                              uint8_t* codes, hipStream_t s) {
   ProfScope prof(KID_FLAT_GRAD, (double)n, s);
   const int grid = flat_grid((n + 7) / 8);
   if (rounding == LBT_ROUND_STOCHASTIC)
     LBT_LAUNCH(k_quantize_flat<3>, dim3(grid), dim3(kThreads), 0, s, g, (long long)n, 0.0f,
                        pmax, nblocks, st, (unsigned long long)seed, codes, (float*)nullptr,
-                       (float*)nullptr);
+                       (float*)nullptr, hindsight);
   else
     LBT_LAUNCH(k_quantize_flat<2>, dim3(grid), dim3(kThreads), 0, s, g, (long long)n, 0.0f,
                        pmax, nblocks, st, (unsigned long long)seed, codes, (float*)nullptr,
-                       (float*)nullptr);
+                       (float*)nullptr, hindsight);
   LBT_LAUNCH_CHECK();
   return LBT_OK;
 }
@@ -948,11 +1012,11 @@ int launch_quantize_flat_operand(const float* x, int64_t n, float c_given, const
   if (is_unsigned)
     LBT_LAUNCH(k_quantize_flat<1>, dim3(grid), dim3(kThreads), 0, s, x, (long long)n,
                        c_given, pmax, nblocks, (lbt_grad_state*)nullptr, 0ull, codes, c_out,
-                       clip_scale_out);
+                       clip_scale_out, 0);
   else
     LBT_LAUNCH(k_quantize_flat<0>, dim3(grid), dim3(kThreads), 0, s, x, (long long)n,
                        c_given, pmax, nblocks, (lbt_grad_state*)nullptr, 0ull, codes, c_out,
-                       clip_scale_out);
+                       clip_scale_out, 0);
   LBT_LAUNCH_CHECK();
   return LBT_OK;
 }
@@ -981,6 +1045,7 @@ int launch_quantize_layer(const LayerTensors& q, hipStream_t s) {
     if (!o.x) continue;
     fill_tile_args(sg.t, o.x, o.A, o.B, o.L, o.io);
     sg.t.seed = q.seed;
+    sg.t.hindsight = (i == 0) ? q.hindsight : 0;
     sg.t.c_given = o.c_given;
     sg.t.c_out = o.c_out;
     sg.t.bad_out = o.bad_out;
