@@ -44,6 +44,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--rounding", choices=["stochastic", "nearest"], default="stochastic")
     ap.add_argument("--gamma0", type=float, default=1.0)
+    ap.add_argument("--separate-update", action="store_true",
+                    help="apply the interval update with lbt_update_interval after every layer "
+                         "instead of inside the backward call (LBT_FUSED_UPDATE)")
     ap.add_argument("--single-sweep", action="store_true",
                     help="extra mode, not the paper's quantizer: the gradient interval comes "
                          "from the previous step's maximum, so dY is read once (needs "
@@ -95,6 +98,8 @@ class LayerRun:
         return lbt.lbt_workspace_bytes_conv2d(s.N, s.C, s.H, s.W, s.K, s.R, s.S, s.stride, s.pad)
 
     def run(self, lbt, ws, rounding):
+        """One layer's backward and its interval update (inside the call when `rounding`
+        carries LBT_FUSED_UPDATE, else as a call of its own)."""
         s = self.spec
         if self.is_linear:
             lbt.lbt_backward_linear(self.X, self.W, self.dY, s.M, s.K, s.N, 0.0, self.x_unsigned,
@@ -103,7 +108,8 @@ class LayerRun:
             lbt.lbt_backward_conv2d(self.X, self.W, self.dY, s.N, s.C, s.H, s.W, s.K, s.R, s.S,
                                     s.stride, s.pad, 0.0, self.x_unsigned, 0.0, self.state,
                                     self.seed, rounding, self.dX, self.dW, ws)
-        lbt.lbt_update_interval(self.state)
+        if not rounding & lbt.FUSED_UPDATE:
+            lbt.lbt_update_interval(self.state)
 
 
 def cpu_baseline(layers, rounding):
@@ -191,6 +197,8 @@ def main():
         print(json.dumps({"copy_probe_bytes_each_way": n, "copies": 3}))
         return
     rounding = lbt.ROUND_STOCHASTIC if args.rounding == "stochastic" else lbt.ROUND_NEAREST
+    if not args.separate_update:
+        rounding |= lbt.FUSED_UPDATE
     if args.single_sweep:
         if args.warmup < 1:
             print("bench.py: --single-sweep needs --warmup >= 1 (the first step has no previous "
@@ -252,8 +260,14 @@ def main():
         torch.cuda.synchronize()
         out["ms_per_step_with_kernel_timing"] = (time.perf_counter() - t0) / args.steps * 1e3
         prof = lbt.lbt_profile_read()
+        # marker overhead: brackets around the one-thread update kernel on a spare state
+        # (after the steps; with the update inside the backward calls the steps have none)
+        spare = lbt.new_state()
+        for _ in range(64):
+            lbt.lbt_update_interval(spare)
+        torch.cuda.synchronize()
+        cal = lbt.lbt_profile_read()["k_update_interval"]
         lbt.lbt_profile_enable(False)
-        cal = prof["k_update_interval"]
         overhead_us = max(cal[1] / cal[0] * 1e3 - UPDATE_KERNEL_US, 0.0)
         out["event_bracket_overhead_us"] = overhead_us
         kernels = {}
@@ -314,7 +328,7 @@ def main():
                                    "frac_of_layer_rooflines": t_roof * 1e3 / t_ms}
 
     if not args.no_cpu_baseline and not args.single_sweep:   # the oracle is timed on the paper's mode
-        out["cpu_baseline"] = cpu_baseline(layers, rounding)
+        out["cpu_baseline"] = cpu_baseline(layers, rounding & lbt.ROUND_STOCHASTIC)
 
     print(json.dumps(out))
 

@@ -59,6 +59,13 @@ extern "C" {
  * LBT_STATUS_NONFINITE, leaves st->gmax unchanged, and the codes are unspecified.
  */
 #define LBT_HINDSIGHT_MAX 2
+/*
+ * May be OR-ed into `rounding`: the call itself applies the interval update (Alg. 1) to *st
+ * once its quantizers have finished, exactly as lbt_update_interval(st) right after the call
+ * would (same arithmetic, same conditions: only when the status is LBT_STATUS_OK); saves that
+ * call's kernel launch.  Do not call lbt_update_interval for the same tensor again.
+ */
+#define LBT_FUSED_UPDATE 4
 
 /*
  * Per-layer state of the gradient quantizer: the scalars of Alg. 1 plus the

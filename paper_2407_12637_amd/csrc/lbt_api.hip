@@ -60,8 +60,10 @@ int backward_common(const float* X, const float* W, const float* dY, const ConvG
   if (!W || !dY || !st || !ws) return LBT_ERR_NULL;
   if (dW && !X) return LBT_ERR_NULL;
   if ((acc_dX && !dX) || (acc_dW && !dW)) return LBT_ERR_NULL;
-  if (rounding & ~(LBT_ROUND_STOCHASTIC | LBT_HINDSIGHT_MAX)) return LBT_ERR_UNSUPPORTED;
+  if (rounding & ~(LBT_ROUND_STOCHASTIC | LBT_HINDSIGHT_MAX | LBT_FUSED_UPDATE))
+    return LBT_ERR_UNSUPPORTED;
   const int hindsight = (rounding & LBT_HINDSIGHT_MAX) ? 1 : 0;
+  const int fused_update = (rounding & LBT_FUSED_UPDATE) ? 1 : 0;
   rounding &= LBT_ROUND_STOCHASTIC;
   if (!aligned(dY, 16) || !aligned(W, 16) || (X && !aligned(X, 16)) || !aligned(ws, 256) ||
       (dX && !aligned(dX, 16)) || (dW && !aligned(dW, 16)) || !aligned(st, 8))
@@ -113,17 +115,21 @@ int backward_common(const float* X, const float* W, const float* dY, const ConvG
                      c_w, &sc->c_w, &sc->bad_w};
     if ((rc = launch_quantize_layer(q, s))) return rc;
   }
-  // 3. the two products
+  // 3. the two products; with LBT_FUSED_UPDATE the last launch also applies Alg. 1 (the
+  //    quantizers, all of which can change the status, have finished by then)
+  lbt_grad_state* const upd = fused_update ? st : nullptr;
   if (dX) {
-    rc = w_is_ck ? launch_linear_dx(g, w_crsk, g_npqk, st, sc, dX, acc_dX, s)
-                 : launch_conv_dx(g, w_crsk, g_npqk, st, sc, dX, acc_dX, s);
+    lbt_grad_state* const u = dW ? nullptr : upd;
+    rc = w_is_ck ? launch_linear_dx(g, w_crsk, g_npqk, st, sc, dX, acc_dX, u, s)
+                 : launch_conv_dx(g, w_crsk, g_npqk, st, sc, dX, acc_dX, u, s);
     if (rc) return rc;
   }
   if (dW) {
-    rc = w_is_ck ? launch_linear_dw(g, g_kpqn, x_chwn, st, sc, x_unsigned, dW, acc_dW, partial, s)
-                 : launch_conv_dw(g, g_kpqn, x_chwn, st, sc, x_unsigned, dW, acc_dW, partial, s);
+    rc = w_is_ck ? launch_linear_dw(g, g_kpqn, x_chwn, st, sc, x_unsigned, dW, acc_dW, partial, upd, s)
+                 : launch_conv_dw(g, g_kpqn, x_chwn, st, sc, x_unsigned, dW, acc_dW, partial, upd, s);
     if (rc) return rc;
   }
+  if (upd && !dX && !dW && (rc = launch_update_interval(st, s))) return rc;
   return LBT_OK;
 }
 
@@ -195,8 +201,10 @@ int lbt_quantize_grad(const float* g, int64_t n, lbt_grad_state* st, uint64_t se
                       uint8_t* codes, void* ws, size_t ws_bytes, void* stream) {
   if (!g || !st || !codes || !ws) return LBT_ERR_NULL;
   if (n <= 0) return LBT_ERR_SHAPE;
-  if (rounding & ~(LBT_ROUND_STOCHASTIC | LBT_HINDSIGHT_MAX)) return LBT_ERR_UNSUPPORTED;
+  if (rounding & ~(LBT_ROUND_STOCHASTIC | LBT_HINDSIGHT_MAX | LBT_FUSED_UPDATE))
+    return LBT_ERR_UNSUPPORTED;
   const int hindsight = (rounding & LBT_HINDSIGHT_MAX) ? 1 : 0;
+  const int fused_update = (rounding & LBT_FUSED_UPDATE) ? 1 : 0;
   rounding &= LBT_ROUND_STOCHASTIC;
   if (!aligned(g, 16) || !aligned(codes, 4) || !aligned(st, 8) || !aligned(ws, 256))
     return LBT_ERR_ALIGN;
@@ -208,7 +216,8 @@ int lbt_quantize_grad(const float* g, int64_t n, lbt_grad_state* st, uint64_t se
   if ((rc = launch_absmax3(hindsight ? nullptr : g, n, 1, nullptr, 0, 0, nullptr, 0, 0, pmax,
                            &nblocks, st, s)))
     return rc;
-  return launch_quantize_flat_grad(g, n, pmax, nblocks, st, seed, rounding, hindsight, codes, s);
+  return launch_quantize_flat_grad(g, n, pmax, nblocks, st, seed, rounding, hindsight, fused_update,
+                                   codes, s);
 }
 
 int lbt_quantize_operand(const float* x, int64_t n, float c, int is_unsigned, int bits,

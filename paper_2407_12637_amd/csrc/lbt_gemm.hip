@@ -36,6 +36,8 @@
 // kernel sums the partials and applies the scale (no atomics: the result does not
 // depend on data sparsity or arrival order).
 #include "lbt_internal.h"
+#include <cstdio>
+#include <cstdlib>
 
 namespace lbt {
 namespace {
@@ -66,6 +68,7 @@ struct GemmArgs {
   int groups;         // granule groups per row of the gathered tensor (Kp/16 or Np/16)
   int gp, gp_log2;    // MODE 0: padded group count; gp_log2 >= 0 when gp is 1, 2 or 4, else -1
   const lbt_grad_state* st;
+  lbt_grad_state* update_st;  // not null: this launch also applies Alg. 1 to the state
   const OperandScalars* sc;
   float* out;
   int32_t* acc;       // optional raw accumulators (direct epilogues only)
@@ -118,6 +121,8 @@ __global__ __launch_bounds__(kThreads) void k_implicit_gemm(const GemmArgs g) {
   const int per_xcd = gridDim.x / kXcds;
   const int lid = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
   if (lid >= g.total_blocks) return;
+  // (the products read only the clip value from the state: no order to keep with this)
+  if (g.update_st && blockIdx.x == 0 && threadIdx.x == 0) interval_update(g.update_st);
   const int m_tile = lid % g.tiles_m;
   const int n_tile = (lid / g.tiles_m) % g.tiles_n;
   const int split = lid / (g.tiles_m * g.tiles_n);
@@ -419,6 +424,7 @@ __global__ __launch_bounds__(kThreads) void k_splitk_reduce(const int32_t* __res
   constexpr int OUTS = kThreads / SL;
   __shared__ int red[SL][OUTS];
   const float scale = output_scale(g);
+  if (g.update_st && blockIdx.x == 0 && threadIdx.x == 0) interval_update(g.update_st);
   const int io = threadIdx.x % OUTS, sl = threadIdx.x / OUTS;
   for (long long base = (long long)blockIdx.x * OUTS; base < n; base += (long long)gridDim.x * OUTS) {
     const long long i = base + io;
@@ -566,15 +572,18 @@ int run_splitk(GemmArgs& g, bool x_unsigned, long long true_k, int32_t* acc, int
   if (plan.splits == 1) {
     g.epi = 2;
     g.acc = acc;
-    return run_gemm(g, 1, plan.bm, 128, 1, KID_GEMM_DW, s);
+    return run_gemm(g, 1, plan.bm, plan.bn, 1, KID_GEMM_DW, s);
   }
   g.epi = 1;
   g.acc = nullptr;
   g.partial = partial;
-  if ((rc = run_gemm(g, 1, plan.bm, 128, plan.splits, KID_GEMM_DW, s))) return rc;
+  lbt_grad_state* const update_st = g.update_st;   // left to the reduce launch
+  g.update_st = nullptr;
+  if ((rc = run_gemm(g, 1, plan.bm, plan.bn, plan.splits, KID_GEMM_DW, s))) return rc;
   const long long n_out = (long long)g.M * g.NJ;
   ProfScope prof(KID_FINALIZE, (double)n_out, s);
   g.acc = acc;
+  g.update_st = update_st;
   const bool many = plan.splits >= 8;
   long long blocks = (n_out + (many ? 63 : 255)) / (many ? 64 : 256);
   if (blocks > 4096) blocks = 4096;
@@ -593,9 +602,16 @@ int run_splitk(GemmArgs& g, bool x_unsigned, long long true_k, int32_t* acc, int
 SplitPlan plan_split_k(int M, int NJ, int chunks) {
   SplitPlan p;
   p.bm = M <= 64 ? 64 : 128;
-  const long long tiles = (long long)((M + p.bm - 1) / p.bm) * ((NJ + 127) / 128);
+  p.bn = 128;
+  long long forced = 0;
+  if (const char* e = getenv("LBT_DW_PLAN")) {   // DEV ONLY
+    int a, b, c;
+    if (sscanf(e, "%d,%d,%d", &a, &b, &c) == 3) { p.bm = a; p.bn = b; forced = c; }
+  }
+  const long long tiles = (long long)((M + p.bm - 1) / p.bm) * ((NJ + p.bn - 1) / p.bn);
   const int iters = (chunks + BKC - 1) / BKC;
   long long splits = 512 / tiles;           // aim at about two workgroups per compute unit
+  if (forced) splits = forced;
   if (splits < 1) splits = 1;
   if (splits > iters) splits = iters;
   const long long out_bytes = (long long)M * NJ * 4;
@@ -609,7 +625,7 @@ SplitPlan plan_split_k(int M, int NJ, int chunks) {
 
 int launch_conv_dx(const ConvGeom& c, const uint8_t* w_codes, const uint8_t* g_codes,
                    const lbt_grad_state* st, const OperandScalars* sc, float* dX, int32_t* acc,
-                   hipStream_t s) {
+                   lbt_grad_state* update_st, hipStream_t s) {
   GemmArgs g{};
   fill_geom(g, c);
   g.A = w_codes;
@@ -638,14 +654,14 @@ int launch_conv_dx(const ConvGeom& c, const uint8_t* w_codes, const uint8_t* g_c
   g.M = c.C;
   g.NJ = (int)nj;
   g.epi = 0;
-  g.st = st; g.sc = sc;
+  g.st = st; g.sc = sc; g.update_st = update_st;
   g.out = dX; g.acc = acc;
   return run_direct(g, 0, s);
 }
 
 int launch_conv_dw(const ConvGeom& c, const uint8_t* g_codes, const uint8_t* x_codes,
                    const lbt_grad_state* st, const OperandScalars* sc, int x_unsigned, float* dW,
-                   int32_t* acc, int32_t* partial, hipStream_t s) {
+                   int32_t* acc, int32_t* partial, lbt_grad_state* update_st, hipStream_t s) {
   GemmArgs g{};
   fill_geom(g, c);
   g.A = g_codes;
@@ -663,7 +679,7 @@ int launch_conv_dw(const ConvGeom& c, const uint8_t* g_codes, const uint8_t* x_c
   g.b_bytes = (unsigned)b_bytes;
   g.M = c.K;
   g.NJ = c.C * c.R * c.S;
-  g.st = st; g.sc = sc;
+  g.st = st; g.sc = sc; g.update_st = update_st;
   g.out = dW;
   return run_splitk(g, x_unsigned != 0, (long long)c.N * c.P * c.Q, acc, partial, s);
 }
@@ -672,7 +688,7 @@ int launch_conv_dw(const ConvGeom& c, const uint8_t* g_codes, const uint8_t* x_c
 // dX[M][K_in] and dW[K_in][N_out] have their contiguous axis on the lanes.
 int launch_linear_dx(const ConvGeom& c, const uint8_t* w_codes, const uint8_t* g_codes,
                      const lbt_grad_state* st, const OperandScalars* sc, float* dX, int32_t* acc,
-                     hipStream_t s) {
+                     lbt_grad_state* update_st, hipStream_t s) {
   GemmArgs g{};
   fill_geom(g, c);
   g.A = g_codes;   // [N][Kp/16][16] gradient rows
@@ -688,14 +704,14 @@ int launch_linear_dx(const ConvGeom& c, const uint8_t* w_codes, const uint8_t* g
   g.M = c.N;
   g.NJ = c.C;
   g.epi = 2;
-  g.st = st; g.sc = sc;
+  g.st = st; g.sc = sc; g.update_st = update_st;
   g.out = dX; g.acc = acc;
   return run_direct(g, 1, s);
 }
 
 int launch_linear_dw(const ConvGeom& c, const uint8_t* g_codes, const uint8_t* x_codes,
                      const lbt_grad_state* st, const OperandScalars* sc, int x_unsigned, float* dW,
-                     int32_t* acc, int32_t* partial, hipStream_t s) {
+                     int32_t* acc, int32_t* partial, lbt_grad_state* update_st, hipStream_t s) {
   GemmArgs g{};
   fill_geom(g, c);
   g.A = x_codes;   // [C][Np/16][16] activation rows
@@ -710,7 +726,7 @@ int launch_linear_dw(const ConvGeom& c, const uint8_t* g_codes, const uint8_t* x
   g.b_bytes = g.lda * (unsigned)c.K;
   g.M = c.C;
   g.NJ = c.K;
-  g.st = st; g.sc = sc;
+  g.st = st; g.sc = sc; g.update_st = update_st;
   g.out = dW;
   return run_splitk(g, x_unsigned != 0, (long long)c.N, acc, partial, s);
 }

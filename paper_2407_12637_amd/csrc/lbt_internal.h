@@ -31,6 +31,25 @@ struct OperandScalars {
   uint32_t bad_w;
 };
 
+// Alg. 1 (Eq. 15-16) for a quantization that ended with status OK, clip-out count n_out of
+// n_total elements: one thread.
+__device__ __forceinline__ void interval_update_with(lbt_grad_state* st, unsigned long long n_out,
+                                                     unsigned long long n_total) {
+  const double lhs = (double)n_out * (double)((1 << st->bits) - 1);
+  const double rhs = __dmul_rn(st->alpha, (double)n_total);
+  const int sg = (lhs > rhs) - (lhs < rhs);
+  double g = __dadd_rn(st->gamma, __dmul_rn(st->beta, (double)sg));
+  g = fmax(g, st->gamma_min);
+  g = fmin(g, st->gamma_max);
+  st->gamma = g;
+  st->step += 1;
+}
+// ... on the statistics the last gradient quantization left in the state.
+__device__ __forceinline__ void interval_update(lbt_grad_state* st) {
+  if (st->status != LBT_STATUS_OK) return;
+  interval_update_with(st, st->n_out, st->n_total);
+}
+
 // ---- profile.hip: optional event timing of every launch ------------------------
 enum KernelId {
   KID_ABSMAX = 0, KID_FLAT_GRAD, KID_FLAT_OPERAND, KID_QUANTIZE_GRAD, KID_QUANTIZE_LAYER, KID_GEMM_DX,
@@ -76,7 +95,7 @@ int launch_absmax3(const float* p0, int64_t n0, int abs0, const float* p1, int64
                    lbt_grad_state* st, hipStream_t s);
 int launch_quantize_flat_grad(const float* g, int64_t n, const uint32_t* pmax, int nblocks,
                               lbt_grad_state* st, uint64_t seed, int rounding, int hindsight,
-                              uint8_t* codes, hipStream_t s);
+                              int fused_update, uint8_t* codes, hipStream_t s);
 int launch_quantize_flat_operand(const float* x, int64_t n, float c_given, const uint32_t* pmax,
                                  int nblocks, int is_unsigned, uint8_t* codes, float* c_out,
                                  float* clip_scale_out, hipStream_t s);
@@ -122,6 +141,7 @@ struct ConvGeom {
 // How the long contraction of dW is cut over workgroups.
 struct SplitPlan {
   int bm;                // rows of the workgroup tile (64 or 128)
+  int bn;                // columns of the workgroup tile (64 or 128)
   int splits;            // number of K slices
   int chunks_per_split;  // chunks (16 codes) per slice
   size_t partial_bytes;  // int32 partial tiles [splits][M][NJ]; 0 when splits == 1
@@ -131,17 +151,19 @@ SplitPlan plan_split_k(int M, int NJ, int chunks);
 // dX: A = W codes [C][R*S][Kp/16][16], B = dY codes [N][Kp/16][P*Q][16]; out/acc [N][C][H][W].
 int launch_conv_dx(const ConvGeom& g, const uint8_t* w_codes, const uint8_t* g_codes,
                    const lbt_grad_state* st, const OperandScalars* sc, float* dX, int32_t* acc,
-                   hipStream_t s);
+                   lbt_grad_state* update_st, hipStream_t s);
 // dW: A = dY codes [K][Np/16][P*Q][16], B = X codes [C][Np/16][H*W][16]; out/acc [K][C][R][S].
 int launch_conv_dw(const ConvGeom& g, const uint8_t* g_codes, const uint8_t* x_codes,
                    const lbt_grad_state* st, const OperandScalars* sc, int x_unsigned, float* dW,
-                   int32_t* acc, int32_t* partial, hipStream_t s);
+                   int32_t* acc, int32_t* partial, lbt_grad_state* update_st, hipStream_t s);
 // Linear layer: A/B roles swapped so both outputs are written along their rows.
+// update_st (all four; may be null): the launch that ends the product also applies Alg. 1 to
+// that state (the products read only the scale from it, so the order inside does not matter).
 int launch_linear_dx(const ConvGeom& g, const uint8_t* w_codes, const uint8_t* g_codes,
                      const lbt_grad_state* st, const OperandScalars* sc, float* dX, int32_t* acc,
-                     hipStream_t s);
+                     lbt_grad_state* update_st, hipStream_t s);
 int launch_linear_dw(const ConvGeom& g, const uint8_t* g_codes, const uint8_t* x_codes,
                      const lbt_grad_state* st, const OperandScalars* sc, int x_unsigned, float* dW,
-                     int32_t* acc, int32_t* partial, hipStream_t s);
+                     int32_t* acc, int32_t* partial, lbt_grad_state* update_st, hipStream_t s);
 
 }  // namespace lbt

@@ -168,6 +168,7 @@ struct GradSetup {
   float gmax, c;
   int status;
   bool hindsight;
+  bool fused_update;  // the workgroup that publishes the statistics also applies Alg. 1
 };
 
 // hindsight: the interval comes from the maximum the previous call left in the state; this
@@ -176,6 +177,7 @@ __device__ __forceinline__ GradSetup grad_setup(const lbt_grad_state* st, const 
                                                 int nblocks, bool hindsight = false) {
   GradSetup g;
   g.hindsight = hindsight;
+  g.fused_update = false;
   uint32_t bits;
   if (hindsight) {
     bits = __float_as_uint(st->gmax) & 0x7fffffffu;
@@ -255,6 +257,7 @@ __device__ __forceinline__ void grad_finish(lbt_grad_state* st, const GradSetup&
       // k_absmax3 has reset the status to OK; an operand quantizer of the same launch
       // may already have flagged a non-finite operand, which must stay
       if (status != LBT_STATUS_OK) atomicCAS(&st->status, LBT_STATUS_OK, status);
+      else if (g.fused_update) interval_update_with(st, (old2 + sub) & kCountMask, n_total);
       st->sync_word = 0;
     }
   }
@@ -287,17 +290,7 @@ __device__ __forceinline__ float operand_setup(float c_given, const uint32_t* pm
 // ---------------------------------------------------------------------------
 // one-thread kernels
 // ---------------------------------------------------------------------------
-__global__ void k_update_interval(lbt_grad_state* st) {
-  if (st->status != LBT_STATUS_OK) return;
-  const double lhs = (double)st->n_out * (double)((1 << st->bits) - 1);
-  const double rhs = __dmul_rn(st->alpha, (double)st->n_total);
-  const int sg = (lhs > rhs) - (lhs < rhs);
-  double g = __dadd_rn(st->gamma, __dmul_rn(st->beta, (double)sg));
-  g = fmax(g, st->gamma_min);
-  g = fmin(g, st->gamma_max);
-  st->gamma = g;
-  st->step += 1;
-}
+__global__ void k_update_interval(lbt_grad_state* st) { interval_update(st); }
 
 __global__ void k_state_set(lbt_grad_state* st, lbt_grad_state v) { *st = v; }
 
@@ -380,12 +373,13 @@ template <int MODE>
 __global__ __launch_bounds__(kThreads) void k_quantize_flat(
     const float* __restrict__ x, long long n, float c_given, const uint32_t* pmax, int nblocks,
     lbt_grad_state* st, unsigned long long seed, uint8_t* __restrict__ codes, float* c_out,
-    float* clip_scale_out, int hindsight) {
+    float* clip_scale_out, int hindsight, int fused_update) {
   constexpr bool kGrad = (MODE >= 2);
   GradSetup gs{};
   float c;
   if (kGrad) {
     gs = grad_setup(st, pmax, nblocks, hindsight != 0);
+    gs.fused_update = fused_update != 0;
     c = gs.c;
   } else {
     c = operand_setup(c_given, pmax, nblocks, 1, MODE == 1, c_out, nullptr, nullptr, clip_scale_out,
@@ -989,17 +983,17 @@ int launch_absmax3(const float* p0, int64_t n0, int abs0, const float* p1, int64
 
 int launch_quantize_flat_grad(const float* g, int64_t n, const uint32_t* pmax, int nblocks,
                               lbt_grad_state* st, uint64_t seed, int rounding, int hindsight,
-                              uint8_t* codes, hipStream_t s) {
+                              int fused_update, uint8_t* codes, hipStream_t s) {
   ProfScope prof(KID_FLAT_GRAD, (double)n, s);
   const int grid = flat_grid((n + 7) / 8);
   if (rounding == LBT_ROUND_STOCHASTIC)
     LBT_LAUNCH(k_quantize_flat<3>, dim3(grid), dim3(kThreads), 0, s, g, (long long)n, 0.0f,
                        pmax, nblocks, st, (unsigned long long)seed, codes, (float*)nullptr,
-                       (float*)nullptr, hindsight);
+                       (float*)nullptr, hindsight, fused_update);
   else
     LBT_LAUNCH(k_quantize_flat<2>, dim3(grid), dim3(kThreads), 0, s, g, (long long)n, 0.0f,
                        pmax, nblocks, st, (unsigned long long)seed, codes, (float*)nullptr,
-                       (float*)nullptr, hindsight);
+                       (float*)nullptr, hindsight, fused_update);
   LBT_LAUNCH_CHECK();
   return LBT_OK;
 }
@@ -1012,11 +1006,11 @@ int launch_quantize_flat_operand(const float* x, int64_t n, float c_given, const
   if (is_unsigned)
     LBT_LAUNCH(k_quantize_flat<1>, dim3(grid), dim3(kThreads), 0, s, x, (long long)n,
                        c_given, pmax, nblocks, (lbt_grad_state*)nullptr, 0ull, codes, c_out,
-                       clip_scale_out, 0);
+                       clip_scale_out, 0, 0);
   else
     LBT_LAUNCH(k_quantize_flat<0>, dim3(grid), dim3(kThreads), 0, s, x, (long long)n,
                        c_given, pmax, nblocks, (lbt_grad_state*)nullptr, 0ull, codes, c_out,
-                       clip_scale_out, 0);
+                       clip_scale_out, 0, 0);
   LBT_LAUNCH_CHECK();
   return LBT_OK;
 }

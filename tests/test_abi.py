@@ -59,7 +59,7 @@ def test_host_validation_rejects_without_gpu(lib):
     p = C.c_void_p(4096)
     big = 1 << 20
     assert lib.lbt_quantize_grad(p, 0, p, 0, 0, p, p, big, None) == -2          # n <= 0
-    assert lib.lbt_quantize_grad(p, 8, p, 0, 7, p, p, big, None) == -3          # rounding mode
+    assert lib.lbt_quantize_grad(p, 8, p, 0, 8, p, p, big, None) == -3          # rounding bits
     assert lib.lbt_quantize_grad(C.c_void_p(4100), 8, p, 0, 0, p, p, big, None) == -7
     assert lib.lbt_quantize_grad(p, 8, p, 0, 0, p, p, 16, None) == -4           # workspace
     assert lib.lbt_workspace_bytes_quantize(8) == 256 + 2048 * 16

@@ -153,7 +153,7 @@ def test_rejects_unknown_rounding_bits():
     codes = torch.zeros(32, dtype=torch.uint8, device=gu.DEV)
     ws = torch.zeros(lbt.lbt_workspace_bytes_quantize(64), dtype=torch.uint8, device=gu.DEV)
     with pytest.raises(lbt.LbtError):
-        lbt.lbt_quantize_grad(g, st, 0, 4, codes, ws)
+        lbt.lbt_quantize_grad(g, st, 0, 8, codes, ws)
 
 
 def test_full_size_layer_single_sweep():

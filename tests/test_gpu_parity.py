@@ -264,3 +264,68 @@ def test_backward_is_deterministic():
     a = gu.backward_conv2d(X, Wt, dY, stride, pad, st, seed=3, rounding=1)
     b = gu.backward_conv2d(X, Wt, dY, stride, pad, st, seed=3, rounding=1)
     assert np.array_equal(a.dW, b.dW) and np.array_equal(a.dX, b.dX)
+
+
+# -- LBT_FUSED_UPDATE: the call applies Alg. 1 itself ---------------------------------------
+def test_fused_update_flat():
+    r = synth.rng(0, 20, 0, synth.T_DY)
+    st = lbt.new_state(gamma0=0.5)
+    ost = oracle.GradState(gamma=0.5)
+    for it in range(6):
+        g = synth.grad_cfg4(r, (300007,))
+        want = oracle.quantize_grad(g, ost, seed=4, rounding=1)
+        oracle.update_interval(ost)
+        packed = gu.quantize_grad(g, st, seed=4, rounding=1 | lbt.FUSED_UPDATE)
+        assert np.array_equal(packed, oracle.pack_nibbles(want))
+        gu.assert_state_equal(lbt.lbt_state_read(st), ost)
+    assert ost.step == 6 and ost.gamma != 0.5
+    # no update on a tensor that cannot be quantized
+    gu.quantize_grad(np.zeros(100, np.float32), st, rounding=lbt.FUSED_UPDATE)
+    h = lbt.lbt_state_read(st)
+    assert h.status == lbt.STATUS_ZERO_GRAD and h.step == 6 and h.gamma == ost.gamma
+
+
+@pytest.mark.parametrize("want", [(True, True), (True, False), (False, True)])
+@pytest.mark.parametrize("case", [(16, 16, 32, 32, 16, 3, 3, 1, 1),     # dW: split contraction
+                                  (2, 3, 8, 8, 4, 3, 3, 1, 1)])         # dW: one slice
+def test_fused_update_conv(case, want):
+    N, Cc, H, W, K, R, S, stride, pad = case
+    want_dx, want_dw = want
+    _say("fused update conv", case, want)
+    r = synth.rng(0, 21, K, 0)
+    X, Wt = synth.relu_normal(r, (N, Cc, H, W)), synth.kaiming_normal(r, (K, Cc, R, S))
+    st = lbt.new_state(gamma0=0.3)
+    ost = oracle.GradState(gamma=0.3)
+    for it in range(3):
+        dY = synth.grad_cfg2(r, (N, K, H, W))
+        ref = oracle.backward_conv2d(X, Wt, dY, stride, pad, ost, seed=8, rounding=1,
+                                     want_dx=want_dx, want_dw=want_dw)
+        oracle.update_interval(ost)
+        res = gu.backward_conv2d(X, Wt, dY, stride, pad, st, seed=8,
+                                 rounding=1 | lbt.FUSED_UPDATE, want_dx=want_dx, want_dw=want_dw)
+        gu.assert_state_equal(lbt.lbt_state_read(st), ost)
+        _check_backward(res, ref)
+    assert ost.step == 3
+    # a non-finite activation: status reported, no update
+    if want_dw:
+        Xb = X.copy()
+        Xb[0, 0, 0, 0] = np.inf
+        gu.backward_conv2d(Xb, Wt, dY, stride, pad, st, seed=8, rounding=1 | lbt.FUSED_UPDATE,
+                           want_dx=want_dx, want_dw=want_dw)
+        h = lbt.lbt_state_read(st)
+        assert h.status == lbt.STATUS_NONFINITE and h.step == 3 and h.gamma == ost.gamma
+
+
+def test_fused_update_linear():
+    M, K, N = 130, 72, 200
+    r = synth.rng(0, 22, 0, 0)
+    X, W = synth.normal(r, (M, K)), synth.normal(r, (K, N), 0.05)
+    st = lbt.new_state(gamma0=0.2)
+    ost = oracle.GradState(gamma=0.2)
+    for it in range(3):
+        dY = synth.dense_grad(r, (M, N))
+        ref = oracle.backward_linear(X, W, dY, ost, seed=2, rounding=1)
+        oracle.update_interval(ost)
+        res = gu.backward_linear(X, W, dY, st, seed=2, rounding=1 | lbt.FUSED_UPDATE)
+        gu.assert_state_equal(lbt.lbt_state_read(st), ost)
+        _check_backward(res, ref)
