@@ -36,8 +36,6 @@
 // kernel sums the partials and applies the scale (no atomics: the result does not
 // depend on data sparsity or arrival order).
 #include "lbt_internal.h"
-#include <cstdio>
-#include <cstdlib>
 
 namespace lbt {
 namespace {
@@ -599,19 +597,31 @@ int run_splitk(GemmArgs& g, bool x_unsigned, long long true_k, int32_t* acc, int
 
 }  // namespace
 
+// Measured on the ResNet-50 shapes (every variant of tile and slice count per layer): a dW
+// launch costs 11 us or more whatever its size, and each slice adds its int32 tile twice to
+// the traffic (written here, read by the reduce).  Long contractions over a small output
+// want many slices of 128-wide tiles; short ones (<= 32 K steps) over an output of 256 or
+// more 64x64 tiles run fastest unsplit, with no reduce launch at all; in between, 64x64
+// tiles cut four ways.
 SplitPlan plan_split_k(int M, int NJ, int chunks) {
   SplitPlan p;
-  p.bm = M <= 64 ? 64 : 128;
-  p.bn = 128;
-  long long forced = 0;
-  if (const char* e = getenv("LBT_DW_PLAN")) {   // DEV ONLY
-    int a, b, c;
-    if (sscanf(e, "%d,%d,%d", &a, &b, &c) == 3) { p.bm = a; p.bn = b; forced = c; }
-  }
-  const long long tiles = (long long)((M + p.bm - 1) / p.bm) * ((NJ + p.bn - 1) / p.bn);
   const int iters = (chunks + BKC - 1) / BKC;
-  long long splits = 512 / tiles;           // aim at about two workgroups per compute unit
-  if (forced) splits = forced;
+  const long long tiles64 = (long long)((M + 63) / 64) * ((NJ + 63) / 64);
+  long long splits;
+  if (iters <= 32 && tiles64 >= 256) {
+    p.bm = (tiles64 >= 512 && M >= 128) ? 128 : 64;
+    p.bn = 64;
+    splits = 1;
+  } else if (iters <= 128 && tiles64 >= 64 && tiles64 <= 256) {
+    p.bm = 64;
+    p.bn = 64;
+    splits = 4;
+  } else {
+    p.bm = M <= 64 ? 64 : 128;
+    p.bn = 128;
+    const long long tiles = (long long)((M + p.bm - 1) / p.bm) * ((NJ + p.bn - 1) / p.bn);
+    splits = 512 / tiles;           // aim at about two workgroups per compute unit
+  }
   if (splits < 1) splits = 1;
   if (splits > iters) splits = iters;
   const long long out_bytes = (long long)M * NJ * 4;

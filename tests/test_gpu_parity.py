@@ -141,7 +141,10 @@ def test_backward_linear_config1():
 
 
 @pytest.mark.parametrize("shape", [(1, 1, 1), (3, 5, 7), (130, 70, 200), (64, 2048, 1000),
-                                   (257, 129, 33)])
+                                   (257, 129, 33),
+                                   (64, 1024, 1024),     # dW unsplit on 64x64 tiles
+                                   (40, 1000, 1030),     # ... with ragged edges
+                                   (32, 2048, 1024)])    # dW unsplit on 128x64 tiles
 @pytest.mark.parametrize("x_unsigned", [False, True])
 def test_backward_linear_shapes(shape, x_unsigned):
     M, K, N = shape
@@ -175,6 +178,7 @@ CONV_CASES = [
     (2, 24, 9, 9, 136, 3, 3, 2, 1),        # 9 channel groups, padded to 16 in the dX walk
     (3, 16, 5, 5, 80, 3, 3, 1, 1),         # 5 channel groups, padded to 8
     (2, 16, 6, 6, 128, 3, 3, 1, 1),        # exactly 8 channel groups: one tap per K step
+    (16, 128, 8, 8, 256, 3, 3, 1, 1),      # dW: 72 tiles of 64x64, contraction cut four ways
 ]
 
 
