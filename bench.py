@@ -44,6 +44,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--rounding", choices=["stochastic", "nearest"], default="stochastic")
     ap.add_argument("--gamma0", type=float, default=1.0)
+    ap.add_argument("--bits", type=int, default=4, choices=[2, 3, 4, 5, 6, 7, 8],
+                    help="bit-width of weights, activations and gradients (the headline is 4; "
+                         "at 8 the activations are quantized as signed values)")
     ap.add_argument("--separate-update", action="store_true",
                     help="apply the interval update with lbt_update_interval after every layer "
                          "instead of inside the backward call (LBT_FUSED_UPDATE)")
@@ -112,7 +115,7 @@ class LayerRun:
             lbt.lbt_update_interval(self.state)
 
 
-def cpu_baseline(layers, rounding):
+def cpu_baseline(layers, rounding, bits=4):
     """Time the CPU oracle (as it stands) on a few layers of the same sweep."""
     import numpy as np
 
@@ -133,11 +136,11 @@ def cpu_baseline(layers, rounding):
     for L in sample:
         s = L.spec
         X, W, dY = (t.cpu().numpy() for t in (L.X, L.W, L.dY))
-        st = oracle.GradState(gamma=1.0)
+        st = oracle.GradState(gamma=1.0, bits=bits)
         t0 = time.perf_counter()
         oracle.quantize_grad(dY, st, L.seed, rounding)
         t1 = time.perf_counter()
-        st = oracle.GradState(gamma=1.0)
+        st = oracle.GradState(gamma=1.0, bits=bits)
         if L.is_linear:
             oracle.backward_linear(X, W, dY, st, x_unsigned=L.x_unsigned, seed=L.seed,
                                    rounding=rounding)
@@ -208,6 +211,7 @@ def main():
     gen = torch.Generator(device="cuda")
     gen.manual_seed(0)
 
+    rounding |= lbt.BITS(args.bits)
     vit = args.workload == "vit-l"
     table = synth.vit_l_layers(64) if vit else synth.resnet50_layers(64)
     layers = []
@@ -216,9 +220,10 @@ def main():
             continue
         for _ in range(spec.count):
             layers.append(LayerRun(spec, len(layers), torch, lbt, gen,
-                                   isinstance(spec, synth.LinearLayer), x_unsigned=not vit))
+                                   isinstance(spec, synth.LinearLayer),
+                                   x_unsigned=not vit and args.bits < 8))
     for L in layers:
-        L.state = lbt.new_state(gamma0=args.gamma0)
+        L.state = lbt.new_state(gamma0=args.gamma0, bits=args.bits)
     ws = torch.zeros(max(L.ws_bytes(lbt) for L in layers), dtype=torch.uint8, device="cuda")
     gemm_ops = sum(2.0 * L.spec.gemm_ops for L in layers)       # dX and dW
     n_grad = sum(L.dY.numel() for L in layers)
@@ -242,10 +247,10 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8",
         "data": "synthetic",
-        "config": {"workload": "%s, batch 64, %d layers, INT4 W/A/G, %s rounding, gamma0=%g"
+        "config": {"workload": "%s, batch 64, %d layers, INT%d W/A/G, %s rounding, gamma0=%g"
                                % ("ViT-L encoder block linear layers (197 tokens)" if vit
-                                  else "ResNet-50 bottleneck sweep", len(layers), args.rounding,
-                                  args.gamma0),
+                                  else "ResNet-50 bottleneck sweep", len(layers), args.bits,
+                                  args.rounding, args.gamma0),
                    "gemm_GOP_per_step": gemm_ops / 1e9, "grad_elements_per_step": n_grad},
     }
     if args.single_sweep:
@@ -328,7 +333,7 @@ def main():
                                    "frac_of_layer_rooflines": t_roof * 1e3 / t_ms}
 
     if not args.no_cpu_baseline and not args.single_sweep:   # the oracle is timed on the paper's mode
-        out["cpu_baseline"] = cpu_baseline(layers, rounding & lbt.ROUND_STOCHASTIC)
+        out["cpu_baseline"] = cpu_baseline(layers, rounding & lbt.ROUND_STOCHASTIC, args.bits)
 
     print(json.dumps(out))
 

@@ -21,8 +21,14 @@
  *     lbt_state_read which waits for its copy.
  *   - Conditions found on the device (non-finite or all-zero gradient) are
  *     written to lbt_grad_state.status and read back with lbt_state_read.
- *   - All tensors are dense, row-major, fp32.  Only b = 4 bits is implemented
- *     on the device in this version; other values return LBT_ERR_UNSUPPORTED.
+ *   - All tensors are dense, row-major, fp32.
+ *   - Bit-width b (Eq. 1-3): 2..8, the same for the weights, activations and gradients of a
+ *     call; 4 unless LBT_BITS(b) is OR-ed into the call's `rounding` word.  A gradient
+ *     quantization records its b in st->bits (used by the update, Eq. 16).
+ *   - Flat code format (lbt_quantize_grad, lbt_quantize_operand): for b <= 4, ceil(n/2)
+ *     bytes, element 2j in the low nibble of byte j and 2j+1 in the high nibble (signed
+ *     codes as 4-bit two's complement, a trailing pad nibble is 0); for b > 4, n bytes, one
+ *     code each (int8 two's complement or uint8), and `codes` must be 8-byte aligned.
  */
 #ifndef LBT_H_
 #define LBT_H_
@@ -37,7 +43,7 @@ extern "C" {
 #define LBT_OK 0
 #define LBT_ERR_NULL (-1)        /* a required pointer is NULL                     */
 #define LBT_ERR_SHAPE (-2)       /* a size is <= 0 or inconsistent                 */
-#define LBT_ERR_UNSUPPORTED (-3) /* bits != 4, size beyond a documented limit      */
+#define LBT_ERR_UNSUPPORTED (-3) /* bits outside 2..8, unknown flag, size beyond a documented limit */
 #define LBT_ERR_WORKSPACE (-4)   /* workspace smaller than lbt_workspace_bytes_*   */
 #define LBT_ERR_OVERFLOW (-5)    /* a contraction could exceed int32 accumulators  */
 #define LBT_ERR_HIP (-6)         /* a HIP runtime call failed                      */
@@ -66,6 +72,8 @@ extern "C" {
  * call's kernel launch.  Do not call lbt_update_interval for the same tensor again.
  */
 #define LBT_FUSED_UPDATE 4
+/* May be OR-ed into `rounding`: bit-width b in 2..8 (the paper's experiments: 4, 5, 6, 8). */
+#define LBT_BITS(b) (((b) & 15) << 8)
 
 /*
  * Per-layer state of the gradient quantizer: the scalars of Alg. 1 plus the
@@ -117,12 +125,11 @@ int lbt_update_interval(lbt_grad_state* st, void* stream);
 
 /*
  * Gradient quantizer of one layer (Sec. 3.1, Eq. 1, 2, 4).
- *   g[n] fp32  ->  codes: ceil(n/2) bytes, element 2j in the low nibble of byte
- *   j and 2j+1 in the high nibble, two's-complement 4-bit values in [-7, 7]
- *   (code -8 never occurs); a trailing pad nibble is 0.
+ *   g[n] fp32  ->  codes in the flat format above, values in [-q, q] with
+ *   q = 2^(b-1) - 1 ([-7, 7] for b = 4; the most negative code never occurs).
  * Computes g_max, c_g = gamma * g_max, the codes, and N(G_out); writes gmax,
  * clip, scale, n_total, n_out, status to *st.  Does not change gamma or step.
- * The code is decided in fp32: x_n = clip(g) * fl32(7 / c_g), one multiply.
+ * The code is decided in fp32: x_n = clip(g) * fl32(q / c_g), one multiply.
  * rounding = LBT_ROUND_STOCHASTIC draws 16 bits per element from
  * Philox4x32-10 with key = seed and counter = (element/8, st->step); element
  * e uses 16-bit lane e%8 of the four output words, low half first.
@@ -135,7 +142,7 @@ size_t lbt_workspace_bytes_quantize(int64_t n);
 /*
  * Weight / activation quantizer (Eq. 2 for zero-centred inputs, Eq. 3 for
  * inputs after a ReLU), nearest rounding, same code format as above (unsigned
- * codes are 0..15).  c > 0 is the clipping value (learned by the caller in the
+ * codes are 0..2^b - 1).  c > 0 is the clipping value (learned by the caller in the
  * paper, Sec. 3.1); c <= 0 selects the tensor's own maximum (max|x| signed,
  * max x unsigned).  clip_scale_out (device, 2 floats, may be NULL) receives
  * the clip value and the scale s.  ws: lbt_workspace_bytes_quantize(n).
@@ -154,7 +161,12 @@ int lbt_quantize_operand(const float* x, int64_t n, float c, int is_unsigned, in
  * tensor's maximum); x_unsigned selects Eq. (3) for X.  The sums run on int8
  * matrix cores with int32 accumulators and are exact; outputs are
  * acc * (s_a * s_b) in fp32.  dX or dW may be NULL to skip that product.
- * Requires M*112*112 and N_out*112*112 < 2^31 (LBT_ERR_OVERFLOW otherwise).
+ * Exactness is checked on the host against the worst case: with q = 2^(b-1) - 1 and
+ * q_x = 2^b - 1 for unsigned X, the dX contraction needs N_out * q * q < 2^31, and every
+ * int32 accumulator of dW (the contraction over M is cut into slices of at most 131072
+ * terms, added in 64 bits) needs slice * q * q_x < 2^31: LBT_ERR_OVERFLOW otherwise.
+ * Unsigned X with b = 8 (codes 0..255) does not fit the signed int8 operands of the
+ * matrix cores: LBT_ERR_UNSUPPORTED when dW is asked for.
  */
 int lbt_backward_linear(const float* X, const float* W, const float* dY, int64_t M,
                         int64_t K_in, int64_t N_out, float c_x, int x_unsigned, float c_w,
@@ -180,7 +192,8 @@ size_t lbt_workspace_bytes_conv2d(int64_t N, int64_t C, int64_t H, int64_t Wd, i
 /*
  * The same two calls with the raw int32 accumulators also written out
  * (acc_dX shaped like dX, acc_dW like dW; either may be NULL).  For checking
- * the integer sums bit for bit.
+ * the integer sums bit for bit.  LBT_ERR_OVERFLOW if the worst case of a whole sum (not
+ * only of a slice) does not fit 32 bits.
  */
 int lbt_backward_linear_acc(const float* X, const float* W, const float* dY, int64_t M,
                             int64_t K_in, int64_t N_out, float c_x, int x_unsigned, float c_w,

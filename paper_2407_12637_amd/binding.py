@@ -19,6 +19,13 @@ OK = 0
 ROUND_NEAREST, ROUND_STOCHASTIC = 0, 1
 HINDSIGHT_MAX = 2  # may be OR-ed into `rounding`: interval from the previous tensor's maximum
 FUSED_UPDATE = 4   # may be OR-ed into `rounding`: the call also applies the interval update (Alg. 1)
+
+
+def BITS(b: int) -> int:
+    """LBT_BITS(b): the bit-width field of the `rounding` flag word (absent = 4)."""
+    return (b & 15) << 8
+
+
 STATUS_OK, STATUS_NONFINITE, STATUS_ZERO_GRAD = 0, 1, 2
 
 

@@ -48,20 +48,33 @@ int make_geom(int64_t N, int64_t C, int64_t H, int64_t W, int64_t K, int64_t R, 
   g.P = (int)P; g.Q = (int)Q; g.stride = (int)stride; g.pad = (int)pad;
   g.Np = (int)round_up(N, kGranule);
   g.Kp = (int)round_up(K, kGranule);
+  g.bits = 4;
   *out = g;
   return LBT_OK;
 }
 
+// Splits the flag word `rounding`: checks it, returns the bit-width (LBT_BITS field, 0 = 4).
+bool split_flags(int rounding, int* bits) {
+  const int known = LBT_ROUND_STOCHASTIC | LBT_HINDSIGHT_MAX | LBT_FUSED_UPDATE | LBT_BITS(15);
+  if (rounding & ~known) return false;
+  const int b = (rounding >> 8) & 15;
+  *bits = b ? b : 4;
+  return *bits >= 2 && *bits <= 8;
+}
+
 // w_is_ck: W is stored [C][K] (linear layer, [in][out]) instead of [K][C][R][S].
-int backward_common(const float* X, const float* W, const float* dY, const ConvGeom& g,
+int backward_common(const float* X, const float* W, const float* dY, ConvGeom g,
                     bool w_is_ck, float c_x, int x_unsigned, float c_w, lbt_grad_state* st,
                     uint64_t seed, int rounding, float* dX, float* dW, int32_t* acc_dX,
                     int32_t* acc_dW, void* ws, size_t ws_bytes, void* stream) {
   if (!W || !dY || !st || !ws) return LBT_ERR_NULL;
   if (dW && !X) return LBT_ERR_NULL;
   if ((acc_dX && !dX) || (acc_dW && !dW)) return LBT_ERR_NULL;
-  if (rounding & ~(LBT_ROUND_STOCHASTIC | LBT_HINDSIGHT_MAX | LBT_FUSED_UPDATE))
-    return LBT_ERR_UNSUPPORTED;
+  int bits;
+  if (!split_flags(rounding, &bits)) return LBT_ERR_UNSUPPORTED;
+  // unsigned 8-bit codes (0..255) do not fit the signed int8 operands of the matrix cores
+  if (x_unsigned && dW && bits == 8) return LBT_ERR_UNSUPPORTED;
+  g.bits = bits;
   const int hindsight = (rounding & LBT_HINDSIGHT_MAX) ? 1 : 0;
   const int fused_update = (rounding & LBT_FUSED_UPDATE) ? 1 : 0;
   rounding &= LBT_ROUND_STOCHASTIC;
@@ -101,6 +114,7 @@ int backward_common(const float* X, const float* W, const float* dY, const ConvG
     q.seed = seed;
     q.rounding = rounding;
     q.hindsight = hindsight;
+    q.bits = bits;
     q.x_unsigned = x_unsigned;
     q.tensor[0] = {dY, g.N, g.K, PQ,
                    RelayoutIo{pmax, nblocks, 0, st, dX ? g_npqk : nullptr, dW ? g_kpqn : nullptr, 0},
@@ -159,7 +173,7 @@ int lbt_state_init(lbt_grad_state* st, double gamma0, double alpha, double beta,
                    double gamma_max, int bits, void* stream) {
   if (!st) return LBT_ERR_NULL;
   if (!aligned(st, 8)) return LBT_ERR_ALIGN;
-  if (bits != 4) return LBT_ERR_UNSUPPORTED;
+  if (bits < 2 || bits > 8) return LBT_ERR_UNSUPPORTED;
   if (!(gamma_min > 0.0) || !(gamma_max >= gamma_min) || !(gamma0 >= gamma_min) ||
       !(gamma0 <= gamma_max) || !(alpha > 0.0) || !(beta >= 0.0))
     return LBT_ERR_SHAPE;
@@ -180,7 +194,7 @@ int lbt_state_read(const lbt_grad_state* st, lbt_grad_state* host_out, void* str
 
 int lbt_state_write(lbt_grad_state* st, const lbt_grad_state* host_in, void* stream) {
   if (!st || !host_in) return LBT_ERR_NULL;
-  if (host_in->bits != 4) return LBT_ERR_UNSUPPORTED;
+  if (host_in->bits < 2 || host_in->bits > 8) return LBT_ERR_UNSUPPORTED;
   lbt_grad_state v = *host_in;
   v.sync_word = 0;
   v.sync_max = 0;
@@ -201,12 +215,12 @@ int lbt_quantize_grad(const float* g, int64_t n, lbt_grad_state* st, uint64_t se
                       uint8_t* codes, void* ws, size_t ws_bytes, void* stream) {
   if (!g || !st || !codes || !ws) return LBT_ERR_NULL;
   if (n <= 0) return LBT_ERR_SHAPE;
-  if (rounding & ~(LBT_ROUND_STOCHASTIC | LBT_HINDSIGHT_MAX | LBT_FUSED_UPDATE))
-    return LBT_ERR_UNSUPPORTED;
+  int bits;
+  if (!split_flags(rounding, &bits)) return LBT_ERR_UNSUPPORTED;
   const int hindsight = (rounding & LBT_HINDSIGHT_MAX) ? 1 : 0;
   const int fused_update = (rounding & LBT_FUSED_UPDATE) ? 1 : 0;
   rounding &= LBT_ROUND_STOCHASTIC;
-  if (!aligned(g, 16) || !aligned(codes, 4) || !aligned(st, 8) || !aligned(ws, 256))
+  if (!aligned(g, 16) || !aligned(codes, bits > 4 ? 8 : 4) || !aligned(st, 8) || !aligned(ws, 256))
     return LBT_ERR_ALIGN;
   if (ws_bytes < lbt_workspace_bytes_quantize(n)) return LBT_ERR_WORKSPACE;
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
@@ -217,7 +231,7 @@ int lbt_quantize_grad(const float* g, int64_t n, lbt_grad_state* st, uint64_t se
                            &nblocks, st, s)))
     return rc;
   return launch_quantize_flat_grad(g, n, pmax, nblocks, st, seed, rounding, hindsight, fused_update,
-                                   codes, s);
+                                   bits, codes, s);
 }
 
 int lbt_quantize_operand(const float* x, int64_t n, float c, int is_unsigned, int bits,
@@ -225,8 +239,8 @@ int lbt_quantize_operand(const float* x, int64_t n, float c, int is_unsigned, in
                          void* stream) {
   if (!x || !codes || !ws) return LBT_ERR_NULL;
   if (n <= 0) return LBT_ERR_SHAPE;
-  if (bits != 4) return LBT_ERR_UNSUPPORTED;
-  if (!aligned(x, 16) || !aligned(codes, 4) || !aligned(ws, 256)) return LBT_ERR_ALIGN;
+  if (bits < 2 || bits > 8) return LBT_ERR_UNSUPPORTED;
+  if (!aligned(x, 16) || !aligned(codes, bits > 4 ? 8 : 4) || !aligned(ws, 256)) return LBT_ERR_ALIGN;
   if (ws_bytes < lbt_workspace_bytes_quantize(n)) return LBT_ERR_WORKSPACE;
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   OperandScalars* sc = static_cast<OperandScalars*>(ws);
@@ -237,7 +251,7 @@ int lbt_quantize_operand(const float* x, int64_t n, float c, int is_unsigned, in
     if ((rc = launch_absmax3(nullptr, 0, 0, x, n, is_unsigned ? 0 : 1, nullptr, 0, 0, pmax, &nblocks,
                              nullptr, s)))
       return rc;
-  return launch_quantize_flat_operand(x, n, c, pmax, nblocks, is_unsigned, codes, &sc->c_x,
+  return launch_quantize_flat_operand(x, n, c, pmax, nblocks, is_unsigned, bits, codes, &sc->c_x,
                                       clip_scale_out, s);
 }
 

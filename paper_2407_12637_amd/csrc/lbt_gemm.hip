@@ -36,6 +36,7 @@
 // kernel sums the partials and applies the scale (no atomics: the result does not
 // depend on data sparsity or arrival order).
 #include "lbt_internal.h"
+#include <type_traits>
 
 namespace lbt {
 namespace {
@@ -61,6 +62,7 @@ struct GemmArgs {
   int epi;            // 0 = scaled store to NCHW dX, 1 = int32 partial tile (split K),
                       // 2 = scaled store row-major
   int scale_kind;     // 0: s_g*s_w   1: s_x*s_g (signed x)   2: s_x*s_g (unsigned x)
+  int bits;           // b: the codes' scales are c / levels(b)
   int N, C, H, W, K, R, S, P, Q, stride, pad;
   int inner;          // MODE 1: chunk t = group * inner + pos, inner = P*Q (1 for linear)
   int groups;         // granule groups per row of the gathered tensor (Kp/16 or Np/16)
@@ -90,10 +92,11 @@ __device__ __forceinline__ void wait_loads() {
 }
 
 __device__ __forceinline__ float output_scale(const GemmArgs& g) {
-  const double s_g = (double)g.st->clip / 7.0;
+  const double q_signed = (double)levels(g.bits, false);
+  const double s_g = (double)g.st->clip / q_signed;
   double other;
-  if (g.scale_kind == 0) other = (double)g.sc->c_w / 7.0;
-  else other = (double)g.sc->c_x / (g.scale_kind == 2 ? 15.0 : 7.0);
+  if (g.scale_kind == 0) other = (double)g.sc->c_w / q_signed;
+  else other = (double)g.sc->c_x / (g.scale_kind == 2 ? (double)levels(g.bits, true) : q_signed);
   return (float)(s_g * other);
 }
 
@@ -416,17 +419,19 @@ __global__ __launch_bounds__(kThreads) void k_implicit_gemm(const GemmArgs g) {
 // (group w sums slices w, w + SL, ..., eight loads in flight per thread) and meet in LDS.
 // SL = 4 for many slices of a small output, SL = 1 for few slices of a large one.
 // Integer adds: the result does not depend on how the slices are grouped.
-template <int SL>
+// WIDE: the slices are added in 64 bits (their sum may exceed 32 bits; each slice fits).
+template <int SL, bool WIDE>
 __global__ __launch_bounds__(kThreads) void k_splitk_reduce(const int32_t* __restrict__ partial,
                                                              int splits, long long n, GemmArgs g) {
   constexpr int OUTS = kThreads / SL;
-  __shared__ int red[SL][OUTS];
+  using sum_t = typename std::conditional<WIDE, long long, int>::type;
+  __shared__ sum_t red[SL][OUTS];
   const float scale = output_scale(g);
   if (g.update_st && blockIdx.x == 0 && threadIdx.x == 0) interval_update(g.update_st);
   const int io = threadIdx.x % OUTS, sl = threadIdx.x / OUTS;
   for (long long base = (long long)blockIdx.x * OUTS; base < n; base += (long long)gridDim.x * OUTS) {
     const long long i = base + io;
-    int sum = 0;
+    sum_t sum = 0;
     if (i < n) {
       for (int s0 = sl; s0 < splits; s0 += 8 * SL) {
         int v[8];
@@ -435,7 +440,7 @@ __global__ __launch_bounds__(kThreads) void k_splitk_reduce(const int32_t* __res
           const int sp = s0 + SL * u;
           v[u] = sp < splits ? partial[(long long)sp * n + i] : 0;
         }
-        sum += ((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7]));
+        sum += (((sum_t)v[0] + v[1]) + ((sum_t)v[2] + v[3])) + (((sum_t)v[4] + v[5]) + ((sum_t)v[6] + v[7]));
       }
     }
     if (SL > 1) {
@@ -449,7 +454,7 @@ __global__ __launch_bounds__(kThreads) void k_splitk_reduce(const int32_t* __res
     }
     if (sl == 0 && i < n) {
       g.out[i] = (float)sum * scale;
-      if (g.acc) g.acc[i] = sum;
+      if (g.acc) g.acc[i] = (int)sum;   // the host has checked that it fits
     }
     if (SL > 1) __syncthreads();
   }
@@ -458,6 +463,7 @@ __global__ __launch_bounds__(kThreads) void k_splitk_reduce(const int32_t* __res
 void fill_geom(GemmArgs& g, const ConvGeom& c) {
   g.N = c.N; g.C = c.C; g.H = c.H; g.W = c.W; g.K = c.K; g.R = c.R; g.S = c.S;
   g.P = c.P; g.Q = c.Q; g.stride = c.stride; g.pad = c.pad;
+  g.bits = c.bits;
 }
 
 constexpr size_t kMaxDynLds = 128 * 1024;
@@ -547,12 +553,13 @@ void pick_tile(int M, int NJ, int splits, int* bm, int* bn) {
   }
 }
 
-// Direct (no split) product with signed operands: |sum| <= chunks * 16 * 7 * 7 < 2^31.
+// Direct (no split) product with signed operands: |sum| <= chunks * 16 * q * q < 2^31.
 int run_direct(GemmArgs& g, int mode, hipStream_t s) {
   g.steps = (g.chunks + BKC - 1) / BKC;
   g.steps_per_split = g.steps;
   g.scale_kind = 0;
-  if ((long long)g.chunks * 16 * 49 >= (1ll << 31)) return LBT_ERR_OVERFLOW;
+  const long long q = levels(g.bits, false);
+  if ((long long)g.chunks * 16 * q * q >= (1ll << 31)) return LBT_ERR_OVERFLOW;
   int bm, bn;
   pick_tile(g.M, g.NJ, 1, &bm, &bn);
   return run_gemm(g, mode, bm, bn, 1, KID_GEMM_DX, s);
@@ -561,9 +568,17 @@ int run_direct(GemmArgs& g, int mode, hipStream_t s) {
 int run_splitk(GemmArgs& g, bool x_unsigned, long long true_k, int32_t* acc, int32_t* partial,
                hipStream_t s) {
   g.scale_kind = x_unsigned ? 2 : 1;
-  // the exact sum must fit int32
-  if (true_k * (x_unsigned ? 105 : 49) >= (1ll << 31)) return LBT_ERR_OVERFLOW;
   const SplitPlan plan = plan_split_k(g.M, g.NJ, g.chunks);
+  // Every int32 accumulator (one slice of the contraction) must hold its exact sum; the
+  // slices are added in 64 bits.  The raw int32 sums can be handed out only if the whole
+  // sum fits as well.
+  const long long term = (long long)levels(g.bits, false) * levels(g.bits, x_unsigned);
+  const long long slice_k = plan.splits == 1 ? true_k
+                                             : (true_k < (long long)plan.chunks_per_split * 16
+                                                    ? true_k : (long long)plan.chunks_per_split * 16);
+  if (slice_k * term >= (1ll << 31)) return LBT_ERR_OVERFLOW;
+  const bool wide = true_k * term >= (1ll << 31);
+  if (acc && wide) return LBT_ERR_OVERFLOW;
   g.steps = (g.chunks + BKC - 1) / BKC;
   g.steps_per_split = plan.chunks_per_split / BKC;
   int rc;
@@ -585,12 +600,14 @@ int run_splitk(GemmArgs& g, bool x_unsigned, long long true_k, int32_t* acc, int
   const bool many = plan.splits >= 8;
   long long blocks = (n_out + (many ? 63 : 255)) / (many ? 64 : 256);
   if (blocks > 4096) blocks = 4096;
-  if (many)
-    LBT_LAUNCH(k_splitk_reduce<4>, dim3((unsigned)blocks), dim3(kThreads), 0, s, partial, plan.splits,
-               n_out, g);
-  else
-    LBT_LAUNCH(k_splitk_reduce<1>, dim3((unsigned)blocks), dim3(kThreads), 0, s, partial, plan.splits,
-               n_out, g);
+#define LBT_REDUCE_CASE(SL_, WIDE_)                                                              \
+  LBT_LAUNCH((k_splitk_reduce<SL_, WIDE_>), dim3((unsigned)blocks), dim3(kThreads), 0, s, partial,  \
+             plan.splits, n_out, g)
+  if (many && wide) LBT_REDUCE_CASE(4, true);
+  else if (many) LBT_REDUCE_CASE(4, false);
+  else if (wide) LBT_REDUCE_CASE(1, true);
+  else LBT_REDUCE_CASE(1, false);
+#undef LBT_REDUCE_CASE
   LBT_LAUNCH_CHECK();
   return LBT_OK;
 }
@@ -623,6 +640,9 @@ SplitPlan plan_split_k(int M, int NJ, int chunks) {
     splits = 512 / tiles;           // aim at about two workgroups per compute unit
   }
   if (splits < 1) splits = 1;
+  // a slice of at most 1024 K steps keeps the int32 accumulators exact at every bit-width
+  // (131072 terms of at most 127 * 127)
+  if (splits < (iters + 1023) / 1024) splits = (iters + 1023) / 1024;
   if (splits > iters) splits = iters;
   const long long out_bytes = (long long)M * NJ * 4;
   while (splits > 1 && splits * out_bytes > (48ll << 20)) --splits;

@@ -22,6 +22,11 @@ constexpr int kGranule = 16;  // contraction-axis padding of the GEMM code layou
 
 inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 
+// Largest code of a b-bit quantizer: 2^(b-1) - 1 signed (Eq. 2), 2^b - 1 unsigned (Eq. 3).
+__host__ __device__ inline int levels(int bits, bool is_unsigned) {
+  return is_unsigned ? (1 << bits) - 1 : (1 << (bits - 1)) - 1;
+}
+
 // Scalars shared between the kernels of one backward call; lives at the start
 // of the caller's workspace.
 struct OperandScalars {
@@ -95,10 +100,10 @@ int launch_absmax3(const float* p0, int64_t n0, int abs0, const float* p1, int64
                    lbt_grad_state* st, hipStream_t s);
 int launch_quantize_flat_grad(const float* g, int64_t n, const uint32_t* pmax, int nblocks,
                               lbt_grad_state* st, uint64_t seed, int rounding, int hindsight,
-                              int fused_update, uint8_t* codes, hipStream_t s);
+                              int fused_update, int bits, uint8_t* codes, hipStream_t s);
 int launch_quantize_flat_operand(const float* x, int64_t n, float c_given, const uint32_t* pmax,
-                                 int nblocks, int is_unsigned, uint8_t* codes, float* c_out,
-                                 float* clip_scale_out, hipStream_t s);
+                                 int nblocks, int is_unsigned, int bits, uint8_t* codes,
+                                 float* c_out, float* clip_scale_out, hipStream_t s);
 // Quantize T[A][B][L] (L contiguous) into GEMM layouts of 16-byte granules (16 int8 codes):
 // out_b [A][ceil(B/16)][L][16] and out_a [B][ceil(A/16)][L][16] (either may be null).
 // The tensor maximum, where needed, comes from the partial maxima of launch_absmax3.
@@ -128,6 +133,7 @@ struct LayerTensors {
   int rounding;
   int hindsight;  // gradient interval from the maximum left in *st by the previous call
   int x_unsigned;
+  int bits;       // b for all three tensors
 };
 int launch_quantize_layer(const LayerTensors& q, hipStream_t s);
 int launch_update_interval(lbt_grad_state* st, hipStream_t s);
@@ -137,6 +143,7 @@ int launch_state_init(lbt_grad_state* st, const lbt_grad_state& v, hipStream_t s
 struct ConvGeom {
   int N, C, H, W, K, R, S, P, Q, stride, pad;
   int Np, Kp;  // N and K rounded up to kGranule
+  int bits;    // b of all three code tensors
 };
 // How the long contraction of dW is cut over workgroups.
 struct SplitPlan {

@@ -78,11 +78,11 @@ struct QConst {
   int kmin;      // smallest code
 };
 
-__device__ __forceinline__ QConst make_qconst(float c, bool is_unsigned) {
+__device__ __forceinline__ QConst make_qconst(float c, bool is_unsigned, int bits) {
   QConst k;
   k.c = c;
-  k.q = is_unsigned ? 15 : 7;
-  k.kmin = is_unsigned ? 0 : -7;
+  k.q = levels(bits, is_unsigned);
+  k.kmin = is_unsigned ? 0 : -k.q;
   k.lo = is_unsigned ? 0.0f : -c;
   k.inv_s = (c > 0.0f) ? (float)((double)k.q / (double)c) : 0.0f;
   return k;
@@ -167,6 +167,7 @@ __device__ __forceinline__ uint32_t reduce_partials(const uint32_t* pmax, int nb
 struct GradSetup {
   float gmax, c;
   int status;
+  int bits;
   bool hindsight;
   bool fused_update;  // the workgroup that publishes the statistics also applies Alg. 1
 };
@@ -174,21 +175,22 @@ struct GradSetup {
 // hindsight: the interval comes from the maximum the previous call left in the state; this
 // tensor's own maximum is gathered during the sweep (grad_finish).
 __device__ __forceinline__ GradSetup grad_setup(const lbt_grad_state* st, const uint32_t* pmax,
-                                                int nblocks, bool hindsight = false) {
+                                                int nblocks, int bits, bool hindsight = false) {
   GradSetup g;
+  g.bits = bits;
   g.hindsight = hindsight;
   g.fused_update = false;
-  uint32_t bits;
+  uint32_t mx;
   if (hindsight) {
-    bits = __float_as_uint(st->gmax) & 0x7fffffffu;
-    if (bits >= kInfBits) bits = 0;      // unusable: treated like "no previous maximum"
+    mx = __float_as_uint(st->gmax) & 0x7fffffffu;
+    if (mx >= kInfBits) mx = 0;      // unusable: treated like "no previous maximum"
   } else {
-    bits = reduce_partials(pmax, nblocks, 0);
+    mx = reduce_partials(pmax, nblocks, 0);
   }
-  g.gmax = __uint_as_float(bits);
+  g.gmax = __uint_as_float(mx);
   g.c = 0.0f;
-  if (bits >= kInfBits) g.status = LBT_STATUS_NONFINITE;
-  else if (bits == 0) g.status = LBT_STATUS_ZERO_GRAD;
+  if (mx >= kInfBits) g.status = LBT_STATUS_NONFINITE;
+  else if (mx == 0) g.status = LBT_STATUS_ZERO_GRAD;
   else {
     g.status = LBT_STATUS_OK;
     g.c = (float)__dmul_rn(st->gamma, (double)g.gmax);
@@ -253,7 +255,8 @@ __device__ __forceinline__ void grad_finish(lbt_grad_state* st, const GradSetup&
         st->gmax = g.gmax;
       }
       st->clip = g.c;
-      st->scale = (g.c > 0.0f) ? (float)((double)g.c / 7.0) : 0.0f;
+      st->scale = (g.c > 0.0f) ? (float)((double)g.c / (double)levels(g.bits, false)) : 0.0f;
+      st->bits = g.bits;
       // k_absmax3 has reset the status to OK; an operand quantizer of the same launch
       // may already have flagged a non-finite operand, which must stay
       if (status != LBT_STATUS_OK) atomicCAS(&st->status, LBT_STATUS_OK, status);
@@ -267,7 +270,7 @@ __device__ __forceinline__ void grad_finish(lbt_grad_state* st, const GradSetup&
 __device__ __forceinline__ float operand_setup(float c_given, const uint32_t* pmax, int nblocks,
                                                int col, bool is_unsigned, float* c_out,
                                                uint32_t* bad_out, lbt_grad_state* st,
-                                               float* clip_scale_out, bool first_block) {
+                                               float* clip_scale_out, bool first_block, int bits) {
   float c = c_given;
   bool bad = false;
   if (!(c > 0.0f)) {
@@ -281,7 +284,7 @@ __device__ __forceinline__ float operand_setup(float c_given, const uint32_t* pm
     if (bad && st) st->status = LBT_STATUS_NONFINITE;
     if (clip_scale_out) {
       clip_scale_out[0] = c;
-      clip_scale_out[1] = (c > 0.0f) ? (float)((double)c / (is_unsigned ? 15.0 : 7.0)) : 0.0f;
+      clip_scale_out[1] = (c > 0.0f) ? (float)((double)c / (double)levels(bits, is_unsigned)) : 0.0f;
     }
   }
   return c;
@@ -373,19 +376,20 @@ template <int MODE>
 __global__ __launch_bounds__(kThreads) void k_quantize_flat(
     const float* __restrict__ x, long long n, float c_given, const uint32_t* pmax, int nblocks,
     lbt_grad_state* st, unsigned long long seed, uint8_t* __restrict__ codes, float* c_out,
-    float* clip_scale_out, int hindsight, int fused_update) {
+    float* clip_scale_out, int hindsight, int fused_update, int bits) {
   constexpr bool kGrad = (MODE >= 2);
   GradSetup gs{};
   float c;
   if (kGrad) {
-    gs = grad_setup(st, pmax, nblocks, hindsight != 0);
+    gs = grad_setup(st, pmax, nblocks, bits, hindsight != 0);
     gs.fused_update = fused_update != 0;
     c = gs.c;
   } else {
     c = operand_setup(c_given, pmax, nblocks, 1, MODE == 1, c_out, nullptr, nullptr, clip_scale_out,
-                      blockIdx.x == 0);
+                      blockIdx.x == 0, bits);
   }
-  const QConst qc = make_qconst(c, MODE == 1);
+  const QConst qc = make_qconst(c, MODE == 1, bits);
+  const bool bytes = bits > 4;   // one byte per code instead of one nibble
   const bool live = c > 0.0f;
   const unsigned long long step = (MODE == 3) ? st->step : 0ull;
   const long long groups = (n + 7) / 8;
@@ -405,7 +409,7 @@ __global__ __launch_bounds__(kThreads) void k_quantize_flat(
       for (int j = 0; j < 8; ++j) v[j] = (j < valid) ? x[e0 + j] : 0.0f;
     }
     if (kGrad && gs.hindsight) seen_max = max(seen_max, max_abs_bits8(v));
-    uint32_t word = 0;
+    uint32_t word = 0, lo = 0, hi = 0;   // nibble format; byte format (elements 0-3, 4-7)
     if (live) {
       Philox4 rnd{};
       if (MODE == 3) rnd = philox_block((unsigned long long)gi, step, seed);
@@ -416,9 +420,18 @@ __global__ __launch_bounds__(kThreads) void k_quantize_flat(
         if (j >= valid) { k = 0; c1 = 0; }
         cnt += c1;
         word |= ((uint32_t)k & 0xFu) << (4 * j);
+        if (j < 4) lo |= ((uint32_t)k & 0xFFu) << (8 * j);
+        else hi |= ((uint32_t)k & 0xFFu) << (8 * (j - 4));
       }
     }
-    if (valid == 8) {
+    if (bytes) {
+      if (valid == 8) {
+        reinterpret_cast<uint2*>(codes)[gi] = make_uint2(lo, hi);
+      } else {
+        for (int j = 0; j < valid; ++j)
+          codes[gi * 8 + j] = (uint8_t)((j < 4 ? lo >> (8 * j) : hi >> (8 * (j - 4))) & 0xFFu);
+      }
+    } else if (valid == 8) {
       reinterpret_cast<uint32_t*>(codes)[gi] = word;
     } else {
       const int nbytes = (valid + 1) / 2;
@@ -457,6 +470,7 @@ struct TileArgs {
   uint4* out_a;
   int a_lmajor;
   int hindsight;  // gradient only: interval from the previous call's maximum
+  int bits;       // b of Eq. (2)/(3)
 };
 
 // Phase B: gather granules out of the LDS tile.  `pitch` = bytes per (a,b) row.  A granule
@@ -633,15 +647,15 @@ __device__ __forceinline__ void stream_body(const TileArgs& t, int pitch, int tl
   GradSetup gs{};
   float c;
   if (kGrad) {
-    gs = grad_setup(t.st, t.pmax, t.nblocks, t.hindsight != 0);
+    gs = grad_setup(t.st, t.pmax, t.nblocks, t.bits, t.hindsight != 0);
     c = gs.c;
   } else if (!(t.c_given > 0.0f) && t.c_ptr) {
     c = *t.c_ptr;
   } else {
     c = operand_setup(t.c_given, t.pmax, t.nblocks, t.pmax_col, MODE == 1, t.c_out, t.bad_out, t.st,
-                      nullptr, bc.first);
+                      nullptr, bc.first, t.bits);
   }
-  const QConst qc = make_qconst(c, MODE == 1);
+  const QConst qc = make_qconst(c, MODE == 1, t.bits);
   const bool live = c > 0.0f;
   const unsigned long long step = (MODE == 3) ? t.st->step : 0ull;
   const int l0 = bc.x * tl, b0 = bc.y * 16, a0 = bc.z * 16;
@@ -718,15 +732,15 @@ __device__ __forceinline__ void generic_body(const TileArgs& t, const TileCoord&
   GradSetup gs{};
   float c;
   if (MODE >= 2) {
-    gs = grad_setup(t.st, t.pmax, t.nblocks, t.hindsight != 0);
+    gs = grad_setup(t.st, t.pmax, t.nblocks, t.bits, t.hindsight != 0);
     c = gs.c;
   } else if (!(t.c_given > 0.0f) && t.c_ptr) {
     c = *t.c_ptr;
   } else {
     c = operand_setup(t.c_given, t.pmax, t.nblocks, t.pmax_col, MODE == 1, t.c_out, t.bad_out, t.st,
-                      nullptr, bc.first);
+                      nullptr, bc.first, t.bits);
   }
-  const QConst qc = make_qconst(c, MODE == 1);
+  const QConst qc = make_qconst(c, MODE == 1, t.bits);
   const bool live = c > 0.0f;
   const unsigned long long step = (MODE == 3) ? t.st->step : 0ull;
   const int l0 = bc.x * TL, b0 = bc.y * 16, a0 = bc.z * 16;
@@ -768,15 +782,15 @@ __device__ __forceinline__ void matrix_body(const TileArgs& t, const TileCoord& 
   GradSetup gs{};
   float c;
   if (MODE >= 2) {
-    gs = grad_setup(t.st, t.pmax, t.nblocks, t.hindsight != 0);
+    gs = grad_setup(t.st, t.pmax, t.nblocks, t.bits, t.hindsight != 0);
     c = gs.c;
   } else if (!(t.c_given > 0.0f) && t.c_ptr) {
     c = *t.c_ptr;
   } else {
     c = operand_setup(t.c_given, t.pmax, t.nblocks, t.pmax_col, MODE == 1, t.c_out, t.bad_out, t.st,
-                      nullptr, bc.first);
+                      nullptr, bc.first, t.bits);
   }
-  const QConst qc = make_qconst(c, MODE == 1);
+  const QConst qc = make_qconst(c, MODE == 1, t.bits);
   const bool live = c > 0.0f;
   const unsigned long long step = (MODE == 3) ? t.st->step : 0ull;
   const int b0 = bc.x * 64, a0 = bc.z * 64;
@@ -983,34 +997,34 @@ int launch_absmax3(const float* p0, int64_t n0, int abs0, const float* p1, int64
 
 int launch_quantize_flat_grad(const float* g, int64_t n, const uint32_t* pmax, int nblocks,
                               lbt_grad_state* st, uint64_t seed, int rounding, int hindsight,
-                              int fused_update, uint8_t* codes, hipStream_t s) {
+                              int fused_update, int bits, uint8_t* codes, hipStream_t s) {
   ProfScope prof(KID_FLAT_GRAD, (double)n, s);
   const int grid = flat_grid((n + 7) / 8);
   if (rounding == LBT_ROUND_STOCHASTIC)
     LBT_LAUNCH(k_quantize_flat<3>, dim3(grid), dim3(kThreads), 0, s, g, (long long)n, 0.0f,
                        pmax, nblocks, st, (unsigned long long)seed, codes, (float*)nullptr,
-                       (float*)nullptr, hindsight, fused_update);
+                       (float*)nullptr, hindsight, fused_update, bits);
   else
     LBT_LAUNCH(k_quantize_flat<2>, dim3(grid), dim3(kThreads), 0, s, g, (long long)n, 0.0f,
                        pmax, nblocks, st, (unsigned long long)seed, codes, (float*)nullptr,
-                       (float*)nullptr, hindsight, fused_update);
+                       (float*)nullptr, hindsight, fused_update, bits);
   LBT_LAUNCH_CHECK();
   return LBT_OK;
 }
 
 int launch_quantize_flat_operand(const float* x, int64_t n, float c_given, const uint32_t* pmax,
-                                 int nblocks, int is_unsigned, uint8_t* codes, float* c_out,
+                                 int nblocks, int is_unsigned, int bits, uint8_t* codes, float* c_out,
                                  float* clip_scale_out, hipStream_t s) {
   ProfScope prof(KID_FLAT_OPERAND, (double)n, s);
   const int grid = flat_grid((n + 7) / 8);
   if (is_unsigned)
     LBT_LAUNCH(k_quantize_flat<1>, dim3(grid), dim3(kThreads), 0, s, x, (long long)n,
                        c_given, pmax, nblocks, (lbt_grad_state*)nullptr, 0ull, codes, c_out,
-                       clip_scale_out, 0, 0);
+                       clip_scale_out, 0, 0, bits);
   else
     LBT_LAUNCH(k_quantize_flat<0>, dim3(grid), dim3(kThreads), 0, s, x, (long long)n,
                        c_given, pmax, nblocks, (lbt_grad_state*)nullptr, 0ull, codes, c_out,
-                       clip_scale_out, 0, 0);
+                       clip_scale_out, 0, 0, bits);
   LBT_LAUNCH_CHECK();
   return LBT_OK;
 }
@@ -1040,6 +1054,7 @@ int launch_quantize_layer(const LayerTensors& q, hipStream_t s) {
     fill_tile_args(sg.t, o.x, o.A, o.B, o.L, o.io);
     sg.t.seed = q.seed;
     sg.t.hindsight = (i == 0) ? q.hindsight : 0;
+    sg.t.bits = q.bits;
     sg.t.c_given = o.c_given;
     sg.t.c_out = o.c_out;
     sg.t.bad_out = o.bad_out;

@@ -22,20 +22,33 @@ def unpack_nibbles(packed: np.ndarray, n: int, signed: bool) -> np.ndarray:
     return np.where(out >= 8, out - 16, out) if signed else out
 
 
+def flat_codes(code: np.ndarray, bits: int) -> np.ndarray:
+    """Integer codes -> the ABI's flat byte format (test-side encoder, independent of both
+    paths): nibbles for b <= 4, one byte per code above."""
+    c = np.asarray(code).reshape(-1).astype(np.int64)
+    if bits > 4:
+        return (c & 0xFF).astype(np.uint8)
+    c = c & 0xF
+    if c.size % 2:
+        c = np.concatenate([c, [0]])
+    return (c[0::2] | (c[1::2] << 4)).astype(np.uint8)
+
+
 def quantize_grad(g: np.ndarray, st, seed=0, rounding=0):
     n = g.size
-    codes = torch.full(((n + 1) // 2,), 0xEE, dtype=torch.uint8, device=DEV)
+    bits = ((rounding >> 8) & 15) or 4
+    codes = torch.full((n if bits > 4 else (n + 1) // 2,), 0xEE, dtype=torch.uint8, device=DEV)
     ws = torch.zeros(lbt.lbt_workspace_bytes_quantize(n), dtype=torch.uint8, device=DEV)
     lbt.lbt_quantize_grad(dev(g.reshape(-1)), st, seed, rounding, codes, ws)
     return codes.cpu().numpy()
 
 
-def quantize_operand(x: np.ndarray, c: float, unsigned: bool):
+def quantize_operand(x: np.ndarray, c: float, unsigned: bool, bits: int = 4):
     n = x.size
-    codes = torch.full(((n + 1) // 2,), 0xEE, dtype=torch.uint8, device=DEV)
+    codes = torch.full((n if bits > 4 else (n + 1) // 2,), 0xEE, dtype=torch.uint8, device=DEV)
     cs = torch.zeros(2, dtype=torch.float32, device=DEV)
     ws = torch.zeros(lbt.lbt_workspace_bytes_quantize(n), dtype=torch.uint8, device=DEV)
-    lbt.lbt_quantize_operand(dev(x.reshape(-1)), c, unsigned, 4, codes, cs, ws)
+    lbt.lbt_quantize_operand(dev(x.reshape(-1)), c, unsigned, bits, codes, cs, ws)
     return codes.cpu().numpy(), cs.cpu().numpy()
 
 
@@ -81,7 +94,7 @@ def backward_conv2d(X, W, dY, stride, pad, st, c_x=0.0, x_unsigned=True, c_w=0.0
 def assert_state_equal(h, o):
     """Device state (binding.GradState) vs oracle.GradState, bit for bit."""
     assert h.status == o.status, (h.status, o.status)
-    assert h.n_total == o.n_total
+    assert h.n_total == o.n_total and h.bits == o.bits
     if o.status == 1:
         return
     assert h.n_out == o.n_out, (h.n_out, o.n_out)

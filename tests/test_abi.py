@@ -54,7 +54,8 @@ def test_host_validation_rejects_without_gpu(lib):
     # these return before any HIP call
     assert lib.lbt_update_interval(None, None) == -1
     assert lib.lbt_quantize_grad(None, 8, None, 0, 0, None, None, 0, None) == -1
-    assert lib.lbt_state_init(C.c_void_p(256), 1.0, 1e-3, 1e-3, 1e-3, 1.0, 5, None) == -3
+    assert lib.lbt_state_init(C.c_void_p(256), 1.0, 1e-3, 1e-3, 1e-3, 1.0, 9, None) == -3
+    assert lib.lbt_state_init(C.c_void_p(256), 1.0, 1e-3, 1e-3, 1e-3, 1.0, 1, None) == -3
     assert lib.lbt_state_init(C.c_void_p(256), 2.0, 1e-3, 1e-3, 1e-3, 1.0, 4, None) == -2
     p = C.c_void_p(4096)
     big = 1 << 20
@@ -74,6 +75,11 @@ def test_host_validation_rejects_without_gpu(lib):
                                  p, p, p, need, None)
     assert rc == -2
     assert lib.lbt_workspace_bytes_linear(256, 512, 512) > 0
+    # bit-width field of the flag word: 2..8, and no unsigned 8-bit activations for dW
+    for flags, want in ((9 << 8, -3), (1 << 8, -3), (8 << 8, -3), (1 << 12, -3)):
+        rc = lib.lbt_backward_conv2d(p, p, p, 4, 16, 12, 12, 32, 3, 3, 1, 1, 0.0, 1, 0.0, p, 0,
+                                     flags, p, p, p, need, None)
+        assert rc == want, (flags, rc)
 
 
 def test_workspace_formula(lib):
