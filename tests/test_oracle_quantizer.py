@@ -335,3 +335,37 @@ def test_hindsight_degenerate_cases():
     bad[3] = np.inf
     oracle.quantize_grad(bad, st, 0, 0, hindsight=True)
     assert st.status == oracle.NONFINITE and st.gmax == np.float32(1.0)   # maximum kept
+
+
+# -- other bit-widths (Sec. 4.2 sweeps b = 4, 5, 6, 8) ------------------------------------------
+@pytest.mark.parametrize("bits", [2, 5, 6, 7, 8])
+def test_unsigned_range_and_error_bound_other_bits(bits):
+    r = synth.rng(0, 91, bits, synth.T_X)
+    x = synth.normal(r, (20000,))
+    c = np.float32(1.5)
+    q = 2 ** bits - 1
+    code, _ = oracle.quantize(x, c, bits, True)
+    assert code.min() == 0 and code.max() == q == oracle.levels(bits, True)
+    s = oracle.scale(c, bits, True)
+    assert s == pytest.approx(1.5 / q, rel=1e-15)
+    x64 = x.astype(np.float64)
+    inside = (x64 >= 0) & (x64 <= 1.5)
+    assert np.all(np.abs(x64 - s * code)[inside] <= s / 2 * (1 + 1e-4))      # Eq. 3 + Eq. 4
+    # signed, same tensor: half-step bound inside the interval, ends outside (Eq. 2)
+    code, n_out = oracle.quantize(x, c, bits, False)
+    s = oracle.scale(c, bits)
+    inside = np.abs(x64) <= 1.5
+    assert np.all(np.abs(x64 - s * code)[inside] <= s / 2 * (1 + 1e-4))
+    assert np.all(np.abs(code[~inside]) == 2 ** (bits - 1) - 1) and n_out == int((~inside).sum())
+
+
+@pytest.mark.parametrize("bits", [2, 5, 6, 8])
+def test_update_threshold_uses_two_to_the_b_minus_one(bits):
+    # Eq. 16: the sign changes where N(G_out)/N(G) crosses alpha / (2^b - 1)
+    levels = 2 ** bits - 1
+    n_total = 1000 * levels * 1000          # alpha * N / (2^b - 1) = 1000 exactly
+    for n_out, want in ((999, -1), (1000, 0), (1001, 1)):
+        st = oracle.GradState(gamma=0.5, alpha=1e-3, beta=1e-3, bits=bits)
+        st.n_out, st.n_total, st.status = n_out, n_total, oracle.OK
+        assert oracle.update_interval(st) == want
+        assert st.gamma == pytest.approx(0.5 + 1e-3 * want, abs=1e-15)
