@@ -5,7 +5,8 @@ from the paper (Kim et al., "Toward INT4 Fixed-Point Training via Exploring
 Quantization Error for Gradients"): the uniform quantizer of Eq. (1)-(4), the
 gradient clip value c_g = gamma * g_max of Sec. 3.1, the clip-out count and the
 clipping-factor update of Eq. (15)-(16) / Alg. 1, and the two integer
-contractions of the backward pass with the denormalisation of Eq. (4).
+contractions of the backward pass with the denormalisation of Eq. (4); also the
+quantized forward product Y = Q(X) . Q(W) of the same layers (numpy int64).
 
 Only tests, the smoke entry and the benchmark's cpu_baseline leg may import
 this package.  It shares nothing with the HIP path and imports nothing from it.
@@ -396,3 +397,89 @@ def backward_conv2d(X, W, dY, stride: int, pad: int, st: GradState, c_x: float =
     return BackwardResult(qG, qX, qW, s_g, s_x, s_w, acc_dx, acc_dw,
                           dequant(acc_dx, s_g, s_w) if want_dx else None,
                           dequant(acc_dw, s_x, s_g) if want_dw else None)
+
+
+# ----------------------------------------------------------------------------
+# quantized forward pass (Sec. 3.1: weights and activations quantized with Eq. 2 / 3 before
+# the layer's product; Eq. 4 denormalises the integer result).  Written out as the plain
+# definition in numpy int64: Y = s_x s_w * sum qX qW.
+# ----------------------------------------------------------------------------
+def linear_fwd(qX, qW):
+    """acc[m, n] = sum_k qX[m, k] * qW[k, n]."""
+    qX, qW = np.asarray(qX, dtype=np.int64), np.asarray(qW, dtype=np.int64)
+    assert qX.shape[1] == qW.shape[0]
+    return qX @ qW
+
+
+def conv2d_fwd(qX, qW, stride: int, pad: int):
+    """Cross-correlation with zero padding:
+    acc[n, k, p, q] = sum_{c, r, s} qW[k, c, r, s] * qX[n, c, p*stride - pad + r, q*stride - pad + s]."""
+    qX, qW = np.asarray(qX, dtype=np.int64), np.asarray(qW, dtype=np.int64)
+    N, Cc, H, W, K, R, S, P, Q = _conv_dims(qX.shape, qW.shape, stride, pad)
+    xp = np.zeros((N, Cc, H + 2 * pad, W + 2 * pad), dtype=np.int64)
+    xp[:, :, pad:pad + H, pad:pad + W] = qX
+    acc = np.zeros((N, K, P, Q), dtype=np.int64)
+    for r in range(R):
+        for s in range(S):
+            window = xp[:, :, r:r + stride * (P - 1) + 1:stride, s:s + stride * (Q - 1) + 1:stride]
+            acc += np.einsum("ncpq,kc->nkpq", window, qW[:, :, r, s])
+    return acc
+
+
+def conv2d_fwd_at(qX, qW, stride: int, pad: int, flat_idx):
+    """The same sum for single output positions (flat indices into [N, K, P, Q]), one by one."""
+    qX, qW = np.asarray(qX), np.asarray(qW)
+    N, Cc, H, W, K, R, S, P, Q = _conv_dims(qX.shape, qW.shape, stride, pad)
+    out = np.empty(len(flat_idx), dtype=np.int64)
+    for i, f in enumerate(np.asarray(flat_idx, dtype=np.int64)):
+        n, k, p, q = np.unravel_index(int(f), (N, K, P, Q))
+        total = 0
+        for r in range(R):
+            h = p * stride - pad + r
+            if h < 0 or h >= H:
+                continue
+            for s in range(S):
+                w = q * stride - pad + s
+                if w < 0 or w >= W:
+                    continue
+                total += int(np.dot(qW[k, :, r, s].astype(np.int64), qX[n, :, h, w].astype(np.int64)))
+        out[i] = total
+    return out
+
+
+@dataclass
+class ForwardResult:
+    qX: np.ndarray
+    qW: np.ndarray
+    s_x: float
+    s_w: float
+    status: int
+    acc: np.ndarray | None
+    Y: np.ndarray | None
+
+
+def _forward_operands(X, W, c_x, x_unsigned, c_w, bits):
+    qX, _, s_x, sx_status = quantize_operand(X, c_x, bool(x_unsigned), bits)
+    qW, _, s_w, sw_status = quantize_operand(W, c_w, False, bits)
+    status = NONFINITE if NONFINITE in (sx_status, sw_status) else OK
+    return qX, qW, s_x, s_w, status
+
+
+def forward_linear(X, W, c_x: float = 0.0, x_unsigned: bool = False, c_w: float = 0.0,
+                   bits: int = 4):
+    """X[M,K], W[K,N]: Y = Q(X) . Q(W), denormalised."""
+    qX, qW, s_x, s_w, status = _forward_operands(X, W, c_x, x_unsigned, c_w, bits)
+    if status != OK:
+        return ForwardResult(qX, qW, s_x, s_w, status, None, None)
+    acc = linear_fwd(qX, qW)
+    return ForwardResult(qX, qW, s_x, s_w, status, acc, dequant(acc, s_x, s_w))
+
+
+def forward_conv2d(X, W, stride: int, pad: int, c_x: float = 0.0, x_unsigned: bool = True,
+                   c_w: float = 0.0, bits: int = 4):
+    """X[N,C,H,W], W[K,C,R,S]: Y[N,K,P,Q] = conv(Q(X), Q(W)), denormalised."""
+    qX, qW, s_x, s_w, status = _forward_operands(X, W, c_x, x_unsigned, c_w, bits)
+    if status != OK:
+        return ForwardResult(qX, qW, s_x, s_w, status, None, None)
+    acc = conv2d_fwd(qX, qW, stride, pad)
+    return ForwardResult(qX, qW, s_x, s_w, status, acc, dequant(acc, s_x, s_w))
