@@ -50,6 +50,9 @@ def parse():
     ap.add_argument("--separate-update", action="store_true",
                     help="apply the interval update with lbt_update_interval after every layer "
                          "instead of inside the backward call (LBT_FUSED_UPDATE)")
+    ap.add_argument("--forward", action="store_true",
+                    help="time the quantized forward pass Y = Q(X).Q(W) of the same layers instead "
+                         "of the backward pass (a separate measurement, never the headline)")
     ap.add_argument("--single-sweep", action="store_true",
                     help="extra mode, not the paper's quantizer: the gradient interval comes "
                          "from the previous step's maximum, so dY is read once (needs "
@@ -94,11 +97,25 @@ class LayerRun:
         self.state = None
         self.seed = 1000 + idx
 
-    def ws_bytes(self, lbt):
+    def ws_bytes(self, lbt, forward=False):
         s = self.spec
+        if forward:
+            if self.is_linear:
+                return lbt.lbt_workspace_bytes_forward_linear(s.M, s.K, s.N)
+            return lbt.lbt_workspace_bytes_forward_conv2d(s.N, s.C, s.H, s.W, s.K, s.R, s.S,
+                                                          s.stride, s.pad)
         if self.is_linear:
             return lbt.lbt_workspace_bytes_linear(s.M, s.K, s.N)
         return lbt.lbt_workspace_bytes_conv2d(s.N, s.C, s.H, s.W, s.K, s.R, s.S, s.stride, s.pad)
+
+    def run_forward(self, lbt, ws, flags):
+        s = self.spec
+        if self.is_linear:
+            lbt.lbt_forward_linear(self.X, self.W, s.M, s.K, s.N, 0.0, self.x_unsigned, 0.0, flags,
+                                   self.Y, None, None, ws)
+        else:
+            lbt.lbt_forward_conv2d(self.X, self.W, s.N, s.C, s.H, s.W, s.K, s.R, s.S, s.stride,
+                                   s.pad, 0.0, self.x_unsigned, 0.0, flags, self.Y, None, None, ws)
 
     def run(self, lbt, ws, rounding):
         """One layer's backward and its interval update (inside the call when `rounding`
@@ -224,13 +241,22 @@ def main():
                                    x_unsigned=not vit and args.bits < 8))
     for L in layers:
         L.state = lbt.new_state(gamma0=args.gamma0, bits=args.bits)
-    ws = torch.zeros(max(L.ws_bytes(lbt) for L in layers), dtype=torch.uint8, device="cuda")
+    ws = torch.zeros(max(L.ws_bytes(lbt, args.forward) for L in layers), dtype=torch.uint8,
+                     device="cuda")
     gemm_ops = sum(2.0 * L.spec.gemm_ops for L in layers)       # dX and dW
+    if args.forward:
+        gemm_ops /= 2.0                                          # one product per layer
+        for L in layers:
+            L.Y = torch.empty_like(L.dY)
+            L.dX = L.dW = None
     n_grad = sum(L.dY.numel() for L in layers)
 
     def step():
         for L in layers:
-            L.run(lbt, ws, rounding)
+            if args.forward:
+                L.run_forward(lbt, ws, lbt.BITS(args.bits))
+            else:
+                L.run(lbt, ws, rounding)
 
     for _ in range(args.warmup):
         step()
@@ -253,6 +279,8 @@ def main():
                                   args.rounding, args.gamma0),
                    "gemm_GOP_per_step": gemm_ops / 1e9, "grad_elements_per_step": n_grad},
     }
+    if args.forward:
+        out["config"]["workload"] += ", FORWARD pass Y = Q(X).Q(W) only"
     if args.single_sweep:
         out["config"]["workload"] += ", single-sweep mode (interval from the previous step's maximum)"
 
@@ -308,7 +336,7 @@ def main():
         # quantized element
         q, am = kernels.get("k_quantize_layer"), kernels.get("k_absmax3")
         if q and am:
-            n_all = n_grad + sum(L.X.numel() + L.W.numel() for L in layers)
+            n_all = (0 if args.forward else n_grad) + sum(L.X.numel() + L.W.numel() for L in layers)
             t_ms = q["ms_per_step"] + am["ms_per_step"]
             if "k_quantize_grad" in kernels:     # large gradients have a launch of their own
                 t_ms += kernels["k_quantize_grad"]["ms_per_step"]
@@ -326,13 +354,15 @@ def main():
             for L in layers:
                 ops = L.spec.gemm_ops
                 nx, nw, ng = L.X.numel(), L.W.numel(), L.dY.numel()
-                for byts in (0.5 * ng + 0.5 * nw + 4.0 * nx, 0.5 * nx + 0.5 * ng + 4.0 * nw):
+                products = ((0.5 * nx + 0.5 * nw + 4.0 * ng,) if args.forward else
+                            (0.5 * ng + 0.5 * nw + 4.0 * nx, 0.5 * nx + 0.5 * ng + 4.0 * nw))
+                for byts in products:
                     t_roof += max(ops / (PEAK_INT8_TOPS * 1e12), byts / (PEAK_HBM_GBPS * 1e9))
             out["contractions"] = {"TOPS": tops, "frac_of_int8_peak": tops / PEAK_INT8_TOPS,
                                    "ms_per_step": t_ms, "roofline_ms_per_step": t_roof * 1e3,
                                    "frac_of_layer_rooflines": t_roof * 1e3 / t_ms}
 
-    if not args.no_cpu_baseline and not args.single_sweep:   # the oracle is timed on the paper's mode
+    if not args.no_cpu_baseline and not args.single_sweep and not args.forward:   # the oracle is timed on the paper's mode
         out["cpu_baseline"] = cpu_baseline(layers, rounding & lbt.ROUND_STOCHASTIC, args.bits)
 
     print(json.dumps(out))

@@ -190,6 +190,32 @@ size_t lbt_workspace_bytes_conv2d(int64_t N, int64_t C, int64_t H, int64_t Wd, i
                                   int64_t R, int64_t S, int64_t stride, int64_t pad);
 
 /*
+ * Quantized forward pass of the same layers (Sec. 3.1: weights and activations go through
+ * Eq. 2 / Eq. 3 before the product, Eq. 4 after it):
+ *   linear: Y[M,N_out] = s_x s_w * sum_k qX[m,k] qW[k,n]       X[M,K_in], W[K_in,N_out]
+ *   conv:   Y[n,k,p,q] = s_x s_w * sum_{c,r,s} qW[k,c,r,s] qX[n,c,p*stride-pad+r,q*stride-pad+s]
+ *           (zero outside the image; X[N,C,H,Wd], W[K,C,R,S], Y[N,K,P,Q])
+ * X and W through the operand quantizer (nearest rounding) with clip values c_x, c_w (<= 0:
+ * the tensor's maximum); x_unsigned selects Eq. (3) for X.  `flags`: 0 or LBT_BITS(b).
+ * acc_Y (may be NULL, shaped like Y): the raw int32 sums.  status (device, may be NULL)
+ * receives LBT_STATUS_OK, or LBT_STATUS_NONFINITE when a tensor whose maximum was taken
+ * holds NaN / Inf (its codes are then all 0, so Y is 0).  The sums are exact:
+ * LBT_ERR_OVERFLOW if K_in (C*R*S) * q * q_x could reach 2^31; LBT_ERR_UNSUPPORTED for
+ * unsigned X at b = 8.  The codes stay in the workspace only: the backward call quantizes
+ * X and W again in the layouts its own products read.
+ */
+int lbt_forward_linear(const float* X, const float* W, int64_t M, int64_t K_in, int64_t N_out,
+                       float c_x, int x_unsigned, float c_w, int flags, float* Y, int32_t* acc_Y,
+                       int32_t* status, void* ws, size_t ws_bytes, void* stream);
+size_t lbt_workspace_bytes_forward_linear(int64_t M, int64_t K_in, int64_t N_out);
+int lbt_forward_conv2d(const float* X, const float* W, int64_t N, int64_t C, int64_t H, int64_t Wd,
+                       int64_t K, int64_t R, int64_t S, int64_t stride, int64_t pad, float c_x,
+                       int x_unsigned, float c_w, int flags, float* Y, int32_t* acc_Y,
+                       int32_t* status, void* ws, size_t ws_bytes, void* stream);
+size_t lbt_workspace_bytes_forward_conv2d(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K,
+                                          int64_t R, int64_t S, int64_t stride, int64_t pad);
+
+/*
  * The same two calls with the raw int32 accumulators also written out
  * (acc_dX shaped like dX, acc_dW like dW; either may be NULL).  For checking
  * the integer sums bit for bit.  LBT_ERR_OVERFLOW if the worst case of a whole sum (not

@@ -74,6 +74,12 @@ SIGNATURES = {
                                        _int, _p, _p, _p, _p, _p, _sz, _p]),
     "lbt_backward_conv2d_acc": (_int, [_p, _p, _p] + [_i64] * 9 + [_f32, _int, _f32, _p, _u64, _int,
                                                                    _p, _p, _p, _p, _p, _sz, _p]),
+    "lbt_forward_linear": (_int, [_p, _p, _i64, _i64, _i64, _f32, _int, _f32, _int, _p, _p, _p, _p,
+                                  _sz, _p]),
+    "lbt_workspace_bytes_forward_linear": (_sz, [_i64, _i64, _i64]),
+    "lbt_forward_conv2d": (_int, [_p, _p] + [_i64] * 9 + [_f32, _int, _f32, _int, _p, _p, _p, _p,
+                                                          _sz, _p]),
+    "lbt_workspace_bytes_forward_conv2d": (_sz, [_i64] * 9),
     "lbt_profile_enable": (_int, [_int]),
     "lbt_profile_kernel_count": (_int, []),
     "lbt_profile_kernel_name": (C.c_char_p, [_int]),
@@ -215,6 +221,29 @@ def lbt_backward_conv2d_acc(X, W, dY, N, Cc, H, Wd, K, R, S, stride, pad, c_x, x
                                           pad, c_x, int(x_unsigned), c_w, _dp(st), seed, rounding,
                                           _dp(dX), _dp(dW), _dp(acc_dX), _dp(acc_dW), wp, wb,
                                           _stream()), "lbt_backward_conv2d_acc")
+
+
+def lbt_workspace_bytes_forward_linear(M, K_in, N_out) -> int:
+    return load().lbt_workspace_bytes_forward_linear(M, K_in, N_out)
+
+
+def lbt_workspace_bytes_forward_conv2d(N, Cc, H, W, K, R, S, stride, pad) -> int:
+    return load().lbt_workspace_bytes_forward_conv2d(N, Cc, H, W, K, R, S, stride, pad)
+
+
+def lbt_forward_linear(X, W, M, K_in, N_out, c_x, x_unsigned, c_w, flags, Y, acc_Y, status, ws):
+    wp, wb = _ws_args(ws)
+    _check(load().lbt_forward_linear(_dp(X), _dp(W), M, K_in, N_out, c_x, int(x_unsigned), c_w,
+                                     flags, _dp(Y), _dp(acc_Y), _dp(status), wp, wb, _stream()),
+           "lbt_forward_linear")
+
+
+def lbt_forward_conv2d(X, W, N, Cc, H, Wd, K, R, S, stride, pad, c_x, x_unsigned, c_w, flags, Y,
+                       acc_Y, status, ws):
+    wp, wb = _ws_args(ws)
+    _check(load().lbt_forward_conv2d(_dp(X), _dp(W), N, Cc, H, Wd, K, R, S, stride, pad, c_x,
+                                     int(x_unsigned), c_w, flags, _dp(Y), _dp(acc_Y), _dp(status),
+                                     wp, wb, _stream()), "lbt_forward_conv2d")
 
 
 def lbt_profile_enable(on: bool):

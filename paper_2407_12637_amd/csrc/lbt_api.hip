@@ -147,6 +147,68 @@ int backward_common(const float* X, const float* W, const float* dY, ConvGeom g,
   return LBT_OK;
 }
 
+// Forward product: maxima where no clip value is given, both operands quantized in one
+// launch into the layouts the product reads, then the product.
+//   linear: X as T[M][K_in][1] -> [M][Kin_p/16][16]; W as T[K_in][N_out][1] -> [N_out][Kin_p/16][16]
+//   conv:   X as T[N][C][H*W]  -> [N][Cp/16][H*W][16]; W as T[K][C][R*S] -> [K][R*S][Cp/16][16]
+struct ForwardWorkspace {
+  size_t off_x, off_w, total;
+};
+ForwardWorkspace forward_workspace(const ConvGeom& g) {
+  ForwardWorkspace w;
+  const size_t cp = (size_t)round_up(g.C, kGranule);
+  size_t o = kWsHeaderBytes;
+  w.off_x = o;
+  o += pad256((size_t)g.N * g.H * g.W * cp);
+  w.off_w = o;
+  o += pad256((size_t)g.K * g.R * g.S * cp);
+  w.total = o;
+  return w;
+}
+
+int forward_common(const float* X, const float* W, ConvGeom g, bool is_linear, float c_x,
+                   int x_unsigned, float c_w, int flags, float* Y, int32_t* acc_Y, int32_t* status,
+                   void* ws, size_t ws_bytes, void* stream) {
+  if (!X || !W || !Y || !ws) return LBT_ERR_NULL;
+  int bits;
+  if ((flags & ~LBT_BITS(15)) || !split_flags(flags, &bits)) return LBT_ERR_UNSUPPORTED;
+  if (x_unsigned && bits == 8) return LBT_ERR_UNSUPPORTED;
+  g.bits = bits;
+  if (!aligned(X, 16) || !aligned(W, 16) || !aligned(Y, 16) || !aligned(ws, 256) ||
+      (acc_Y && !aligned(acc_Y, 16)) || (status && !aligned(status, 4)))
+    return LBT_ERR_ALIGN;
+  const ForwardWorkspace lay = forward_workspace(g);
+  if (ws_bytes < lay.total) return LBT_ERR_WORKSPACE;
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  uint8_t* base = static_cast<uint8_t*>(ws);
+  OperandScalars* sc = reinterpret_cast<OperandScalars*>(base);
+  uint32_t* pmax = reinterpret_cast<uint32_t*>(base + kWsScalarsBytes);
+  uint8_t* x_codes = base + lay.off_x;
+  uint8_t* w_codes = base + lay.off_w;
+  const int64_t HW = (int64_t)g.H * g.W, RS = (int64_t)g.R * g.S;
+  const int64_t n_x = (int64_t)g.N * g.C * HW, n_w = (int64_t)g.K * g.C * RS;
+  int rc, nblocks = 0;
+  if ((rc = launch_absmax3(nullptr, 0, 0, !(c_x > 0.0f) ? X : nullptr, n_x, x_unsigned ? 0 : 1,
+                           !(c_w > 0.0f) ? W : nullptr, n_w, 1, pmax, &nblocks, nullptr, s)))
+    return rc;
+  LayerTensors q{};
+  q.rounding = LBT_ROUND_NEAREST;
+  q.x_unsigned = x_unsigned;
+  q.bits = bits;
+  q.tensor[1] = {X, g.N, g.C, HW, RelayoutIo{pmax, nblocks, 1, nullptr, x_codes, nullptr, 0, 0},
+                 c_x, &sc->c_x, &sc->bad_x};
+  if (is_linear)   // W[K_in][N_out]: rows of W^T, sixteen consecutive k_in per granule
+    q.tensor[2] = {W, g.C, g.K, 1, RelayoutIo{pmax, nblocks, 2, nullptr, nullptr, w_codes, 0, 0},
+                   c_w, &sc->c_w, &sc->bad_w};
+  else             // W[K][C][R*S]: tap-major rows, sixteen consecutive c per granule
+    q.tensor[2] = {W, g.K, g.C, RS, RelayoutIo{pmax, nblocks, 2, nullptr, w_codes, nullptr, 0, 1},
+                   c_w, &sc->c_w, &sc->bad_w};
+  if ((rc = launch_quantize_layer(q, s))) return rc;
+  return is_linear ? launch_linear_fwd(g.N, g.C, g.K, bits, x_codes, w_codes, sc, x_unsigned, Y, acc_Y,
+                                       status, s)
+                   : launch_conv_fwd(g, w_codes, x_codes, sc, x_unsigned, Y, acc_Y, status, s);
+}
+
 }  // namespace
 
 extern "C" {
@@ -266,6 +328,40 @@ size_t lbt_workspace_bytes_linear(int64_t M, int64_t K_in, int64_t N_out) {
   ConvGeom g;
   if (make_geom(M, K_in, 1, 1, N_out, 1, 1, 1, 0, &g) != LBT_OK) return 0;
   return conv_workspace(g, true).total;
+}
+
+size_t lbt_workspace_bytes_forward_conv2d(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K,
+                                          int64_t R, int64_t S, int64_t stride, int64_t pad) {
+  ConvGeom g;
+  if (make_geom(N, C, H, Wd, K, R, S, stride, pad, &g) != LBT_OK) return 0;
+  return forward_workspace(g).total;
+}
+
+size_t lbt_workspace_bytes_forward_linear(int64_t M, int64_t K_in, int64_t N_out) {
+  ConvGeom g;
+  if (make_geom(M, K_in, 1, 1, N_out, 1, 1, 1, 0, &g) != LBT_OK) return 0;
+  return forward_workspace(g).total;
+}
+
+int lbt_forward_conv2d(const float* X, const float* W, int64_t N, int64_t C, int64_t H, int64_t Wd,
+                       int64_t K, int64_t R, int64_t S, int64_t stride, int64_t pad, float c_x,
+                       int x_unsigned, float c_w, int flags, float* Y, int32_t* acc_Y,
+                       int32_t* status, void* ws, size_t ws_bytes, void* stream) {
+  ConvGeom g;
+  const int rc = make_geom(N, C, H, Wd, K, R, S, stride, pad, &g);
+  if (rc) return rc;
+  return forward_common(X, W, g, false, c_x, x_unsigned, c_w, flags, Y, acc_Y, status, ws, ws_bytes,
+                        stream);
+}
+
+int lbt_forward_linear(const float* X, const float* W, int64_t M, int64_t K_in, int64_t N_out,
+                       float c_x, int x_unsigned, float c_w, int flags, float* Y, int32_t* acc_Y,
+                       int32_t* status, void* ws, size_t ws_bytes, void* stream) {
+  ConvGeom g;
+  const int rc = make_geom(M, K_in, 1, 1, N_out, 1, 1, 1, 0, &g);
+  if (rc) return rc;
+  return forward_common(X, W, g, true, c_x, x_unsigned, c_w, flags, Y, acc_Y, status, ws, ws_bytes,
+                        stream);
 }
 
 int lbt_backward_conv2d_acc(const float* X, const float* W, const float* dY, int64_t N, int64_t C,

@@ -62,6 +62,9 @@ struct GemmArgs {
   int epi;            // 0 = scaled store to NCHW dX, 1 = int32 partial tile (split K),
                       // 2 = scaled store row-major
   int scale_kind;     // 0: s_g*s_w   1: s_x*s_g (signed x)   2: s_x*s_g (unsigned x)
+                      // 3: s_x*s_w (signed x)   4: s_x*s_w (unsigned x): forward product
+  int fwd;            // MODE 0 gathers input pixels of a forward convolution (see the tap table)
+  int32_t* status_out;  // forward product: receives LBT_STATUS_OK / NONFINITE of its operands
   int bits;           // b: the codes' scales are c / levels(b)
   int N, C, H, W, K, R, S, P, Q, stride, pad;
   int inner;          // MODE 1: chunk t = group * inner + pos, inner = P*Q (1 for linear)
@@ -93,6 +96,9 @@ __device__ __forceinline__ void wait_loads() {
 
 __device__ __forceinline__ float output_scale(const GemmArgs& g) {
   const double q_signed = (double)levels(g.bits, false);
+  if (g.scale_kind >= 3)
+    return (float)(((double)g.sc->c_x / (g.scale_kind == 4 ? (double)levels(g.bits, true) : q_signed)) *
+                   ((double)g.sc->c_w / q_signed));
   const double s_g = (double)g.st->clip / q_signed;
   double other;
   if (g.scale_kind == 0) other = (double)g.sc->c_w / q_signed;
@@ -124,6 +130,8 @@ __global__ __launch_bounds__(kThreads) void k_implicit_gemm(const GemmArgs g) {
   if (lid >= g.total_blocks) return;
   // (the products read only the clip value from the state: no order to keep with this)
   if (g.update_st && blockIdx.x == 0 && threadIdx.x == 0) interval_update(g.update_st);
+  if (g.status_out && blockIdx.x == 0 && threadIdx.x == 0)
+    *g.status_out = (g.sc->bad_x | g.sc->bad_w) ? LBT_STATUS_NONFINITE : LBT_STATUS_OK;
   const int m_tile = lid % g.tiles_m;
   const int n_tile = (lid / g.tiles_m) % g.tiles_n;
   const int split = lid / (g.tiles_m * g.tiles_n);
@@ -206,9 +214,15 @@ __global__ __launch_bounds__(kThreads) void k_implicit_gemm(const GemmArgs g) {
       int fr = 0, fs = tid / BN;
       while (fs >= g.S) { fs -= g.S; ++fr; }
       for (int tap = tid / BN; tap < RS; tap += SUB) {
-        const int hp = h_ + g.pad - fr, wq = w_ + g.pad - fs;
+        int hp = h_ + g.pad - fr, wq = w_ + g.pad - fs;
         int off = -1;
-        if (ok && hp >= 0 && wq >= 0) {
+        if (g.fwd) {
+          // forward: column (h_, w_) is an OUTPUT pixel, the table points at the input pixel
+          // under tap (fr, fs); g.P x g.Q is the input image here
+          hp = h_ * g.stride - g.pad + fr;
+          wq = w_ * g.stride - g.pad + fs;
+          if (ok && hp >= 0 && wq >= 0 && hp < g.P && wq < g.Q) off = (hp * g.Q + wq) * 16;
+        } else if (ok && hp >= 0 && wq >= 0) {
           int p, q;
           bool on_grid;
           if (g.stride == 1) {
@@ -488,7 +502,9 @@ int launch_one(const GemmArgs& g, unsigned grid, size_t tap_bytes, hipStream_t s
 
 int run_gemm(GemmArgs& g, int mode, int bm, int bn, int splits, int kid, hipStream_t s) {
   // algorithmic work: the convolution's multiply-adds, padding taps included
-  const double work = 2.0 * g.N * g.P * g.Q * (double)g.K * g.C * g.R * g.S;
+  // (the convolution's output image is P x Q, except in the forward product's geometry)
+  const double out_px = g.fwd ? (double)g.H * g.W : (double)g.P * g.Q;
+  const double work = 2.0 * g.N * out_px * (double)g.K * g.C * g.R * g.S;
   ProfScope prof(kid, work, s);
   // 32-bit buffer offsets: both code tensors below 2 GiB, with room for the rows of a
   // ragged last tile
@@ -553,16 +569,17 @@ void pick_tile(int M, int NJ, int splits, int* bm, int* bn) {
   }
 }
 
-// Direct (no split) product with signed operands: |sum| <= chunks * 16 * q * q < 2^31.
-int run_direct(GemmArgs& g, int mode, hipStream_t s) {
+// Direct (no split) product: |sum| <= chunks * 16 * q * q' < 2^31 (q' = the unsigned range
+// when the forward product reads unsigned activations).
+int run_direct(GemmArgs& g, int mode, int scale_kind, int kid, hipStream_t s) {
   g.steps = (g.chunks + BKC - 1) / BKC;
   g.steps_per_split = g.steps;
-  g.scale_kind = 0;
-  const long long q = levels(g.bits, false);
-  if ((long long)g.chunks * 16 * q * q >= (1ll << 31)) return LBT_ERR_OVERFLOW;
+  g.scale_kind = scale_kind;
+  const long long q = levels(g.bits, false), q2 = levels(g.bits, scale_kind == 4);
+  if ((long long)g.chunks * 16 * q * q2 >= (1ll << 31)) return LBT_ERR_OVERFLOW;
   int bm, bn;
   pick_tile(g.M, g.NJ, 1, &bm, &bn);
-  return run_gemm(g, mode, bm, bn, 1, KID_GEMM_DX, s);
+  return run_gemm(g, mode, bm, bn, 1, kid, s);
 }
 
 int run_splitk(GemmArgs& g, bool x_unsigned, long long true_k, int32_t* acc, int32_t* partial,
@@ -686,7 +703,78 @@ int launch_conv_dx(const ConvGeom& c, const uint8_t* w_codes, const uint8_t* g_c
   g.epi = 0;
   g.st = st; g.sc = sc; g.update_st = update_st;
   g.out = dX; g.acc = acc;
-  return run_direct(g, 0, s);
+  return run_direct(g, 0, 0, KID_GEMM_DX, s);
+}
+
+// Forward convolution through the same gather kernel: rows are output channels, columns
+// output pixels (n, p, q), the contraction walks (tap, input-channel group).
+//   A = W codes [K][R*S][Cp/16][16], B = X codes [N][Cp/16][H*W][16]; out/acc [N][K][P][Q].
+int launch_conv_fwd(const ConvGeom& c, const uint8_t* w_codes, const uint8_t* x_codes,
+                    const OperandScalars* sc, int x_unsigned, float* Y, int32_t* acc,
+                    int32_t* status_out, hipStream_t s) {
+  GemmArgs g{};
+  g.N = c.N; g.R = c.R; g.S = c.S; g.stride = c.stride; g.pad = c.pad; g.bits = c.bits;
+  g.C = c.K;            // rows of the output
+  g.K = c.C;            // contraction channels
+  g.H = c.P; g.W = c.Q;  // the columns' image: the output
+  g.P = c.H; g.Q = c.W;  // the gathered image: the input
+  g.fwd = 1;
+  g.A = w_codes;
+  g.B = x_codes;
+  g.groups = (int)(round_up(c.C, kGranule) / kGranule);
+  g.inner = c.R * c.S;
+  if (g.groups <= 4) {
+    g.gp = g.groups == 3 ? 4 : g.groups;
+    g.gp_log2 = g.gp == 1 ? 0 : (g.gp == 2 ? 1 : 2);
+  } else {
+    g.gp = (g.groups + BKC - 1) / BKC * BKC;
+    g.gp_log2 = -1;
+  }
+  const long long padded = (long long)g.gp * g.inner;
+  const long long a_bytes = (long long)c.K * g.groups * g.inner * 16;
+  const long long b_bytes = (long long)c.N * g.groups * c.H * c.W * 16;
+  const long long nj = (long long)c.N * c.P * c.Q;
+  if (nj > 0x7fffffffll || padded > 0x7fffffffll / 16 || a_bytes >= (1ll << 31) ||
+      b_bytes >= (1ll << 31))
+    return LBT_ERR_UNSUPPORTED;
+  g.chunks = (int)padded;
+  g.lda = (unsigned)(g.groups * g.inner * 16);
+  g.a_bytes = (unsigned)a_bytes;
+  g.b_bytes = (unsigned)b_bytes;
+  g.M = c.K;
+  g.NJ = (int)nj;
+  g.epi = 0;
+  g.sc = sc;
+  g.status_out = status_out;
+  g.out = Y; g.acc = acc;
+  return run_direct(g, 0, x_unsigned ? 4 : 3, KID_GEMM_FWD, s);
+}
+
+// Forward product of a linear layer, Y[M][N_out] = X . W: rows of X against rows of W^T.
+//   A = X codes [M][Kin_p/16][16], B = W codes [N_out][Kin_p/16][16].
+int launch_linear_fwd(int M, int K_in, int N_out, int bits, const uint8_t* x_codes,
+                      const uint8_t* w_codes, const OperandScalars* sc, int x_unsigned, float* Y,
+                      int32_t* acc, int32_t* status_out, hipStream_t s) {
+  GemmArgs g{};
+  g.N = M; g.C = N_out; g.K = K_in; g.H = g.W = g.P = g.Q = g.R = g.S = 1; g.stride = 1; g.pad = 0;
+  g.bits = bits;
+  g.A = x_codes;
+  g.B = w_codes;
+  g.groups = (int)(round_up(K_in, kGranule) / kGranule);
+  g.inner = 1;
+  g.chunks = g.groups;
+  if ((long long)g.chunks * 16 * M >= (1ll << 31) || (long long)g.chunks * 16 * N_out >= (1ll << 31))
+    return LBT_ERR_UNSUPPORTED;
+  g.lda = (unsigned)(g.chunks * 16);
+  g.a_bytes = g.lda * (unsigned)M;
+  g.b_bytes = g.lda * (unsigned)N_out;
+  g.M = M;
+  g.NJ = N_out;
+  g.epi = 2;
+  g.sc = sc;
+  g.status_out = status_out;
+  g.out = Y; g.acc = acc;
+  return run_direct(g, 1, x_unsigned ? 4 : 3, KID_GEMM_FWD, s);
 }
 
 int launch_conv_dw(const ConvGeom& c, const uint8_t* g_codes, const uint8_t* x_codes,
@@ -736,7 +824,7 @@ int launch_linear_dx(const ConvGeom& c, const uint8_t* w_codes, const uint8_t* g
   g.epi = 2;
   g.st = st; g.sc = sc; g.update_st = update_st;
   g.out = dX; g.acc = acc;
-  return run_direct(g, 1, s);
+  return run_direct(g, 1, 0, KID_GEMM_DX, s);
 }
 
 int launch_linear_dw(const ConvGeom& c, const uint8_t* g_codes, const uint8_t* x_codes,

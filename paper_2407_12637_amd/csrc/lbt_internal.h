@@ -58,7 +58,7 @@ __device__ __forceinline__ void interval_update(lbt_grad_state* st) {
 // ---- profile.hip: optional event timing of every launch ------------------------
 enum KernelId {
   KID_ABSMAX = 0, KID_FLAT_GRAD, KID_FLAT_OPERAND, KID_QUANTIZE_GRAD, KID_QUANTIZE_LAYER, KID_GEMM_DX,
-  KID_GEMM_DW,
+  KID_GEMM_DW, KID_GEMM_FWD,
   KID_FINALIZE, KID_UPDATE, KID_STATE, KID_COUNT
 };
 // Records a start event now and a stop event when it goes out of scope (after the
@@ -115,6 +115,7 @@ struct RelayoutIo {
   uint8_t* out_b;
   uint8_t* out_a;
   int a_lmajor;  // out_a as [B][L][A/16][16] instead of [B][A/16][L][16]
+  int b_lmajor;  // out_b as [A][L][B/16][16] instead of [A][B/16][L][16]
 };
 // The tensors of one layer, quantized by ONE launch: [0] the output gradient (clip value
 // from gamma in *st and the maximum; statistics go to *st), [1] the activations, [2] the
@@ -163,6 +164,14 @@ int launch_conv_dx(const ConvGeom& g, const uint8_t* w_codes, const uint8_t* g_c
 int launch_conv_dw(const ConvGeom& g, const uint8_t* g_codes, const uint8_t* x_codes,
                    const lbt_grad_state* st, const OperandScalars* sc, int x_unsigned, float* dW,
                    int32_t* acc, int32_t* partial, lbt_grad_state* update_st, hipStream_t s);
+// Forward products Y = Q(X) . Q(W) (no gradient state: the scale comes from the operand
+// scalars; status_out, may be null, receives the operands' status).
+int launch_conv_fwd(const ConvGeom& g, const uint8_t* w_codes, const uint8_t* x_codes,
+                    const OperandScalars* sc, int x_unsigned, float* Y, int32_t* acc,
+                    int32_t* status_out, hipStream_t s);
+int launch_linear_fwd(int M, int K_in, int N_out, int bits, const uint8_t* x_codes,
+                      const uint8_t* w_codes, const OperandScalars* sc, int x_unsigned, float* Y,
+                      int32_t* acc, int32_t* status_out, hipStream_t s);
 // Linear layer: A/B roles swapped so both outputs are written along their rows.
 // update_st (all four; may be null): the launch that ends the product also applies Alg. 1 to
 // that state (the products read only the scale from it, so the order inside does not matter).

@@ -446,7 +446,8 @@ __global__ __launch_bounds__(kThreads) void k_quantize_flat(
 // quantize + re-layout of T[A][B][L] (L contiguous) into the GEMM layouts
 //   out_b [A][BG][L][16]  sixteen consecutive b per 16-byte granule (BG = Bp/16)
 //   out_a [B][AG][L][16]  sixteen consecutive a per 16-byte granule (AG = Ap/16);
-//         [B][L][AG][16] when a_lmajor is set (the dX kernel reads weights tap by tap)
+//         [B][L][AG][16] when a_lmajor is set (the dX kernel reads weights tap by tap);
+//         likewise out_b as [A][L][BG][16] when b_lmajor is set (forward product)
 // zero padded in the last granule.  A workgroup owns a 16(a) x 16(b) x TL(l)
 // tile: it quantizes into LDS (one byte per code, [a][b][l]), then each thread
 // gathers the sixteen codes of one granule and stores its 16 bytes; consecutive
@@ -469,6 +470,7 @@ struct TileArgs {
   uint4* out_b;
   uint4* out_a;
   int a_lmajor;
+  int b_lmajor;   // out_b as [A][L][BG][16]
   int hindsight;  // gradient only: interval from the previous call's maximum
   int bits;       // b of Eq. (2)/(3)
 };
@@ -487,7 +489,9 @@ __device__ __forceinline__ void store_granules(const TileArgs& t, const uint8_t*
       uint32_t w[4] = {0, 0, 0, 0};
 #pragma unroll
       for (int j = 0; j < 16; ++j) w[j >> 2] |= (uint32_t)tile[(a * 16 + j) * pitch + l] << (8 * (j & 3));
-      t.out_b[((long long)(a0 + a) * t.BG + bg) * t.L + l0 + l] = make_uint4(w[0], w[1], w[2], w[3]);
+      const long long o = t.b_lmajor ? ((long long)(a0 + a) * t.L + l0 + l) * t.BG + bg
+                                     : ((long long)(a0 + a) * t.BG + bg) * t.L + l0 + l;
+      t.out_b[o] = make_uint4(w[0], w[1], w[2], w[3]);
     }
   }
   if (t.out_a) {
@@ -542,9 +546,11 @@ __device__ __forceinline__ void store_granules_w4(const TileArgs& t, const uint8
       if (a0 + a >= t.A) continue;
       uint4 g4[4];
       granules4(tile, (a * 16) * pitch + l, pitch, g4);
-      uint4* dst = t.out_b + ((long long)(a0 + a) * t.BG + bg) * t.L + l0 + l;
+      const long long o = t.b_lmajor ? ((long long)(a0 + a) * t.L + l0 + l) * t.BG + bg
+                                     : ((long long)(a0 + a) * t.BG + bg) * t.L + l0 + l;
+      const int step = t.b_lmajor ? t.BG : 1;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) dst[i] = g4[i];
+      for (int i = 0; i < 4; ++i) t.out_b[o + (long long)i * step] = g4[i];
     }
   }
   if (t.out_a) {
@@ -1039,6 +1045,7 @@ static void fill_tile_args(TileArgs& t, const float* x, int64_t A, int64_t B, in
   t.out_b = reinterpret_cast<uint4*>(io.out_b);
   t.out_a = reinterpret_cast<uint4*>(io.out_a);
   t.a_lmajor = io.a_lmajor;
+  t.b_lmajor = io.b_lmajor;
 }
 
 int launch_quantize_layer(const LayerTensors& q, hipStream_t s) {

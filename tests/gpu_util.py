@@ -91,6 +91,35 @@ def backward_conv2d(X, W, dY, stride, pad, st, c_x=0.0, x_unsigned=True, c_w=0.0
     return r
 
 
+def forward_linear(X, W, c_x=0.0, x_unsigned=False, c_w=0.0, flags=0, with_acc=True):
+    M, K = X.shape
+    N = W.shape[1]
+    ws = torch.zeros(lbt.lbt_workspace_bytes_forward_linear(M, K, N), dtype=torch.uint8, device=DEV)
+    Y = torch.full((M, N), float("nan"), device=DEV)
+    acc = torch.full((M, N), -1, dtype=torch.int32, device=DEV) if with_acc else None
+    status = torch.full((1,), -1, dtype=torch.int32, device=DEV)
+    lbt.lbt_forward_linear(dev(X), dev(W), M, K, N, c_x, x_unsigned, c_w, flags, Y, acc, status, ws)
+    r = Result()
+    r.Y, r.acc, r.status = Y.cpu().numpy(), None if acc is None else acc.cpu().numpy(), int(status.item())
+    return r
+
+
+def forward_conv2d(X, W, stride, pad, c_x=0.0, x_unsigned=True, c_w=0.0, flags=0, with_acc=True):
+    N, Cc, H, Wd = X.shape
+    K, _, R, S = W.shape
+    P, Q = (H + 2 * pad - R) // stride + 1, (Wd + 2 * pad - S) // stride + 1
+    ws = torch.zeros(lbt.lbt_workspace_bytes_forward_conv2d(N, Cc, H, Wd, K, R, S, stride, pad),
+                     dtype=torch.uint8, device=DEV)
+    Y = torch.full((N, K, P, Q), float("nan"), device=DEV)
+    acc = torch.full((N, K, P, Q), -1, dtype=torch.int32, device=DEV) if with_acc else None
+    status = torch.full((1,), -1, dtype=torch.int32, device=DEV)
+    lbt.lbt_forward_conv2d(dev(X), dev(W), N, Cc, H, Wd, K, R, S, stride, pad, c_x, x_unsigned, c_w,
+                           flags, Y, acc, status, ws)
+    r = Result()
+    r.Y, r.acc, r.status = Y.cpu().numpy(), None if acc is None else acc.cpu().numpy(), int(status.item())
+    return r
+
+
 def assert_state_equal(h, o):
     """Device state (binding.GradState) vs oracle.GradState, bit for bit."""
     assert h.status == o.status, (h.status, o.status)
