@@ -50,6 +50,10 @@ def parse():
     ap.add_argument("--separate-update", action="store_true",
                     help="apply the interval update with lbt_update_interval after every layer "
                          "instead of inside the backward call (LBT_FUSED_UPDATE)")
+    ap.add_argument("--given-clips", action="store_true",
+                    help="pass clip values for X and W (learned parameters in the paper, Sec. 3.1: "
+                         "3 standard deviations here) instead of letting the call take the tensors' "
+                         "maxima; a separate measurement, the default sweep uses the maxima")
     ap.add_argument("--forward", action="store_true",
                     help="time the quantized forward pass Y = Q(X).Q(W) of the same layers instead "
                          "of the backward pass (a separate measurement, never the headline)")
@@ -96,6 +100,11 @@ class LayerRun:
         self.dW = torch.empty(ws, device=dev, dtype=f32)
         self.state = None
         self.seed = 1000 + idx
+        self.c_x = self.c_w = 0.0            # <= 0: the call takes the tensor's maximum
+        self.fan_in = fan_in
+
+    def use_given_clips(self):
+        self.c_x, self.c_w = 3.0, 3.0 * (2.0 / self.fan_in) ** 0.5
 
     def ws_bytes(self, lbt, forward=False):
         s = self.spec
@@ -111,22 +120,23 @@ class LayerRun:
     def run_forward(self, lbt, ws, flags):
         s = self.spec
         if self.is_linear:
-            lbt.lbt_forward_linear(self.X, self.W, s.M, s.K, s.N, 0.0, self.x_unsigned, 0.0, flags,
-                                   self.Y, None, None, ws)
+            lbt.lbt_forward_linear(self.X, self.W, s.M, s.K, s.N, self.c_x, self.x_unsigned,
+                                   self.c_w, flags, self.Y, None, None, ws)
         else:
             lbt.lbt_forward_conv2d(self.X, self.W, s.N, s.C, s.H, s.W, s.K, s.R, s.S, s.stride,
-                                   s.pad, 0.0, self.x_unsigned, 0.0, flags, self.Y, None, None, ws)
+                                   s.pad, self.c_x, self.x_unsigned, self.c_w, flags, self.Y, None,
+                                   None, ws)
 
     def run(self, lbt, ws, rounding):
         """One layer's backward and its interval update (inside the call when `rounding`
         carries LBT_FUSED_UPDATE, else as a call of its own)."""
         s = self.spec
         if self.is_linear:
-            lbt.lbt_backward_linear(self.X, self.W, self.dY, s.M, s.K, s.N, 0.0, self.x_unsigned,
-                                    0.0, self.state, self.seed, rounding, self.dX, self.dW, ws)
+            lbt.lbt_backward_linear(self.X, self.W, self.dY, s.M, s.K, s.N, self.c_x, self.x_unsigned,
+                                    self.c_w, self.state, self.seed, rounding, self.dX, self.dW, ws)
         else:
             lbt.lbt_backward_conv2d(self.X, self.W, self.dY, s.N, s.C, s.H, s.W, s.K, s.R, s.S,
-                                    s.stride, s.pad, 0.0, self.x_unsigned, 0.0, self.state,
+                                    s.stride, s.pad, self.c_x, self.x_unsigned, self.c_w, self.state,
                                     self.seed, rounding, self.dX, self.dW, ws)
         if not rounding & lbt.FUSED_UPDATE:
             lbt.lbt_update_interval(self.state)
@@ -241,6 +251,8 @@ def main():
                                    x_unsigned=not vit and args.bits < 8))
     for L in layers:
         L.state = lbt.new_state(gamma0=args.gamma0, bits=args.bits)
+        if args.given_clips:
+            L.use_given_clips()
     ws = torch.zeros(max(L.ws_bytes(lbt, args.forward) for L in layers), dtype=torch.uint8,
                      device="cuda")
     gemm_ops = sum(2.0 * L.spec.gemm_ops for L in layers)       # dX and dW
@@ -279,6 +291,8 @@ def main():
                                   args.rounding, args.gamma0),
                    "gemm_GOP_per_step": gemm_ops / 1e9, "grad_elements_per_step": n_grad},
     }
+    if args.given_clips:
+        out["config"]["workload"] += ", clip values of X and W given (no maximum taken)"
     if args.forward:
         out["config"]["workload"] += ", FORWARD pass Y = Q(X).Q(W) only"
     if args.single_sweep:
@@ -362,7 +376,7 @@ def main():
                                    "ms_per_step": t_ms, "roofline_ms_per_step": t_roof * 1e3,
                                    "frac_of_layer_rooflines": t_roof * 1e3 / t_ms}
 
-    if not args.no_cpu_baseline and not args.single_sweep and not args.forward:   # the oracle is timed on the paper's mode
+    if not (args.no_cpu_baseline or args.single_sweep or args.forward or args.given_clips):   # the oracle is timed on the paper's mode
         out["cpu_baseline"] = cpu_baseline(layers, rounding & lbt.ROUND_STOCHASTIC, args.bits)
 
     print(json.dumps(out))
