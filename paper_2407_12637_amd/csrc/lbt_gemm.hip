@@ -60,7 +60,11 @@ struct GemmArgs {
   int steps, steps_per_split;
   int tiles_m, tiles_n, total_blocks;
   int epi;            // 0 = scaled store to NCHW dX, 1 = int32 partial tile (split K),
-                      // 2 = scaled store row-major
+                      // 2 = scaled store row-major, 3 = NCHW dX of a strided 1x1 convolution:
+                      //     the columns are the P x Q output pixels of the forward layer, each
+                      //     owning a cell of up x up input pixels of which only the corner
+                      //     receives a sum (out_h x out_w = the input image, up = the stride)
+  int out_h, out_w, up;
   int scale_kind;     // 0: s_g*s_w   1: s_x*s_g (signed x)   2: s_x*s_g (unsigned x)
                       // 3: s_x*s_w (signed x)   4: s_x*s_w (unsigned x): forward product
   int fwd;            // MODE 0 gathers input pixels of a forward convolution (see the tap table)
@@ -402,6 +406,42 @@ __global__ __launch_bounds__(kThreads) void k_implicit_gemm(const GemmArgs g) {
     if (col_j >= g.NJ) continue;
     long long base;
     long long row_stride;
+    if (g.epi == 3) {
+      // column = (n, p, q); the cell's corner is input pixel (p * up, q * up); the rest of
+      // the cell gets zeros (no output position of the layer reads those pixels with a tap)
+      const int n_ = col_j / HW, pq = col_j - n_ * HW;
+      const int p_ = pq / g.W, q_ = pq - p_ * g.W;
+      const int h0 = p_ * g.up, w0 = q_ * g.up;
+      const long long plane = (long long)g.out_h * g.out_w;
+      const long long cell = (long long)n_ * g.C * plane + (long long)h0 * g.out_w + w0;
+      const bool pair = g.up == 2 && (g.out_w & 1) == 0;   // (value, 0) as one 8-byte store
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int row = m0 + wm + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+          if (row >= g.M) continue;
+          const int v = acc[i][j][r];
+          const float f = (float)v * scale;
+          const long long o = cell + (long long)row * plane;
+          if (pair) {
+            *reinterpret_cast<float2*>(g.out + o) = make_float2(f, 0.0f);
+            if (g.acc) *reinterpret_cast<int2*>(g.acc + o) = make_int2(v, 0);
+            if (h0 + 1 < g.out_h) {
+              *reinterpret_cast<float2*>(g.out + o + g.out_w) = make_float2(0.0f, 0.0f);
+              if (g.acc) *reinterpret_cast<int2*>(g.acc + o + g.out_w) = make_int2(0, 0);
+            }
+          } else {
+            for (int dy = 0; dy < g.up && h0 + dy < g.out_h; ++dy)
+              for (int dx = 0; dx < g.up && w0 + dx < g.out_w; ++dx) {
+                const bool corner = (dy | dx) == 0;
+                g.out[o + (long long)dy * g.out_w + dx] = corner ? f : 0.0f;
+                if (g.acc) g.acc[o + (long long)dy * g.out_w + dx] = corner ? v : 0;
+              }
+          }
+        }
+      continue;
+    }
     if (g.epi == 0) {
       const int n_ = col_j / HW, hw = col_j - n_ * HW;
       base = (long long)n_ * g.C * HW + hw;
@@ -701,6 +741,15 @@ int launch_conv_dx(const ConvGeom& c, const uint8_t* w_codes, const uint8_t* g_c
   g.M = c.C;
   g.NJ = (int)nj;
   g.epi = 0;
+  if (c.R == 1 && c.S == 1 && c.pad == 0 && c.stride > 1) {
+    // strided 1x1 layer: only input pixels (p * stride, q * stride) receive a sum.  The
+    // product runs over the P x Q grid as an unstrided 1x1 layer and the epilogue fills each
+    // stride x stride cell (the corner's value, zeros elsewhere).
+    g.H = c.P; g.W = c.Q; g.stride = 1;
+    g.NJ = c.N * c.P * c.Q;
+    g.epi = 3;
+    g.out_h = c.H; g.out_w = c.W; g.up = c.stride;
+  }
   g.st = st; g.sc = sc; g.update_st = update_st;
   g.out = dX; g.acc = acc;
   return run_direct(g, 0, 0, KID_GEMM_DX, s);

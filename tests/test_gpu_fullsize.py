@@ -27,6 +27,7 @@ CASES = [
     (_layer("l1.3x3.64-64@56", R50), "t25", 1.0, 1),
     (_layer("l1.1x1.64-256@56", R50), "t25", 0.01, 1),        # 51.4 M gradients, dense codes
     (_layer("l2.3x3s2.128-128@56", R50), "dense", 1.0, 0),     # stride 2
+    (_layer("l2.ds1x1s2.256-512@56", R50), "dense", 0.5, 1),   # strided 1x1 (dX written cell-wise)
     (_layer("l3.1x1.256-1024@14", R50), "t25", 0.002, 1),      # 14x14 maps
     (_layer("l4.1x1.512-2048@7", R50), "dense", 0.5, 1),       # 7x7 maps (odd row length)
     (_layer("l4.3x3.512-512@7", R50), "t25", 0.05, 1),

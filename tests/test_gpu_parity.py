@@ -179,6 +179,9 @@ CONV_CASES = [
     (3, 16, 5, 5, 80, 3, 3, 1, 1),         # 5 channel groups, padded to 8
     (2, 16, 6, 6, 128, 3, 3, 1, 1),        # exactly 8 channel groups: one tap per K step
     (16, 128, 8, 8, 256, 3, 3, 1, 1),      # dW: 72 tiles of 64x64, contraction cut four ways
+    (2, 8, 9, 7, 12, 1, 1, 2, 0),          # strided 1x1, odd image: dX cells cut at the border
+    (2, 8, 10, 11, 12, 1, 1, 3, 0),        # strided 1x1, stride 3
+    (4, 136, 12, 12, 40, 1, 1, 2, 0),      # strided 1x1, several row tiles of dX
 ]
 
 
