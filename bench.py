@@ -50,6 +50,12 @@ def parse():
     ap.add_argument("--separate-update", action="store_true",
                     help="apply the interval update with lbt_update_interval after every layer "
                          "instead of inside the backward call (LBT_FUSED_UPDATE)")
+    ap.add_argument("--streams", type=int, default=1,
+                    help="layers are issued round-robin on this many HIP streams, each with a "
+                         "workspace of its own (the sweep's layers are independent of each other); "
+                         "1 = everything on one stream, the headline configuration")
+    ap.add_argument("--no-overlap-probe", action="store_true",
+                    help="skip the extra measurement of the same steps on three streams")
     ap.add_argument("--given-clips", action="store_true",
                     help="pass clip values for X and W (learned parameters in the paper, Sec. 3.1: "
                          "3 standard deviations here) instead of letting the call take the tensors' "
@@ -263,12 +269,37 @@ def main():
             L.dX = L.dW = None
     n_grad = sum(L.dY.numel() for L in layers)
 
-    def step():
-        for L in layers:
-            if args.forward:
-                L.run_forward(lbt, ws, lbt.BITS(args.bits))
-            else:
-                L.run(lbt, ws, rounding)
+    n_streams = max(1, args.streams)
+
+    def run_layer(L, space):
+        if args.forward:
+            L.run_forward(lbt, space, lbt.BITS(args.bits))
+        else:
+            L.run(lbt, space, rounding)
+
+    def make_step(n):
+        """One pass over the sweep, layers issued round-robin on n streams (each stream has a
+        workspace of its own; n = 1: everything on the current stream)."""
+        if n == 1:
+            def one_stream():
+                for L in layers:
+                    run_layer(L, ws)
+            return one_stream
+        streams = [torch.cuda.Stream() for _ in range(n)]
+        spaces = [ws] + [torch.zeros_like(ws) for _ in range(n - 1)]
+
+        def many_streams():
+            main = torch.cuda.current_stream()
+            for st in streams:
+                st.wait_stream(main)
+            for i, L in enumerate(layers):
+                with torch.cuda.stream(streams[i % n]):
+                    run_layer(L, spaces[i % n])
+            for st in streams:
+                main.wait_stream(st)
+        return many_streams
+
+    step = make_step(n_streams)
 
     for _ in range(args.warmup):
         step()
@@ -291,6 +322,24 @@ def main():
                                   args.rounding, args.gamma0),
                    "gemm_GOP_per_step": gemm_ops / 1e9, "grad_elements_per_step": n_grad},
     }
+    if n_streams > 1:
+        out["config"]["workload"] += ", layers round-robin on %d streams" % n_streams
+    elif not args.no_overlap_probe:
+        # the same K steps once more with the (independent) layers of the sweep issued on three
+        # streams: kernels bound by HBM overlap with kernels bound by latency.  Reported beside
+        # the headline, which stays the one-stream figure the per-kernel numbers refer to.
+        overlapped = make_step(3)
+        overlapped()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            overlapped()
+        torch.cuda.synchronize()
+        dt3 = (time.perf_counter() - t0) / args.steps
+        out["multi_stream"] = {"streams": 3, "ms_per_step": dt3 * 1e3,
+                               "value": gemm_ops / dt3 / 1e12, "unit": "TOPS"}
+        del overlapped
+        step = make_step(1)
     if args.given_clips:
         out["config"]["workload"] += ", clip values of X and W given (no maximum taken)"
     if args.forward:
