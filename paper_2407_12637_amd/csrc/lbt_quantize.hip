@@ -644,6 +644,8 @@ struct TileCoord {
   unsigned n_blocks;    // workgroups that work on this tensor
   unsigned id;          // this workgroup's index among them
   bool first;           // the tensor's first workgroup
+  unsigned gx, tiles;   // matrix tiles: tiles along b and in all; workgroup id takes tiles
+                        // id, id + n_blocks, ...
 };
 
 template <int MODE, bool SMALL>
@@ -779,7 +781,9 @@ __device__ __forceinline__ void generic_body(const TileArgs& t, const TileCoord&
 // A thread quantizes two runs of 8 consecutive b (one generator block each) into an [a][b]
 // LDS tile.  Granules along b are 16 consecutive tile bytes (one per thread); granules along a
 // come out of the 16 x 4 byte transpose also used by the streaming tiles (64 threads, four
-// granules each).  Four neighbouring threads store 64 contiguous bytes.
+// granules each).  Four neighbouring threads store 64 contiguous bytes.  A workgroup walks
+// several tiles when the matrix has more than the grid's cap, so that the prologue (the
+// re-reduction of the partial maxima) and the ticket are paid once per workgroup.
 // ---------------------------------------------------------------------------
 template <int MODE>
 __device__ __forceinline__ void matrix_body(const TileArgs& t, const TileCoord& bc, uint8_t* lds) {
@@ -799,8 +803,9 @@ __device__ __forceinline__ void matrix_body(const TileArgs& t, const TileCoord& 
   const QConst qc = make_qconst(c, MODE == 1, t.bits);
   const bool live = c > 0.0f;
   const unsigned long long step = (MODE == 3) ? t.st->step : 0ull;
-  const int b0 = bc.x * 64, a0 = bc.z * 64;
   uint32_t cnt = 0, seen_max = 0;
+  for (unsigned tile_id = bc.id; tile_id < bc.tiles; tile_id += bc.n_blocks) {
+  const int b0 = (int)(tile_id % bc.gx) * 64, a0 = (int)(tile_id / bc.gx) * 64;
   float v[2][8];
   bool ok[2];
   long long e0[2];
@@ -816,7 +821,7 @@ __device__ __forceinline__ void matrix_body(const TileArgs& t, const TileCoord& 
     v[i][4] = hi.x; v[i][5] = hi.y; v[i][6] = hi.z; v[i][7] = hi.w;
   }
   // (a run outside the matrix has fetched the tensor's first elements: harmless for a maximum)
-  if (MODE >= 2 && gs.hindsight) seen_max = max(max_abs_bits8(v[0]), max_abs_bits8(v[1]));
+  if (MODE >= 2 && gs.hindsight) seen_max = max(seen_max, max(max_abs_bits8(v[0]), max_abs_bits8(v[1])));
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
     const int it = threadIdx.x + kThreads * i;
@@ -844,6 +849,8 @@ __device__ __forceinline__ void matrix_body(const TileArgs& t, const TileCoord& 
 #pragma unroll
     for (int i = 0; i < 4; ++i)
       if (b0 + 4 * r + i < t.B) t.out_a[(long long)(b0 + 4 * r + i) * t.AG + (a0 >> 4) + gl] = g4[i];
+  }
+  __syncthreads();   // the tile is free for the workgroup's next one
   }
   if (MODE >= 2) grad_finish(t.st, gs, cnt, (unsigned long long)t.A * t.B * t.L, bc.n_blocks, bc.id,
                              ticket_slots(t.pmax), seen_max);
@@ -875,6 +882,8 @@ __device__ __forceinline__ void run_segment(const Segment& sg, unsigned blk, uin
   bc.n_blocks = sg.n_blocks;
   bc.id = local;
   bc.first = local == 0;
+  bc.gx = sg.gx;
+  bc.tiles = sg.gx * sg.gy * sg.gz;
   switch (sg.kind) {
     case kWindowed: stream_body<MODE, false>(sg.t, sg.pitch, sg.tl, bc, lds); break;
     case kWholeRow: stream_body<MODE, true>(sg.t, sg.pitch, sg.tl, bc, lds); break;
@@ -900,6 +909,8 @@ __global__ __launch_bounds__(kThreads) void k_quantize_grad(const Segment sg) {
   bc.n_blocks = sg.n_blocks;
   bc.id = local;
   bc.first = local == 0;
+  bc.gx = sg.gx;
+  bc.tiles = sg.gx * sg.gy * sg.gz;
   if (KIND == kWindowed) stream_body<MODE, false>(sg.t, sg.pitch, sg.tl, bc, dyn_tile);
   else if (KIND == kWholeRow) stream_body<MODE, true>(sg.t, sg.pitch, sg.tl, bc, dyn_tile);
   else if (KIND == kGenericColumn) generic_body<MODE, 1>(sg.t, bc, dyn_tile);
@@ -926,6 +937,9 @@ inline int flat_grid(long long work_items) {
   if (blocks < 1) blocks = 1;
   return (int)blocks;
 }
+
+// Matrix tiles: workgroups per tensor above which a workgroup takes more than one tile.
+constexpr unsigned long long kMatrixGridCap = 2048;
 
 TileKind tile_kind(const float* x, long long B, long long L) {
   if (reinterpret_cast<uintptr_t>(x) % 16 == 0) {
@@ -1067,8 +1081,12 @@ int launch_quantize_layer(const LayerTensors& q, hipStream_t s) {
     sg.t.bad_out = o.bad_out;
     const size_t need = plan_segment(sg);
     if (need > lds) lds = need;
-    const unsigned long long nb = (unsigned long long)sg.gx * sg.gy * sg.gz;
-    if (nb == 0 || next + nb > 0x7fffffffull) return LBT_ERR_UNSUPPORTED;
+    unsigned long long nb = (unsigned long long)sg.gx * sg.gy * sg.gz;
+    if (nb == 0 || nb > 0x7fffffffull || next + nb > 0x7fffffffull) return LBT_ERR_UNSUPPORTED;
+    if (sg.kind == kMatrix && nb > kMatrixGridCap) {   // several tiles per workgroup
+      const unsigned long long per = (nb + kMatrixGridCap - 1) / kMatrixGridCap;
+      nb = (nb + per - 1) / per;
+    }
     sg.n_blocks = (unsigned)nb;
     next += nb;
     work += (double)o.A * (double)o.B * (double)o.L;
