@@ -63,6 +63,14 @@ def test_full_size_layer(idx):
     h_before = lbt.lbt_state_read(st)
     lbt.lbt_update_interval(st)
     h_after = lbt.lbt_state_read(st)
+    # the benchmark's launch configuration: the same call with the interval update inside it
+    st2 = lbt.new_state(gamma0=gamma0)
+    res2 = gu.backward_conv2d(X, W, dY, L.stride, L.pad, st2, x_unsigned=True, seed=seed,
+                              rounding=rounding | lbt.FUSED_UPDATE, with_acc=False)
+    h2 = lbt.lbt_state_read(st2)
+    assert (h2.gamma, h2.step, h2.n_out, h2.status) == (h_after.gamma, h_after.step, h_after.n_out,
+                                                        h_after.status)
+    assert np.array_equal(res2.dX, res.dX) and np.array_equal(res2.dW, res.dW)
 
     # --- oracle: quantizers in full ---------------------------------------------------------
     ost = oracle.GradState(gamma=gamma0)
