@@ -425,10 +425,12 @@ __global__ __launch_bounds__(kThreads) void k_implicit_gemm(const GemmArgs g) {
           const float f = (float)v * scale;
           const long long o = cell + (long long)row * plane;
           if (pair) {
-            *reinterpret_cast<float2*>(g.out + o) = make_float2(f, 0.0f);
+            __builtin_nontemporal_store(f, g.out + o);
+            __builtin_nontemporal_store(0.0f, g.out + o + 1);
             if (g.acc) *reinterpret_cast<int2*>(g.acc + o) = make_int2(v, 0);
             if (h0 + 1 < g.out_h) {
-              *reinterpret_cast<float2*>(g.out + o + g.out_w) = make_float2(0.0f, 0.0f);
+              __builtin_nontemporal_store(0.0f, g.out + o + g.out_w);
+              __builtin_nontemporal_store(0.0f, g.out + o + g.out_w + 1);
               if (g.acc) *reinterpret_cast<int2*>(g.acc + o + g.out_w) = make_int2(0, 0);
             }
           } else {
@@ -461,7 +463,7 @@ __global__ __launch_bounds__(kThreads) void k_implicit_gemm(const GemmArgs g) {
         if (g.epi == 1) {
           g.partial[(long long)split * g.M * g.NJ + o] = v;
         } else {
-          g.out[o] = (float)v * scale;
+          __builtin_nontemporal_store((float)v * scale, &g.out[o]);
           if (g.acc) g.acc[o] = v;
         }
       }

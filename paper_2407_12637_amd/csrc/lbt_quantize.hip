@@ -310,19 +310,6 @@ struct MaxSeg {
   int first_block;  // first workgroup of this tensor
 };
 
-__device__ __forceinline__ uint32_t max_key(float v, int use_abs) {
-  const uint32_t b = __float_as_uint(v);
-  const uint32_t mag = b & 0x7fffffffu;
-  if (use_abs) return mag;
-  if (mag >= kInfBits) return mag;  // keep NaN/Inf visible
-  return (b >> 31) ? 0u : b;        // negatives count as 0
-}
-
-__device__ __forceinline__ uint32_t max_key4(const float4& v, int use_abs) {
-  return max(max(max_key(v.x, use_abs), max_key(v.y, use_abs)),
-             max(max_key(v.z, use_abs), max_key(v.w, use_abs)));
-}
-
 __global__ __launch_bounds__(kThreads) void k_absmax3(MaxSeg s0, MaxSeg s1, MaxSeg s2,
                                                        long long per_block, uint32_t* pmax,
                                                        lbt_grad_state* st) {
@@ -344,18 +331,32 @@ __global__ __launch_bounds__(kThreads) void k_absmax3(MaxSeg s0, MaxSeg s1, MaxS
   const long long count = min(per_block, s.n - start);
   const float4* p4 = reinterpret_cast<const float4*>(s.p + start);
   const long long n4 = count / 4;
-  uint32_t m = 0;
+  // Two running maxima, three operations per element: of the magnitudes' bit patterns (unsigned
+  // compare: NaN / Inf of either sign end up on top) and of the bit patterns as signed integers
+  // (= max(x, 0) for finite values: negatives are negative integers).
+  uint32_t mag = 0;
+  int pos = 0;
+  auto take = [&](const float4& v) __attribute__((always_inline)) {
+    const uint32_t b0 = __float_as_uint(v.x), b1 = __float_as_uint(v.y), b2 = __float_as_uint(v.z),
+                   b3 = __float_as_uint(v.w);
+    mag = max(max(mag, b0 & 0x7fffffffu), max(b1 & 0x7fffffffu, max(b2 & 0x7fffffffu, b3 & 0x7fffffffu)));
+    pos = max(max(pos, (int)b0), max((int)b1, max((int)b2, (int)b3)));
+  };
   long long i = threadIdx.x;
   for (; i + 7 * kThreads < n4; i += 8 * kThreads) {
     float4 v[8];
 #pragma unroll
     for (int u = 0; u < 8; ++u) v[u] = p4[i + u * kThreads];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) m = max(m, max_key4(v[u], s.use_abs));
+    for (int u = 0; u < 8; ++u) take(v[u]);
   }
-  for (; i < n4; i += kThreads) m = max(m, max_key4(p4[i], s.use_abs));
-  if ((long long)threadIdx.x < count - n4 * 4)
-    m = max(m, max_key(s.p[start + n4 * 4 + threadIdx.x], s.use_abs));
+  for (; i < n4; i += kThreads) take(p4[i]);
+  if ((long long)threadIdx.x < count - n4 * 4) {
+    const float x = s.p[start + n4 * 4 + threadIdx.x];
+    take(make_float4(x, 0.0f, 0.0f, 0.0f));
+  }
+  // max |x|, or max(x, 0) with a non-finite value of either sign kept visible
+  uint32_t m = (s.use_abs || mag >= kInfBits) ? mag : (uint32_t)pos;
   m = block_max(m);
   if (threadIdx.x < 4) pmax[blk * 4 + threadIdx.x] = ((int)threadIdx.x == t) ? m : 0u;
 }
