@@ -310,6 +310,9 @@ struct MaxSeg {
   int first_block;  // first workgroup of this tensor
 };
 
+// The tensors are read with streaming (non-temporal) loads.  Measured on the ResNet-50 sweep:
+// the maximum sweep then runs at 5.7 TB/s instead of 4.8; the quantizer's second sweep loses
+// the few cache hits it had (+0.1 ms per step against -0.16 ms here), at every tensor size.
 __global__ __launch_bounds__(kThreads) void k_absmax3(MaxSeg s0, MaxSeg s1, MaxSeg s2,
                                                        long long per_block, uint32_t* pmax,
                                                        lbt_grad_state* st) {
@@ -346,7 +349,11 @@ __global__ __launch_bounds__(kThreads) void k_absmax3(MaxSeg s0, MaxSeg s1, MaxS
   for (; i + 7 * kThreads < n4; i += 8 * kThreads) {
     float4 v[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) v[u] = p4[i + u * kThreads];
+    for (int u = 0; u < 8; ++u) {
+      typedef float f4n __attribute__((ext_vector_type(4)));
+      const f4n t = __builtin_nontemporal_load(reinterpret_cast<const f4n*>(p4 + i + u * kThreads));
+      v[u] = make_float4(t.x, t.y, t.z, t.w);
+    }
 #pragma unroll
     for (int u = 0; u < 8; ++u) take(v[u]);
   }
