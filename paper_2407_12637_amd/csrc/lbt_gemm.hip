@@ -425,12 +425,10 @@ __global__ __launch_bounds__(kThreads) void k_implicit_gemm(const GemmArgs g) {
           const float f = (float)v * scale;
           const long long o = cell + (long long)row * plane;
           if (pair) {
-            __builtin_nontemporal_store(f, g.out + o);
-            __builtin_nontemporal_store(0.0f, g.out + o + 1);
+            *reinterpret_cast<float2*>(g.out + o) = make_float2(f, 0.0f);
             if (g.acc) *reinterpret_cast<int2*>(g.acc + o) = make_int2(v, 0);
             if (h0 + 1 < g.out_h) {
-              __builtin_nontemporal_store(0.0f, g.out + o + g.out_w);
-              __builtin_nontemporal_store(0.0f, g.out + o + g.out_w + 1);
+              *reinterpret_cast<float2*>(g.out + o + g.out_w) = make_float2(0.0f, 0.0f);
               if (g.acc) *reinterpret_cast<int2*>(g.acc + o + g.out_w) = make_int2(0, 0);
             }
           } else {
