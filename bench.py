@@ -31,9 +31,10 @@ PEAK_HBM_GBPS = 8000.0          # MI355X HBM3E
 PEAK_INT8_TOPS = 5000.0         # MI355X dense int8 MFMA
 BYTES_PER_GRAD_ELEMENT = 4.5    # algorithmic: 4 B fp32 read + 0.5 B code written
 # The library's event brackets add a fixed marker overhead to every kernel.  It is
-# measured live on the one-thread clipping-factor update kernel, whose own duration is
-# known from rocprofv3 (profiles/bench_resnet50_b64_kernel_stats.txt), and removed:
+# measured live on launches of the one-thread clipping-factor update kernel and removed:
 #   kernel time = bracket(kernel) - (bracket(update kernel) - UPDATE_KERNEL_US)
+# with the constant for which the corrected averages of all kernel classes agree with
+# rocprofv3's durations (profiles/bench_resnet50_b64_kernel_stats.txt).
 UPDATE_KERNEL_US = 4.1
 
 
