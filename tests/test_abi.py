@@ -93,3 +93,20 @@ def test_workspace_formula(lib):
     partial = got - want
     # dW is [256][2304] int32; the contraction is cut into at most 512/36 slices
     assert partial % (K * Cc * R * S * 4) == 0 and 2 <= partial // (K * Cc * R * S * 4) <= 14
+
+
+def test_sizes_beyond_the_documented_limits_are_refused(lib):
+    # tensors of 2^31 elements or more: refused by the geometry check, before any HIP call
+    assert lib.lbt_workspace_bytes_conv2d(1 << 16, 1 << 10, 8, 8, 8, 1, 1, 1, 0) == 0
+    assert lib.lbt_workspace_bytes_linear(1 << 20, 1 << 12, 8) == 0
+    p = C.c_void_p(4096)
+    rc = lib.lbt_backward_conv2d(p, p, p, 1 << 16, 1 << 10, 8, 8, 8, 1, 1, 1, 0, 0.0, 1, 0.0, p, 0, 0,
+                                 p, p, p, 1 << 40, None)
+    assert rc == -3
+    # non-positive sizes, kernel larger than the padded image, zero stride
+    for shape in ((0, 1, 4, 4, 1, 1, 1, 1, 0), (1, 1, 4, 4, 1, 7, 7, 1, 1), (1, 1, 4, 4, 1, 1, 1, 0, 0)):
+        rc = lib.lbt_backward_conv2d(p, p, p, *shape, 0.0, 1, 0.0, p, 0, 0, p, p, p, 1 << 40, None)
+        assert rc == -2, shape
+    assert lib.lbt_forward_conv2d(p, p, 0, 1, 4, 4, 1, 1, 1, 1, 0, 0.0, 1, 0.0, 0, p, None, None, p,
+                                  1 << 40, None) == -2
+    assert lib.lbt_forward_linear(p, p, 4, 4, 4, 0.0, 1, 0.0, 1, p, None, None, p, 1 << 40, None) == -3

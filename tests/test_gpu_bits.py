@@ -166,3 +166,22 @@ def test_8bit_sum_beyond_int32_is_exact():
         lbt.lbt_backward_linear_acc(dev[0], dev[1], dev[2], M, K, N, 0.0, False, 0.0, st, 0,
                                     lbt.BITS(8), None, dW, None, aW, ws)
     assert e.value.code == -5
+
+
+def test_contraction_that_could_overflow_is_refused():
+    """dX of a linear layer contracts over N_out: at 8 bits 140000 terms of up to 127 * 127 can
+    exceed 2^31, and that product is not split: LBT_ERR_OVERFLOW, not a wrapped sum.  The same
+    shape at 4 bits (49 per term) is fine."""
+    M, K, N = 16, 16, 140000
+    r = synth.rng(0, 56, 0, 0)
+    X, W, dY = synth.normal(r, (M, K)), synth.normal(r, (K, N), 0.05), synth.dense_grad(r, (M, N))
+    st = lbt.new_state(bits=8)
+    with pytest.raises(lbt.LbtError) as e:
+        gu.backward_linear(X, W, dY, st, rounding=lbt.BITS(8))
+    assert e.value.code == -5
+    ost = oracle.GradState(gamma=1.0)
+    st = lbt.new_state()
+    ref = oracle.backward_linear(X, W, dY, ost)
+    res = gu.backward_linear(X, W, dY, st)
+    gu.assert_state_equal(lbt.lbt_state_read(st), ost)
+    _check_backward(res, ref)
