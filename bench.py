@@ -154,10 +154,12 @@ def cpu_baseline(layers, rounding, bits=4):
     import numpy as np
 
     import oracle
-    # a bounded sample (about 10 s of host time on the GPU machine) that spans the sweep's stages
+    # a bounded sample (10-15 s of host time on the GPU machine) that spans the sweep's stages
     pick = ["l1.3x3.64-64@56", "l1.1x1.64-256@56", "l2.1x1.128-512@28", "l2.3x3.128-128@28",
             "l2.3x3s2.128-128@56", "l3.1x1.256-1024@14", "l3.3x3.256-256@14", "l3.1x1.1024-256@14",
-            "l4.1x1.512-2048@7", "l4.3x3.512-512@7", "l4.1x1.2048-512@7", "l3.3x3s2.256-256@28"]
+            "l4.1x1.512-2048@7", "l4.3x3.512-512@7", "l4.1x1.2048-512@7", "l3.3x3s2.256-256@28",
+            "l1.1x1.256-64@56", "l2.1x1.256-128@56", "l2.ds1x1s2.256-512@56", "l2.1x1.512-128@28",
+            "l3.1x1.512-256@28", "l3.ds1x1s2.512-1024@28", "l4.1x1.1024-512@14"]
     chosen = [L for L in layers if not L.is_linear and L.spec.name in pick]
     if not chosen:      # a sweep of linear layers: its smallest layer
         chosen = [min(layers, key=lambda L: L.spec.gemm_ops)]
