@@ -406,7 +406,9 @@ __global__ __launch_bounds__(kThreads) void k_implicit_gemm(const GemmArgs g) {
     if (col_j >= g.NJ) continue;
     long long base;
     long long row_stride;
-    if (g.epi == 3) {
+    // (the gather mode only ever has the two NCHW epilogues, the dense-row mode the other two:
+    // each kernel compiles its own pair)
+    if (MODE == 0 && g.epi == 3) {
       // column = (n, p, q); the cell's corner is input pixel (p * up, q * up); the rest of
       // the cell gets zeros (no output position of the layer reads those pixels with a tap)
       const int n_ = col_j / HW, pq = col_j - n_ * HW;
@@ -442,7 +444,7 @@ __global__ __launch_bounds__(kThreads) void k_implicit_gemm(const GemmArgs g) {
         }
       continue;
     }
-    if (g.epi == 0) {
+    if (MODE == 0) {
       const int n_ = col_j / HW, hw = col_j - n_ * HW;
       base = (long long)n_ * g.C * HW + hw;
       row_stride = HW;
@@ -458,7 +460,7 @@ __global__ __launch_bounds__(kThreads) void k_implicit_gemm(const GemmArgs g) {
         if (row >= g.M) continue;
         const int v = acc[i][j][r];
         const long long o = base + (long long)row * row_stride;
-        if (g.epi == 1) {
+        if (MODE == 1 && g.epi == 1) {
           g.partial[(long long)split * g.M * g.NJ + o] = v;
         } else {
           if (STREAM) __builtin_nontemporal_store((float)v * scale, &g.out[o]);
