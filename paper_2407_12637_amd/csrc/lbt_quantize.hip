@@ -481,6 +481,7 @@ struct TileArgs {
   int b_lmajor;   // out_b as [A][L][BG][16]
   int hindsight;  // gradient only: interval from the previous call's maximum
   int bits;       // b of Eq. (2)/(3)
+  int is_unsigned;  // operand only: Eq. (3) instead of Eq. (2)
 };
 
 // Phase B: gather granules out of the LDS tile.  `pitch` = bytes per (a,b) row.  A granule
@@ -668,10 +669,10 @@ __device__ __forceinline__ void stream_body(const TileArgs& t, int pitch, int tl
   } else if (!(t.c_given > 0.0f) && t.c_ptr) {
     c = *t.c_ptr;
   } else {
-    c = operand_setup(t.c_given, t.pmax, t.nblocks, t.pmax_col, MODE == 1, t.c_out, t.bad_out, t.st,
-                      nullptr, bc.first, t.bits);
+    c = operand_setup(t.c_given, t.pmax, t.nblocks, t.pmax_col, t.is_unsigned != 0, t.c_out, t.bad_out,
+                      t.st, nullptr, bc.first, t.bits);
   }
-  const QConst qc = make_qconst(c, MODE == 1, t.bits);
+  const QConst qc = make_qconst(c, MODE < 2 && t.is_unsigned != 0, t.bits);
   const bool live = c > 0.0f;
   const unsigned long long step = (MODE == 3) ? t.st->step : 0ull;
   const int l0 = bc.x * tl, b0 = bc.y * 16, a0 = bc.z * 16;
@@ -753,10 +754,10 @@ __device__ __forceinline__ void generic_body(const TileArgs& t, const TileCoord&
   } else if (!(t.c_given > 0.0f) && t.c_ptr) {
     c = *t.c_ptr;
   } else {
-    c = operand_setup(t.c_given, t.pmax, t.nblocks, t.pmax_col, MODE == 1, t.c_out, t.bad_out, t.st,
-                      nullptr, bc.first, t.bits);
+    c = operand_setup(t.c_given, t.pmax, t.nblocks, t.pmax_col, t.is_unsigned != 0, t.c_out, t.bad_out,
+                      t.st, nullptr, bc.first, t.bits);
   }
-  const QConst qc = make_qconst(c, MODE == 1, t.bits);
+  const QConst qc = make_qconst(c, MODE < 2 && t.is_unsigned != 0, t.bits);
   const bool live = c > 0.0f;
   const unsigned long long step = (MODE == 3) ? t.st->step : 0ull;
   const int l0 = bc.x * TL, b0 = bc.y * 16, a0 = bc.z * 16;
@@ -805,10 +806,10 @@ __device__ __forceinline__ void matrix_body(const TileArgs& t, const TileCoord& 
   } else if (!(t.c_given > 0.0f) && t.c_ptr) {
     c = *t.c_ptr;
   } else {
-    c = operand_setup(t.c_given, t.pmax, t.nblocks, t.pmax_col, MODE == 1, t.c_out, t.bad_out, t.st,
-                      nullptr, bc.first, t.bits);
+    c = operand_setup(t.c_given, t.pmax, t.nblocks, t.pmax_col, t.is_unsigned != 0, t.c_out, t.bad_out,
+                      t.st, nullptr, bc.first, t.bits);
   }
-  const QConst qc = make_qconst(c, MODE == 1, t.bits);
+  const QConst qc = make_qconst(c, MODE < 2 && t.is_unsigned != 0, t.bits);
   const bool live = c > 0.0f;
   const unsigned long long step = (MODE == 3) ? t.st->step : 0ull;
   uint32_t cnt = 0, seen_max = 0;
@@ -926,16 +927,17 @@ __global__ __launch_bounds__(kThreads) void k_quantize_grad(const Segment sg) {
   else generic_body<MODE, 32>(sg.t, bc, dyn_tile);
 }
 
-// GMODE: 2 nearest / 3 stochastic gradient quantizer; XMODE: 0 signed / 1 unsigned activations;
-// weights are always signed nearest.  A tensor with n_blocks == 0 is absent.
-template <int GMODE, int XMODE>
+// GMODE: 2 nearest / 3 stochastic gradient quantizer.  Activations and weights share ONE copy
+// of the operand code (signed or unsigned is a run-time field of the tensor): the kernel's
+// size counts, its workgroups run three different bodies side by side on a compute unit.
+// A tensor with n_blocks == 0 is absent.
+template <int GMODE>
 __global__ __launch_bounds__(kThreads) void k_quantize_layer(const Segment sg, const Segment sx,
                                                               const Segment sw) {
   extern __shared__ __attribute__((aligned(16))) uint8_t dyn_tile[];
   const unsigned blk = blockIdx.x;
   if (blk < sx.first) run_segment<GMODE>(sg, blk, dyn_tile);
-  else if (blk < sw.first) run_segment<XMODE>(sx, blk, dyn_tile);
-  else run_segment<0>(sw, blk, dyn_tile);
+  else run_segment<0>(blk < sw.first ? sx : sw, blk, dyn_tile);
 }
 
 inline int flat_grid(long long work_items) {
@@ -1084,6 +1086,7 @@ int launch_quantize_layer(const LayerTensors& q, hipStream_t s) {
     sg.t.seed = q.seed;
     sg.t.hindsight = (i == 0) ? q.hindsight : 0;
     sg.t.bits = q.bits;
+    sg.t.is_unsigned = (i == 1) ? q.x_unsigned : 0;
     sg.t.c_given = o.c_given;
     sg.t.c_out = o.c_out;
     sg.t.bad_out = o.bad_out;
@@ -1131,10 +1134,8 @@ int launch_quantize_layer(const LayerTensors& q, hipStream_t s) {
   }
   ProfScope prof(KID_QUANTIZE_LAYER, work, s);
   const dim3 grid((unsigned)next);
-  if (sr && q.x_unsigned) LBT_LAUNCH((k_quantize_layer<3, 1>), grid, block, lds, s, seg[0], seg[1], seg[2]);
-  else if (sr) LBT_LAUNCH((k_quantize_layer<3, 0>), grid, block, lds, s, seg[0], seg[1], seg[2]);
-  else if (q.x_unsigned) LBT_LAUNCH((k_quantize_layer<2, 1>), grid, block, lds, s, seg[0], seg[1], seg[2]);
-  else LBT_LAUNCH((k_quantize_layer<2, 0>), grid, block, lds, s, seg[0], seg[1], seg[2]);
+  if (sr) LBT_LAUNCH((k_quantize_layer<3>), grid, block, lds, s, seg[0], seg[1], seg[2]);
+  else LBT_LAUNCH((k_quantize_layer<2>), grid, block, lds, s, seg[0], seg[1], seg[2]);
   LBT_LAUNCH_CHECK();
   return LBT_OK;
 }
