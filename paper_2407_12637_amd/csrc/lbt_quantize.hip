@@ -932,7 +932,7 @@ __global__ __launch_bounds__(kThreads) void k_quantize_grad(const Segment sg) {
 // size counts, its workgroups run three different bodies side by side on a compute unit.
 // A tensor with n_blocks == 0 is absent.
 template <int GMODE>
-__global__ __launch_bounds__(kThreads) void k_quantize_layer(const Segment sg, const Segment sx,
+__global__ __launch_bounds__(kThreads, 6) void k_quantize_layer(const Segment sg, const Segment sx,
                                                               const Segment sw) {
   extern __shared__ __attribute__((aligned(16))) uint8_t dyn_tile[];
   const unsigned blk = blockIdx.x;
