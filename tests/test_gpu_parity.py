@@ -336,3 +336,50 @@ def test_fused_update_linear():
         res = gu.backward_linear(X, W, dY, st, seed=2, rounding=1 | lbt.FUSED_UPDATE)
         gu.assert_state_equal(lbt.lbt_state_read(st), ost)
         _check_backward(res, ref)
+
+
+# -- outputs of one call feeding the next, on the device --------------------------------------
+def test_chained_layers_consume_device_outputs():
+    """Three convolution layers back to front, several iterations: the dX a call leaves on the
+    device is the dY of the next call (no host round trip), as in a real backward pass.  Every
+    call is checked against the oracle run on the same inputs (the device's own dX of the layer
+    above, read back)."""
+    N = 8
+    layers = [  # (C, H, W, K, R, S, stride, pad): input of layer i+1 = output of layer i
+        (16, 16, 16, 32, 3, 3, 1, 1),
+        (32, 16, 16, 64, 1, 1, 2, 0),
+        (64, 8, 8, 48, 3, 3, 1, 1),
+    ]
+    r = synth.rng(0, 23, 0, 0)
+    Xs = [synth.relu_normal(r, (N, c, h, w)) for (c, h, w, *_rest) in layers]
+    Ws = [synth.kaiming_normal(r, (k, c, rr, ss)) for (c, h, w, k, rr, ss, st_, p) in layers]
+    dXs_dev = [torch.empty((N, c, h, w), device=gu.DEV) for (c, h, w, *_rest) in layers]
+    dWs_dev = [torch.empty(Wt.shape, device=gu.DEV) for Wt in Ws]
+    X_dev = [gu.dev(x) for x in Xs]
+    W_dev = [gu.dev(w) for w in Ws]
+    states = [lbt.new_state(gamma0=0.5) for _ in layers]
+    ostates = [oracle.GradState(gamma=0.5) for _ in layers]
+    ws = torch.zeros(max(lbt.lbt_workspace_bytes_conv2d(N, c, h, w, k, rr, ss, st_, p)
+                         for (c, h, w, k, rr, ss, st_, p) in layers), dtype=torch.uint8, device=gu.DEV)
+    for it in range(3):
+        top = synth.grad_cfg2(r, (N, 48, 8, 8)) if it % 2 == 0 else synth.dense_grad(r, (N, 48, 8, 8))
+        dY_dev = gu.dev(top)
+        for i in (2, 1, 0):
+            c, h, w, k, rr, ss, st_, p = layers[i]
+            lbt.lbt_backward_conv2d(X_dev[i], W_dev[i], dY_dev, N, c, h, w, k, rr, ss, st_, p, 0.0, True,
+                                    0.0, states[i], 40 + i, lbt.ROUND_STOCHASTIC | lbt.FUSED_UPDATE,
+                                    dXs_dev[i], dWs_dev[i], ws)
+            dY_dev = dXs_dev[i]                     # stays on the device
+        # the oracle, layer by layer, on what the device actually consumed
+        dY_host = top
+        for i in (2, 1, 0):
+            c, h, w, k, rr, ss, st_, p = layers[i]
+            ref = oracle.backward_conv2d(Xs[i], Ws[i], dY_host, st_, p, ostates[i], seed=40 + i,
+                                         rounding=oracle.STOCHASTIC)
+            oracle.update_interval(ostates[i])
+            gu.assert_state_equal(lbt.lbt_state_read(states[i]), ostates[i])
+            got_dx, got_dw = dXs_dev[i].cpu().numpy(), dWs_dev[i].cpu().numpy()
+            gu.assert_outputs_close(got_dx, ref.dX)
+            gu.assert_outputs_close(got_dw, ref.dW)
+            dY_host = got_dx
+    assert ostates[0].step == 3 and ostates[0].n_total == N * 32 * 16 * 16
