@@ -383,3 +383,41 @@ def test_chained_layers_consume_device_outputs():
             gu.assert_outputs_close(got_dw, ref.dW)
             dY_host = got_dx
     assert ostates[0].step == 3 and ostates[0].n_total == N * 32 * 16 * 16
+
+
+def test_calls_on_several_streams_with_their_own_workspaces():
+    """Independent layers issued round-robin on three streams (a workspace and a state each), as
+    the benchmark's multi-stream measurement does: the results do not depend on the overlap."""
+    cases = [(4, 16, 12, 12, 32, 3, 3, 1, 1), (8, 64, 14, 14, 160, 1, 1, 1, 0),
+             (3, 20, 10, 10, 24, 1, 1, 2, 0), (16, 16, 32, 32, 16, 3, 3, 1, 1),
+             (2, 24, 9, 9, 136, 3, 3, 2, 1), (5, 17, 6, 6, 33, 1, 1, 1, 0)]
+    r = synth.rng(0, 24, 0, 0)
+    streams = [torch.cuda.Stream() for _ in range(3)]
+    work = []
+    for i, (N, Cc, H, W, K, R, S, stride, pad) in enumerate(cases):
+        P, Q = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1
+        X, Wt = synth.relu_normal(r, (N, Cc, H, W)), synth.kaiming_normal(r, (K, Cc, R, S))
+        dY = synth.grad_cfg4(r, (N, K, P, Q))
+        work.append(dict(case=cases[i], X=X, W=Wt, dY=dY, dev=[gu.dev(a) for a in (X, Wt, dY)],
+                         dX=torch.empty(X.shape, device=gu.DEV), dW=torch.empty(Wt.shape, device=gu.DEV),
+                         st=lbt.new_state(gamma0=0.3), ost=oracle.GradState(gamma=0.3)))
+    spaces = [torch.zeros(max(lbt.lbt_workspace_bytes_conv2d(*w["case"]) for w in work),
+                          dtype=torch.uint8, device=gu.DEV) for _ in streams]
+    torch.cuda.synchronize()
+    for it in range(2):
+        for i, w in enumerate(work):
+            N, Cc, H, W, K, R, S, stride, pad = w["case"]
+            with torch.cuda.stream(streams[i % 3]):
+                lbt.lbt_backward_conv2d(w["dev"][0], w["dev"][1], w["dev"][2], N, Cc, H, W, K, R, S, stride,
+                                        pad, 0.0, True, 0.0, w["st"], 60 + i,
+                                        lbt.ROUND_STOCHASTIC | lbt.FUSED_UPDATE, w["dX"], w["dW"],
+                                        spaces[i % 3])
+        torch.cuda.synchronize()
+        for i, w in enumerate(work):
+            N, Cc, H, W, K, R, S, stride, pad = w["case"]
+            ref = oracle.backward_conv2d(w["X"], w["W"], w["dY"], stride, pad, w["ost"], seed=60 + i,
+                                         rounding=oracle.STOCHASTIC)
+            oracle.update_interval(w["ost"])
+            gu.assert_state_equal(lbt.lbt_state_read(w["st"]), w["ost"])
+            gu.assert_outputs_close(w["dX"].cpu().numpy(), ref.dX)
+            gu.assert_outputs_close(w["dW"].cpu().numpy(), ref.dW)
