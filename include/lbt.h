@@ -6,7 +6,13 @@
  * quantizer whose interval is gamma * max|dY| (Sec. 3.1), with gamma moved by
  * the clipping-factor update of Sec. 3.3 (Eq. 15-16, Alg. 1), then the two
  * integer contractions of the backward pass on the 4-bit codes and the
- * denormalisation of Eq. (4).
+ * denormalisation of Eq. (4).  Also: the quantized forward product of the same
+ * layers (Sec. 3.1), bit-widths 2..8 (Sec. 4.2 uses 4, 5, 6 and 8), and two options of
+ * the backward calls (interval update inside the call; single-sweep quantizer).
+ *
+ * A layer's calls may be issued on any stream; calls that share a workspace or a state must
+ * be ordered (same stream, or the caller's events).  Calls on different streams with
+ * workspaces and states of their own may overlap.
  *
  * Conventions for every entry point
  *   - Returns LBT_OK (0) or a negative LBT_ERR_* code.  Nothing throws.
