@@ -27,9 +27,11 @@
 //       fragment read touches fall into different banks;
 //   gathered pixels (B of dX): [chunk][row], 64 lanes read the granules of 64
 //       consecutive pixels (consecutive in memory) and a fragment read is contiguous.
-// Two LDS stages: while the matrix cores work on step s (fragments already in
-// registers), the loads of step s + 1 are in flight.  v_mfma_i32_32x32x32_i8, int32
-// accumulation, exact.
+// Two to four LDS stages: while the matrix cores work on step s (fragments already in
+// registers), the loads of the following steps are in flight.  v_mfma_i32_32x32x32_i8, int32
+// accumulation, exact.  The forward product of a convolution is the dX kernel with another
+// tap table (output pixel -> input pixel under the tap); that of a linear layer the dense-row
+// mode with the operands' roles exchanged.
 //
 // dW has a small output and a very long contraction: the contraction is split
 // over workgroups, each writes its partial tile with plain stores, and a second

@@ -1,19 +1,20 @@
-// Quantizer kernels: tensor maximum, uniform b=4 quantizer (Eq. 1-4 of the paper)
-// with nearest or stochastic rounding, clip-out count (Sec. 3.3, Alg. 1 step 5),
-// nibble packing in the flat format of the C ABI, byte-per-code granules in the two
-// GEMM layouts, and the one-thread clipping-factor update (Eq. 15-16).
+// Quantizer kernels: tensor maximum, uniform b-bit quantizer (Eq. 1-4 of the paper, b = 2..8,
+// 4 by default) with nearest or stochastic rounding, clip-out count (Sec. 3.3, Alg. 1 step 5),
+// the flat code format of the C ABI (nibbles up to 4 bits, bytes above), byte-per-code granules
+// in the GEMM layouts, and the one-thread clipping-factor update (Eq. 15-16).
 //
 // Arithmetic contract (decides integer codes, so it is fixed to the last bit):
 //   c      = (float)(gamma * (double)g_max)
-//   inv_s  = (float)((double)q / (double)c),  q = 7 (signed) or 15 (unsigned)
+//   inv_s  = (float)((double)q / (double)c),  q = 2^(b-1) - 1 (signed) or 2^b - 1 (unsigned)
 //   t      = clip(x) * inv_s                  -- one fp32 multiply, no FMA
 //   code   = rint(t)  |  (floor(t * 2^16) + r16) >> 16   (16 fractional bits)
 //   code   = clamp(code, -q or 0, q)
 //
 // A tensor is swept twice: k_absmax3 takes the maxima of up to three tensors in one
 // launch (one partial maximum per workgroup, no atomics), then a quantizer kernel
-// re-reduces those partials in its prologue and streams the tensor once more (the
-// second read mostly hits the memory-side cache).  The clip-out count travels in one
+// re-reduces those partials in its prologue and streams the tensor once more.  (With the
+// single-sweep flag the interval comes from the previous tensor's maximum instead and this
+// tensor's maximum is gathered during the one sweep.)  The clip-out count travels in one
 // 64-bit atomic per workgroup (count in the low 40 bits, arrival ticket above) on one of
 // 16 counters in the workspace, whose sums meet in a word of the layer state; k_absmax3
 // zeroes the counters and the last workgroup clears the word, so no scratch memory has to
