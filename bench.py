@@ -425,8 +425,6 @@ def main():
         if q and am:
             n_all = (0 if args.forward else n_grad) + sum(L.X.numel() + L.W.numel() for L in layers)
             t_ms = q["ms_per_step"] + am["ms_per_step"]
-            if "k_quantize_grad" in kernels:     # large gradients have a launch of their own
-                t_ms += kernels["k_quantize_grad"]["ms_per_step"]
             gbps = n_all * BYTES_PER_GRAD_ELEMENT / (t_ms * 1e-3) / 1e9
             out["quantize_pass"] = {"GBps": gbps, "frac_of_hbm_peak": gbps / PEAK_HBM_GBPS,
                                     "ms_per_step": t_ms, "bytes_per_element": BYTES_PER_GRAD_ELEMENT,

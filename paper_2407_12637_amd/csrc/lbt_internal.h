@@ -57,7 +57,7 @@ __device__ __forceinline__ void interval_update(lbt_grad_state* st) {
 
 // ---- profile.hip: optional event timing of every launch ------------------------
 enum KernelId {
-  KID_ABSMAX = 0, KID_FLAT_GRAD, KID_FLAT_OPERAND, KID_QUANTIZE_GRAD, KID_QUANTIZE_LAYER, KID_GEMM_DX,
+  KID_ABSMAX = 0, KID_FLAT_GRAD, KID_FLAT_OPERAND, KID_QUANTIZE_LAYER, KID_GEMM_DX,
   KID_GEMM_DW, KID_GEMM_FWD,
   KID_FINALIZE, KID_UPDATE, KID_STATE, KID_COUNT
 };

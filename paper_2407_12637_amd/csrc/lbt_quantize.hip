@@ -28,8 +28,6 @@ constexpr int kThreads = 256;
 constexpr uint32_t kInfBits = 0x7f800000u;
 constexpr unsigned long long kTicket = 1ull << 40;
 constexpr unsigned long long kCountMask = kTicket - 1;
-// gradient tensors of at least this many elements are quantized by a launch of their own
-constexpr double kOwnLaunchElements = 16.0 * 1024 * 1024;
 
 // ---------------------------------------------------------------------------
 // Philox4x32-10 (Salmon et al., SC'11): counter-based generator, 10 rounds.
@@ -903,31 +901,6 @@ __device__ __forceinline__ void run_segment(const Segment& sg, unsigned blk, uin
   }
 }
 
-// One tensor per launch, one tile kind per kernel: the large gradient tensors go through
-// these (measured: inside the multi-tensor kernel below the same loop runs at less than
-// half the speed on tensors of 25 M elements and more, while for small tensors the saved
-// launches matter more).
-template <int MODE, int KIND>
-__global__ __launch_bounds__(kThreads) void k_quantize_grad(const Segment sg) {
-  extern __shared__ __attribute__((aligned(16))) uint8_t dyn_tile[];
-  const unsigned local = blockIdx.x;
-  TileCoord bc;
-  bc.x = (int)(local % sg.gx);
-  const unsigned rest = local / sg.gx;
-  bc.y = (int)(rest % sg.gy);
-  bc.z = (int)(rest / sg.gy);
-  bc.n_blocks = sg.n_blocks;
-  bc.id = local;
-  bc.first = local == 0;
-  bc.gx = sg.gx;
-  bc.tiles = sg.gx * sg.gy * sg.gz;
-  if (KIND == kWindowed) stream_body<MODE, false>(sg.t, sg.pitch, sg.tl, bc, dyn_tile);
-  else if (KIND == kWholeRow) stream_body<MODE, true>(sg.t, sg.pitch, sg.tl, bc, dyn_tile);
-  else if (KIND == kGenericColumn) generic_body<MODE, 1>(sg.t, bc, dyn_tile);
-  else if (KIND == kMatrix) matrix_body<MODE>(sg.t, bc, dyn_tile);
-  else generic_body<MODE, 32>(sg.t, bc, dyn_tile);
-}
-
 // GMODE: 2 nearest / 3 stochastic gradient quantizer.  Activations and weights share ONE copy
 // of the operand code (signed or unsigned is a run-time field of the tensor): the kernel's
 // size counts, its workgroups run three different bodies side by side on a compute unit.
@@ -1106,33 +1079,6 @@ int launch_quantize_layer(const LayerTensors& q, hipStream_t s) {
   if (next == 0) return LBT_OK;
   const dim3 block(kThreads);
   const bool sr = q.rounding == LBT_ROUND_STOCHASTIC;
-  // a large gradient tensor gets a launch (and a lean kernel) of its own
-  const double n_grad = (double)q.tensor[0].A * (double)q.tensor[0].B * (double)q.tensor[0].L;
-  if (seg[0].n_blocks && n_grad >= kOwnLaunchElements) {
-    ProfScope prof(KID_QUANTIZE_GRAD, n_grad, s);
-    Segment one = seg[0];
-    const dim3 grid(one.n_blocks);
-    const size_t need = plan_segment(one);
-#define LBT_GRAD_CASE(KIND_)                                                              \
-    if (one.kind == KIND_) {                                                                \
-      if (sr) LBT_LAUNCH((k_quantize_grad<3, KIND_>), grid, block, need, s, one);           \
-      else LBT_LAUNCH((k_quantize_grad<2, KIND_>), grid, block, need, s, one);              \
-    }
-    LBT_GRAD_CASE(kWindowed)
-    LBT_GRAD_CASE(kWholeRow)
-    LBT_GRAD_CASE(kGenericColumn)
-    LBT_GRAD_CASE(kMatrix)
-    LBT_GRAD_CASE(kGenericTile)
-#undef LBT_GRAD_CASE
-    LBT_LAUNCH_CHECK();
-    // the others move up: the multi-tensor kernel sees an absent gradient
-    work -= n_grad;
-    next -= one.n_blocks;
-    seg[1].first -= one.n_blocks;
-    seg[2].first -= one.n_blocks;
-    seg[0] = Segment{};
-    if (next == 0) return LBT_OK;
-  }
   ProfScope prof(KID_QUANTIZE_LAYER, work, s);
   const dim3 grid((unsigned)next);
   if (sr) LBT_LAUNCH((k_quantize_layer<3>), grid, block, lds, s, seg[0], seg[1], seg[2]);

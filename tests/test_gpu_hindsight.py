@@ -157,8 +157,7 @@ def test_rejects_unknown_rounding_bits():
 
 
 def test_full_size_layer_single_sweep():
-    """The largest gradient tensor of the ResNet-50 sweep (51.4 M elements, the lean one-tensor
-    kernel): a two-sweep call records the maximum, the single-sweep call after it is checked in
+    """The largest gradient tensor of the ResNet-50 sweep (51.4 M elements): a two-sweep call records the maximum, the single-sweep call after it is checked in
     full on the statistics and on sampled outputs of both products."""
     L = [x for x in synth.resnet50_layers(64) if x.name == "l1.1x1.64-256@56"][0]
     _say("hindsight full-size", L.name)
