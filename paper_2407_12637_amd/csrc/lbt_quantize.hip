@@ -983,8 +983,9 @@ int launch_absmax3(const float* p0, int64_t n0, int abs0, const float* p1, int64
   if (!p2) n2 = 0;
   ProfScope prof(KID_ABSMAX, (double)(n0 + n1 + n2), s);
   const long long total = n0 + n1 + n2;
-  // at most ~1000 partial rows, so that a consumer's prologue reads 4 per thread
-  long long per = (total + 999) / 1000;
+  // at most ~512 partial rows (two workgroups per compute unit on a large layer), so that a
+  // consumer's prologue reads 2 per thread
+  long long per = (total + 511) / 512;
   per = (per + 8191) / 8192 * 8192;  // 256 threads x 8 float4
   if (per < 8192) per = 8192;
   const long long nb0 = (n0 + per - 1) / per, nb1 = (n1 + per - 1) / per, nb2 = (n2 + per - 1) / per;
