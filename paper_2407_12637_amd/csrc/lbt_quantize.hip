@@ -867,7 +867,7 @@ __device__ __forceinline__ void matrix_body(const TileArgs& t, const TileCoord& 
 // ---------------------------------------------------------------------------
 // One launch quantizes up to three tensors of a layer (output gradient, activations,
 // weights): workgroups [first, first + n_blocks) belong to a tensor and walk its tiles in
-// the order l fastest, then b, then a.
+// the order l fastest, then b, then a (matrix tiles: in the order of their indices).
 // ---------------------------------------------------------------------------
 enum TileKind { kGenericTile = 0, kGenericColumn, kWindowed, kWholeRow, kMatrix };
 
@@ -882,9 +882,15 @@ struct Segment {
 template <int MODE>
 __device__ __forceinline__ void run_segment(const Segment& sg, unsigned blk, uint8_t* lds) {
   const unsigned local = blk - sg.first;
+  // Workgroups are dealt to the eight dies round-robin by their index, and each die has its own
+  // L2.  Neighbouring windows of a row share the cache lines at their common edge whenever the
+  // rows do not start on line boundaries (28 x 28 and 14 x 14 maps), so a die is given a
+  // contiguous run of tiles: workgroups j, j + 8, j + 16, ... take consecutive tiles.
+  const unsigned per_die = sg.n_blocks >> 3, extra = sg.n_blocks & 7u, die = local & 7u;
+  const unsigned tile = die * per_die + min(die, extra) + (local >> 3);
   TileCoord bc;
-  bc.x = (int)(local % sg.gx);
-  const unsigned rest = local / sg.gx;
+  bc.x = (int)(tile % sg.gx);
+  const unsigned rest = tile / sg.gx;
   bc.y = (int)(rest % sg.gy);
   bc.z = (int)(rest / sg.gy);
   bc.n_blocks = sg.n_blocks;
