@@ -74,6 +74,12 @@ def parse():
     ap.add_argument("--workload", choices=["resnet50", "vit-l"], default="resnet50",
                     help="resnet50: the headline sweep (default); vit-l: the linear layers of one "
                          "ViT-L encoder block at batch 64 x 197 tokens (signed activations)")
+    ap.add_argument("--dense-codes", action="store_true",
+                    help="control: gradients uniform over the interval, so that all 15 codes "
+                         "occur (the heavy-tailed default leaves almost every code at 0)")
+    ap.add_argument("--per-layer", action="store_true",
+                    help="print a table: every layer shape of the sweep run on its own, "
+                         "kernel times against the layer's own rooflines; then exit")
     ap.add_argument("--copy-probe", action="store_true",
                     help="only run three plain 256 MiB device copies (calibrates the HBM byte "
                          "counters of a rocprofv3 --pmc run) and exit")
@@ -83,7 +89,7 @@ def parse():
 class LayerRun:
     """Device tensors and state of one layer occurrence."""
 
-    def __init__(self, spec, idx, torch, lbt, gen, is_linear, x_unsigned=True):
+    def __init__(self, spec, idx, torch, lbt, gen, is_linear, x_unsigned=True, dense=False):
         dev = "cuda"
         self.spec, self.is_linear, self.x_unsigned = spec, is_linear, x_unsigned
         f32 = torch.float32
@@ -97,12 +103,16 @@ class LayerRun:
         if x_unsigned:
             self.X.clamp_(min=0)        # post-ReLU activations, quantized with Eq. 3
         self.W = torch.randn(ws, generator=gen, device=dev, dtype=f32).mul_((2.0 / fan_in) ** 0.5)
-        # Student-t(nu) = Z / sqrt(chi2_nu / nu), chi2_nu = 2 * Gamma(nu / 2)
-        nu = 2.5
-        z = torch.randn(gs, generator=gen, device=dev, dtype=f32)
-        chi2 = torch._standard_gamma(torch.full(gs, nu / 2, device=dev, dtype=f32), generator=gen) * 2
-        self.dY = (z / (chi2 / nu).sqrt_()).mul_(1e-3)
-        del z, chi2
+        if dense:
+            # control: uniform over (-1e-3, 1e-3), every code equally likely
+            self.dY = torch.rand(gs, generator=gen, device=dev, dtype=f32).mul_(2e-3).sub_(1e-3)
+        else:
+            # Student-t(nu) = Z / sqrt(chi2_nu / nu), chi2_nu = 2 * Gamma(nu / 2)
+            nu = 2.5
+            z = torch.randn(gs, generator=gen, device=dev, dtype=f32)
+            chi2 = torch._standard_gamma(torch.full(gs, nu / 2, device=dev, dtype=f32), generator=gen) * 2
+            self.dY = (z / (chi2 / nu).sqrt_()).mul_(1e-3)
+            del z, chi2
         self.dX = torch.empty(xs, device=dev, dtype=f32)
         self.dW = torch.empty(ws, device=dev, dtype=f32)
         self.state = None
@@ -198,6 +208,99 @@ def cpu_baseline(layers, rounding, bits=4):
     }
 
 
+def per_layer_report(args, torch, lbt, synth, rounding, gen, vit):
+    """Every layer shape of the sweep on its own: the call is repeated over enough instances of
+    the layer (distinct tensors, > 600 MB together) that no cache serves the next call's reads,
+    with the library's event brackets on.  Times are per call; the products are rated against
+    the int8 peak and against the layer's own roofline max(ops / peak, algorithmic bytes / HBM
+    peak); the quantize pass (maximum + quantize launches over dY, X and W) at 4.5 B/element."""
+    table = synth.vit_l_layers(64) if vit else synth.resnet50_layers(64)
+    reps = 12
+    # marker overhead, as in the main run
+    lbt.lbt_profile_enable(True)
+    spare = lbt.new_state()
+    for _ in range(64):
+        lbt.lbt_update_interval(spare)
+    torch.cuda.synchronize()
+    cal = lbt.lbt_profile_read()["k_update_interval"]
+    lbt.lbt_profile_enable(False)
+    ov = max(cal[1] / cal[0] * 1e3 - UPDATE_KERNEL_US, 0.0)
+    head = ("%-24s %2s %7s | %7s %6s %5s | %7s %6s %5s %5s %1s | %7s %6s %5s %5s %1s"
+            % ("layer", "x", "n_dY(M)", "quant", "GB/s", "%HBM", "dX us", "TOPS", "%MFMA", "%roof",
+               "b", "dW us", "TOPS", "%MFMA", "%roof", "b"))
+    print(head)
+    print("-" * len(head))
+    tot = {"q_t": 0.0, "q_b": 0.0, "c_ops": 0.0, "c_t": 0.0, "all_ops": 0.0, "all_t": 0.0,
+           "roof_t": 0.0}
+    for spec in table:
+        if args.layer and args.layer not in spec.name:
+            continue
+        is_lin = isinstance(spec, synth.LinearLayer)
+        probe = LayerRun(spec, 0, torch, lbt, gen, is_lin, x_unsigned=not vit and args.bits < 8,
+                         dense=args.dense_codes)
+        per_inst = 4 * (2 * probe.X.numel() + 2 * probe.W.numel() + probe.dY.numel())
+        n_inst = min(max(2, -(-600_000_000 // per_inst)), 8)
+        Ls = [probe] + [LayerRun(spec, i, torch, lbt, gen, is_lin,
+                                 x_unsigned=not vit and args.bits < 8, dense=args.dense_codes)
+                        for i in range(1, n_inst)]
+        for L in Ls:
+            L.state = lbt.new_state(gamma0=args.gamma0, bits=args.bits)
+            if args.given_clips:
+                L.use_given_clips()
+        ws = torch.zeros(probe.ws_bytes(lbt), dtype=torch.uint8, device="cuda")
+        for L in Ls:
+            L.run(lbt, ws, rounding)
+        torch.cuda.synchronize()
+        lbt.lbt_profile_enable(True)
+        lbt.lbt_profile_read()
+        for r in range(reps):
+            Ls[r % n_inst].run(lbt, ws, rounding)
+        torch.cuda.synchronize()
+        prof = lbt.lbt_profile_read()
+        lbt.lbt_profile_enable(False)
+        us = {k: max((v[1] * 1e3 - ov * v[0]) / reps, 0.0) for k, v in prof.items()}
+        ng, nx, nw = probe.dY.numel(), probe.X.numel(), probe.W.numel()
+        ops = spec.gemm_ops
+        t_q = us.get("k_absmax3", 0.0) + us.get("k_quantize_layer", 0.0)
+        q_bytes = BYTES_PER_GRAD_ELEMENT * (ng + nx + nw)
+        t_dx = us.get("k_implicit_gemm(dX)", 0.0)
+        t_dw = us.get("k_implicit_gemm(dW)", 0.0) + us.get("k_splitk_reduce", 0.0)
+        cols = []
+        for t_us, byts in ((t_dx, 0.5 * ng + 0.5 * nw + 4.0 * nx), (t_dw, 0.5 * nx + 0.5 * ng + 4.0 * nw)):
+            t_c, t_m = ops / (PEAK_INT8_TOPS * 1e12), byts / (PEAK_HBM_GBPS * 1e9)
+            roof_us = max(t_c, t_m) * 1e6
+            tops = ops / (t_us * 1e-6) / 1e12
+            cols += [t_us, tops, 100 * tops / PEAK_INT8_TOPS, 100 * roof_us / t_us, "C" if t_c > t_m else "M"]
+            tot["all_ops"] += ops * spec.count
+            tot["all_t"] += t_us * spec.count
+            tot["roof_t"] += roof_us * spec.count
+            if t_c > t_m:
+                tot["c_ops"] += ops * spec.count
+                tot["c_t"] += t_us * spec.count
+        tot["q_t"] += t_q * spec.count
+        tot["q_b"] += q_bytes * spec.count
+        gbps = q_bytes / (t_q * 1e-6) / 1e9
+        print("%-24s %2d %7.2f | %7.1f %6.0f %5.1f | %7.1f %6.0f %5.1f %5.1f %1s | %7.1f %6.0f %5.1f %5.1f %1s"
+              % (spec.name, spec.count, ng / 1e6, t_q, gbps, 100 * gbps / PEAK_HBM_GBPS, *cols),
+              flush=True)
+        del Ls, probe, ws
+        torch.cuda.empty_cache()
+    print("-" * len(head))
+    print("x = occurrences in the network; quant = maximum + quantize launches of dY, X and W, rated at "
+          "4.5 B per element; %%roof = the layer's own roofline time max(ops / 5.0 POP/s, algorithmic "
+          "bytes / 8 TB/s) over the measured time; b = which of the two binds (C compute, M memory); "
+          "dW includes its split reduce.  Event-bracket overhead removed per launch: %.2f us." % ov)
+    summary = {
+        "quantize_pass_GBps": tot["q_b"] / (tot["q_t"] * 1e-6) / 1e9,
+        "products_TOPS": tot["all_ops"] / (tot["all_t"] * 1e-6) / 1e12,
+        "products_frac_of_layer_rooflines": tot["roof_t"] / tot["all_t"],
+        "compute_bound_products_TOPS": (tot["c_ops"] / (tot["c_t"] * 1e-6) / 1e12) if tot["c_t"] else None,
+        "compute_bound_products_frac_of_int8_peak":
+            (tot["c_ops"] / (tot["c_t"] * 1e-6) / 1e12 / PEAK_INT8_TOPS) if tot["c_t"] else None,
+    }
+    print("occurrence-weighted over the sweep:", json.dumps(summary))
+
+
 def measured_traffic(kernel_class):
     """HBM bytes per launch (fetched + written) of a kernel class, from the committed summary
     of the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this benchmark; None if absent."""
@@ -249,6 +352,12 @@ def main():
 
     rounding |= lbt.BITS(args.bits)
     vit = args.workload == "vit-l"
+    if args.per_layer:
+        if args.forward:
+            print("bench.py: --per-layer covers the backward calls", file=sys.stderr)
+            sys.exit(2)
+        per_layer_report(args, torch, lbt, synth, rounding, gen, vit)
+        return
     table = synth.vit_l_layers(64) if vit else synth.resnet50_layers(64)
     layers = []
     for spec in table:
@@ -257,7 +366,7 @@ def main():
         for _ in range(spec.count):
             layers.append(LayerRun(spec, len(layers), torch, lbt, gen,
                                    isinstance(spec, synth.LinearLayer),
-                                   x_unsigned=not vit and args.bits < 8))
+                                   x_unsigned=not vit and args.bits < 8, dense=args.dense_codes))
     for L in layers:
         L.state = lbt.new_state(gamma0=args.gamma0, bits=args.bits)
         if args.given_clips:
@@ -343,6 +452,8 @@ def main():
                                "value": gemm_ops / dt3 / 1e12, "unit": "TOPS"}
         del overlapped
         step = make_step(1)
+    if args.dense_codes:
+        out["config"]["workload"] += ", CONTROL: gradients uniform over the interval (dense codes)"
     if args.given_clips:
         out["config"]["workload"] += ", clip values of X and W given (no maximum taken)"
     if args.forward:
