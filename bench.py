@@ -74,6 +74,10 @@ def parse():
     ap.add_argument("--workload", choices=["resnet50", "vit-l"], default="resnet50",
                     help="resnet50: the headline sweep (default); vit-l: the linear layers of one "
                          "ViT-L encoder block at batch 64 x 197 tokens (signed activations)")
+    ap.add_argument("--saved-codes", action="store_true",
+                    help="the backward calls read the operand codes a forward call kept "
+                         "(lbt_forward_*_save before the timed region, lbt_backward_*_saved in it): "
+                         "X and W are not quantized again")
     ap.add_argument("--dense-codes", action="store_true",
                     help="control: gradients uniform over the interval, so that all 15 codes "
                          "occur (the heavy-tailed default leaves almost every code at 0)")
@@ -119,6 +123,24 @@ class LayerRun:
         self.seed = 1000 + idx
         self.c_x = self.c_w = 0.0            # <= 0: the call takes the tensor's maximum
         self.fan_in = fan_in
+        self.saved = None
+
+    def keep_codes(self, torch, lbt, flags):
+        """What the forward pass of the layer leaves behind: the codes of X and W in the layouts
+        the backward products read (no forward product here: Y = NULL)."""
+        s = self.spec
+        if self.is_linear:
+            self.saved = torch.zeros(lbt.lbt_saved_bytes_linear(s.M, s.K, s.N), dtype=torch.uint8,
+                                     device="cuda")
+            lbt.lbt_forward_linear_save(self.X, self.W, s.M, s.K, s.N, self.c_x, self.x_unsigned,
+                                        self.c_w, flags, None, None, None, self.saved, None)
+        else:
+            self.saved = torch.zeros(lbt.lbt_saved_bytes_conv2d(s.N, s.C, s.H, s.W, s.K, s.R, s.S,
+                                                                s.stride, s.pad),
+                                     dtype=torch.uint8, device="cuda")
+            lbt.lbt_forward_conv2d_save(self.X, self.W, s.N, s.C, s.H, s.W, s.K, s.R, s.S, s.stride,
+                                        s.pad, self.c_x, self.x_unsigned, self.c_w, flags, None,
+                                        None, None, self.saved, None)
 
     def use_given_clips(self):
         self.c_x, self.c_w = 3.0, 3.0 * (2.0 / self.fan_in) ** 0.5
@@ -148,7 +170,16 @@ class LayerRun:
         """One layer's backward and its interval update (inside the call when `rounding`
         carries LBT_FUSED_UPDATE, else as a call of its own)."""
         s = self.spec
-        if self.is_linear:
+        if self.saved is not None:
+            if self.is_linear:
+                lbt.lbt_backward_linear_saved(self.saved, self.dY, s.M, s.K, s.N, self.x_unsigned,
+                                              self.state, self.seed, rounding, self.dX, self.dW,
+                                              None, None, ws)
+            else:
+                lbt.lbt_backward_conv2d_saved(self.saved, self.dY, s.N, s.C, s.H, s.W, s.K, s.R, s.S,
+                                              s.stride, s.pad, self.x_unsigned, self.state,
+                                              self.seed, rounding, self.dX, self.dW, None, None, ws)
+        elif self.is_linear:
             lbt.lbt_backward_linear(self.X, self.W, self.dY, s.M, s.K, s.N, self.c_x, self.x_unsigned,
                                     self.c_w, self.state, self.seed, rounding, self.dX, self.dW, ws)
         else:
@@ -247,6 +278,8 @@ def per_layer_report(args, torch, lbt, synth, rounding, gen, vit):
             L.state = lbt.new_state(gamma0=args.gamma0, bits=args.bits)
             if args.given_clips:
                 L.use_given_clips()
+            if args.saved_codes:
+                L.keep_codes(torch, lbt, lbt.BITS(args.bits))
         ws = torch.zeros(probe.ws_bytes(lbt), dtype=torch.uint8, device="cuda")
         for L in Ls:
             L.run(lbt, ws, rounding)
@@ -262,7 +295,7 @@ def per_layer_report(args, torch, lbt, synth, rounding, gen, vit):
         ng, nx, nw = probe.dY.numel(), probe.X.numel(), probe.W.numel()
         ops = spec.gemm_ops
         t_q = us.get("k_absmax3", 0.0) + us.get("k_quantize_layer", 0.0)
-        q_bytes = BYTES_PER_GRAD_ELEMENT * (ng + nx + nw)
+        q_bytes = BYTES_PER_GRAD_ELEMENT * (ng if args.saved_codes else ng + nx + nw)
         t_dx = us.get("k_implicit_gemm(dX)", 0.0)
         t_dw = us.get("k_implicit_gemm(dW)", 0.0) + us.get("k_splitk_reduce", 0.0)
         cols = []
@@ -371,6 +404,8 @@ def main():
         L.state = lbt.new_state(gamma0=args.gamma0, bits=args.bits)
         if args.given_clips:
             L.use_given_clips()
+        if args.saved_codes and not args.forward:
+            L.keep_codes(torch, lbt, lbt.BITS(args.bits))
     ws = torch.zeros(max(L.ws_bytes(lbt, args.forward) for L in layers), dtype=torch.uint8,
                      device="cuda")
     gemm_ops = sum(2.0 * L.spec.gemm_ops for L in layers)       # dX and dW
@@ -452,6 +487,9 @@ def main():
                                "value": gemm_ops / dt3 / 1e12, "unit": "TOPS"}
         del overlapped
         step = make_step(1)
+    if args.saved_codes:
+        out["config"]["workload"] += (", X and W codes kept by the forward pass (not quantized "
+                                      "again in the backward calls)")
     if args.dense_codes:
         out["config"]["workload"] += ", CONTROL: gradients uniform over the interval (dense codes)"
     if args.given_clips:
@@ -534,7 +572,8 @@ def main():
         # quantized element
         q, am = kernels.get("k_quantize_layer"), kernels.get("k_absmax3")
         if q and am:
-            n_all = (0 if args.forward else n_grad) + sum(L.X.numel() + L.W.numel() for L in layers)
+            n_all = (0 if args.forward else n_grad) + (0 if args.saved_codes else
+                                                       sum(L.X.numel() + L.W.numel() for L in layers))
             t_ms = q["ms_per_step"] + am["ms_per_step"]
             gbps = n_all * BYTES_PER_GRAD_ELEMENT / (t_ms * 1e-3) / 1e9
             out["quantize_pass"] = {"GBps": gbps, "frac_of_hbm_peak": gbps / PEAK_HBM_GBPS,
@@ -558,7 +597,7 @@ def main():
                                    "ms_per_step": t_ms, "roofline_ms_per_step": t_roof * 1e3,
                                    "frac_of_layer_rooflines": t_roof * 1e3 / t_ms}
 
-    if not (args.no_cpu_baseline or args.single_sweep or args.forward or args.given_clips):   # the oracle is timed on the paper's mode
+    if not (args.no_cpu_baseline or args.single_sweep or args.forward or args.given_clips or args.saved_codes):   # the oracle is timed on the paper's mode
         out["cpu_baseline"] = cpu_baseline(layers, rounding & lbt.ROUND_STOCHASTIC, args.bits)
 
     print(json.dumps(out))

@@ -207,8 +207,8 @@ size_t lbt_workspace_bytes_conv2d(int64_t N, int64_t C, int64_t H, int64_t Wd, i
  * receives LBT_STATUS_OK, or LBT_STATUS_NONFINITE when a tensor whose maximum was taken
  * holds NaN / Inf (its codes are then all 0, so Y is 0).  The sums are exact:
  * LBT_ERR_OVERFLOW if K_in (C*R*S) * q * q_x could reach 2^31; LBT_ERR_UNSUPPORTED for
- * unsigned X at b = 8.  The codes stay in the workspace only: the backward call quantizes
- * X and W again in the layouts its own products read.
+ * unsigned X at b = 8.  The codes stay in the workspace only; lbt_forward_*_save below keeps
+ * them for the backward call.
  */
 int lbt_forward_linear(const float* X, const float* W, int64_t M, int64_t K_in, int64_t N_out,
                        float c_x, int x_unsigned, float c_w, int flags, float* Y, int32_t* acc_Y,
@@ -220,6 +220,46 @@ int lbt_forward_conv2d(const float* X, const float* W, int64_t N, int64_t C, int
                        int32_t* status, void* ws, size_t ws_bytes, void* stream);
 size_t lbt_workspace_bytes_forward_conv2d(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K,
                                           int64_t R, int64_t S, int64_t stride, int64_t pad);
+
+/*
+ * Forward pass that keeps the quantized operands for the layer's backward pass (Sec. 3.1: the
+ * weights and activations are quantized once, in the forward pass; the backward products of
+ * the layer read the same quantized tensors).  As lbt_forward_linear / lbt_forward_conv2d, and
+ * in the same quantize launch the codes of X in the layout dW reads and of W in the layout dX
+ * reads go to `saved` (device memory of the caller, lbt_saved_bytes_*(same shape) bytes,
+ * 256-byte aligned, opaque; it also holds the two clip values and the non-finite flags).
+ * Y may be NULL: then only the codes are produced (no product; acc_Y and status must be NULL,
+ * ws may be NULL).
+ *
+ * lbt_backward_*_saved: the backward call without X and W: dY goes through the gradient
+ * quantizer exactly as in lbt_backward_*, the products read `saved`.  Same geometry, bit-width
+ * (LBT_BITS in `rounding` = the `flags` of the saving call) and x_unsigned as the call that
+ * wrote `saved`; results are identical to lbt_backward_* on the same X, W, c_x, c_w.  A
+ * non-finite X or W seen while saving gives LBT_STATUS_NONFINITE in *st here.  acc_dX / acc_dW
+ * (may be NULL) as in lbt_backward_*_acc.  ws: lbt_workspace_bytes_linear / _conv2d.
+ * `saved` is only read: several backward calls may use it.
+ */
+size_t lbt_saved_bytes_linear(int64_t M, int64_t K_in, int64_t N_out);
+size_t lbt_saved_bytes_conv2d(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R,
+                              int64_t S, int64_t stride, int64_t pad);
+int lbt_forward_linear_save(const float* X, const float* W, int64_t M, int64_t K_in,
+                            int64_t N_out, float c_x, int x_unsigned, float c_w, int flags,
+                            float* Y, int32_t* acc_Y, int32_t* status, void* saved,
+                            size_t saved_bytes, void* ws, size_t ws_bytes, void* stream);
+int lbt_forward_conv2d_save(const float* X, const float* W, int64_t N, int64_t C, int64_t H,
+                            int64_t Wd, int64_t K, int64_t R, int64_t S, int64_t stride,
+                            int64_t pad, float c_x, int x_unsigned, float c_w, int flags,
+                            float* Y, int32_t* acc_Y, int32_t* status, void* saved,
+                            size_t saved_bytes, void* ws, size_t ws_bytes, void* stream);
+int lbt_backward_linear_saved(const void* saved, size_t saved_bytes, const float* dY, int64_t M,
+                              int64_t K_in, int64_t N_out, int x_unsigned, lbt_grad_state* st,
+                              uint64_t seed, int rounding, float* dX, float* dW, int32_t* acc_dX,
+                              int32_t* acc_dW, void* ws, size_t ws_bytes, void* stream);
+int lbt_backward_conv2d_saved(const void* saved, size_t saved_bytes, const float* dY, int64_t N,
+                              int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S,
+                              int64_t stride, int64_t pad, int x_unsigned, lbt_grad_state* st,
+                              uint64_t seed, int rounding, float* dX, float* dW, int32_t* acc_dX,
+                              int32_t* acc_dW, void* ws, size_t ws_bytes, void* stream);
 
 /*
  * The same two calls with the raw int32 accumulators also written out

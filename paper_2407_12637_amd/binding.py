@@ -80,6 +80,16 @@ SIGNATURES = {
     "lbt_forward_conv2d": (_int, [_p, _p] + [_i64] * 9 + [_f32, _int, _f32, _int, _p, _p, _p, _p,
                                                           _sz, _p]),
     "lbt_workspace_bytes_forward_conv2d": (_sz, [_i64] * 9),
+    "lbt_saved_bytes_linear": (_sz, [_i64, _i64, _i64]),
+    "lbt_saved_bytes_conv2d": (_sz, [_i64] * 9),
+    "lbt_forward_linear_save": (_int, [_p, _p, _i64, _i64, _i64, _f32, _int, _f32, _int, _p, _p, _p,
+                                       _p, _sz, _p, _sz, _p]),
+    "lbt_forward_conv2d_save": (_int, [_p, _p] + [_i64] * 9 + [_f32, _int, _f32, _int, _p, _p, _p,
+                                                               _p, _sz, _p, _sz, _p]),
+    "lbt_backward_linear_saved": (_int, [_p, _sz, _p, _i64, _i64, _i64, _int, _p, _u64, _int,
+                                         _p, _p, _p, _p, _p, _sz, _p]),
+    "lbt_backward_conv2d_saved": (_int, [_p, _sz, _p] + [_i64] * 9 + [_int, _p, _u64, _int,
+                                                                      _p, _p, _p, _p, _p, _sz, _p]),
     "lbt_profile_enable": (_int, [_int]),
     "lbt_profile_kernel_count": (_int, []),
     "lbt_profile_kernel_name": (C.c_char_p, [_int]),
@@ -244,6 +254,54 @@ def lbt_forward_conv2d(X, W, N, Cc, H, Wd, K, R, S, stride, pad, c_x, x_unsigned
     _check(load().lbt_forward_conv2d(_dp(X), _dp(W), N, Cc, H, Wd, K, R, S, stride, pad, c_x,
                                      int(x_unsigned), c_w, flags, _dp(Y), _dp(acc_Y), _dp(status),
                                      wp, wb, _stream()), "lbt_forward_conv2d")
+
+
+def lbt_saved_bytes_linear(M, K_in, N_out) -> int:
+    return load().lbt_saved_bytes_linear(M, K_in, N_out)
+
+
+def lbt_saved_bytes_conv2d(N, Cc, H, W, K, R, S, stride, pad) -> int:
+    return load().lbt_saved_bytes_conv2d(N, Cc, H, W, K, R, S, stride, pad)
+
+
+def lbt_forward_linear_save(X, W, M, K_in, N_out, c_x, x_unsigned, c_w, flags, Y, acc_Y, status,
+                            saved, ws):
+    """Y (and ws) may be None: only the codes for the backward call are produced."""
+    wp, wb = _ws_args(ws) if ws is not None else (None, 0)
+    sp, sb = _ws_args(saved)
+    _check(load().lbt_forward_linear_save(_dp(X), _dp(W), M, K_in, N_out, c_x, int(x_unsigned), c_w,
+                                          flags, _dp(Y), _dp(acc_Y), _dp(status), sp, sb, wp, wb,
+                                          _stream()), "lbt_forward_linear_save")
+
+
+def lbt_forward_conv2d_save(X, W, N, Cc, H, Wd, K, R, S, stride, pad, c_x, x_unsigned, c_w, flags,
+                            Y, acc_Y, status, saved, ws):
+    wp, wb = _ws_args(ws) if ws is not None else (None, 0)
+    sp, sb = _ws_args(saved)
+    _check(load().lbt_forward_conv2d_save(_dp(X), _dp(W), N, Cc, H, Wd, K, R, S, stride, pad, c_x,
+                                          int(x_unsigned), c_w, flags, _dp(Y), _dp(acc_Y),
+                                          _dp(status), sp, sb, wp, wb, _stream()),
+           "lbt_forward_conv2d_save")
+
+
+def lbt_backward_linear_saved(saved, dY, M, K_in, N_out, x_unsigned, st, seed, rounding, dX, dW,
+                              acc_dX, acc_dW, ws):
+    wp, wb = _ws_args(ws)
+    sp, sb = _ws_args(saved)
+    _check(load().lbt_backward_linear_saved(sp, sb, _dp(dY), M, K_in, N_out, int(x_unsigned),
+                                            _dp(st), seed, rounding, _dp(dX), _dp(dW), _dp(acc_dX),
+                                            _dp(acc_dW), wp, wb, _stream()),
+           "lbt_backward_linear_saved")
+
+
+def lbt_backward_conv2d_saved(saved, dY, N, Cc, H, Wd, K, R, S, stride, pad, x_unsigned, st, seed,
+                              rounding, dX, dW, acc_dX, acc_dW, ws):
+    wp, wb = _ws_args(ws)
+    sp, sb = _ws_args(saved)
+    _check(load().lbt_backward_conv2d_saved(sp, sb, _dp(dY), N, Cc, H, Wd, K, R, S, stride, pad,
+                                            int(x_unsigned), _dp(st), seed, rounding, _dp(dX),
+                                            _dp(dW), _dp(acc_dX), _dp(acc_dW), wp, wb, _stream()),
+           "lbt_backward_conv2d_saved")
 
 
 def lbt_profile_enable(on: bool):

@@ -35,6 +35,23 @@ ConvWorkspace conv_workspace(const ConvGeom& g, bool is_linear) {
   return w;
 }
 
+// Operand codes kept from the forward pass for the layer's backward call: a header like the
+// workspace's (clip values and non-finite flags of X and W; partial maxima while saving),
+// then X in the layout dW reads and W in the layout dX reads.
+struct SavedLayout {
+  size_t off_x, off_w, total;
+};
+SavedLayout saved_layout(const ConvGeom& g) {
+  SavedLayout w{};
+  size_t o = kWsHeaderBytes;
+  w.off_x = o;
+  o += pad256((size_t)g.C * g.H * g.W * g.Np);
+  w.off_w = o;
+  o += pad256((size_t)g.C * g.R * g.S * g.Kp);
+  w.total = o;
+  return w;
+}
+
 int make_geom(int64_t N, int64_t C, int64_t H, int64_t W, int64_t K, int64_t R, int64_t S,
               int64_t stride, int64_t pad, ConvGeom* out) {
   if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || K <= 0 || R <= 0 || S <= 0 || stride <= 0 || pad < 0)
@@ -66,9 +83,11 @@ bool split_flags(int rounding, int* bits) {
 int backward_common(const float* X, const float* W, const float* dY, ConvGeom g,
                     bool w_is_ck, float c_x, int x_unsigned, float c_w, lbt_grad_state* st,
                     uint64_t seed, int rounding, float* dX, float* dW, int32_t* acc_dX,
-                    int32_t* acc_dW, void* ws, size_t ws_bytes, void* stream) {
-  if (!W || !dY || !st || !ws) return LBT_ERR_NULL;
-  if (dW && !X) return LBT_ERR_NULL;
+                    int32_t* acc_dW, void* ws, size_t ws_bytes, void* stream,
+                    const void* saved = nullptr, size_t saved_bytes = 0) {
+  // saved: X and W were quantized by a forward call (lbt_forward_*_save); X, W, c_x, c_w unused
+  if (!dY || !st || !ws) return LBT_ERR_NULL;
+  if (!saved && (!W || (dW && !X))) return LBT_ERR_NULL;
   if ((acc_dX && !dX) || (acc_dW && !dW)) return LBT_ERR_NULL;
   int bits;
   if (!split_flags(rounding, &bits)) return LBT_ERR_UNSUPPORTED;
@@ -78,11 +97,14 @@ int backward_common(const float* X, const float* W, const float* dY, ConvGeom g,
   const int hindsight = (rounding & LBT_HINDSIGHT_MAX) ? 1 : 0;
   const int fused_update = (rounding & LBT_FUSED_UPDATE) ? 1 : 0;
   rounding &= LBT_ROUND_STOCHASTIC;
-  if (!aligned(dY, 16) || !aligned(W, 16) || (X && !aligned(X, 16)) || !aligned(ws, 256) ||
-      (dX && !aligned(dX, 16)) || (dW && !aligned(dW, 16)) || !aligned(st, 8))
+  if (!aligned(dY, 16) || (W && !aligned(W, 16)) || (X && !aligned(X, 16)) || !aligned(ws, 256) ||
+      (dX && !aligned(dX, 16)) || (dW && !aligned(dW, 16)) || !aligned(st, 8) ||
+      (saved && !aligned(saved, 256)))
     return LBT_ERR_ALIGN;
   const ConvWorkspace lay = conv_workspace(g, w_is_ck);
   if (ws_bytes < lay.total) return LBT_ERR_WORKSPACE;
+  const SavedLayout kept = saved_layout(g);
+  if (saved && saved_bytes < kept.total) return LBT_ERR_WORKSPACE;
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   uint8_t* base = static_cast<uint8_t*>(ws);
   OperandScalars* sc = reinterpret_cast<OperandScalars*>(base + lay.off_scalars);
@@ -91,6 +113,12 @@ int backward_common(const float* X, const float* W, const float* dY, ConvGeom g,
   uint8_t* x_chwn = base + lay.off_x_chwn;
   uint8_t* w_crsk = base + lay.off_w_crsk;
   int32_t* partial = reinterpret_cast<int32_t*>(base + lay.off_partial);
+  if (saved) {
+    uint8_t* kept_base = const_cast<uint8_t*>(static_cast<const uint8_t*>(saved));
+    sc = reinterpret_cast<OperandScalars*>(kept_base);
+    x_chwn = kept_base + kept.off_x;
+    w_crsk = kept_base + kept.off_w;
+  }
 
   uint32_t* pmax = reinterpret_cast<uint32_t*>(base + kWsScalarsBytes);
   const int64_t n_dy = (int64_t)g.N * g.K * g.P * g.Q;
@@ -98,13 +126,14 @@ int backward_common(const float* X, const float* W, const float* dY, ConvGeom g,
   const int64_t n_w = (int64_t)g.K * g.C * g.R * g.S;
   const int64_t PQ = (int64_t)g.P * g.Q, HW = (int64_t)g.H * g.W, RS = (int64_t)g.R * g.S;
   int rc, nblocks = 0;
-  const bool want_cw = dX && !(c_w > 0.0f), want_cx = dW && !(c_x > 0.0f);
+  const bool want_cw = !saved && dX && !(c_w > 0.0f), want_cx = !saved && dW && !(c_x > 0.0f);
   // Tensor shapes as the re-layout sees them: T[A][B][L], L contiguous
   const int64_t wA = w_is_ck ? g.C : g.K, wB = w_is_ck ? g.K : g.C, wL = w_is_ck ? 1 : RS;
   // 1. maxima of dY (unless the previous tensor's maximum is to be used), and of X / W where
   //    no clip value was given, in one launch
   if ((rc = launch_absmax3(hindsight ? nullptr : dY, n_dy, 1, want_cx ? X : nullptr, n_x, x_unsigned ? 0 : 1,
-                           want_cw ? W : nullptr, n_w, 1, pmax, &nblocks, st, s)))
+                           want_cw ? W : nullptr, n_w, 1, pmax, &nblocks, st, s,
+                           saved ? sc : nullptr, (dW ? 1 : 0) | (dX ? 2 : 0))))
     return rc;
   // 2. codes of all three tensors in the layouts the two products read, one launch:
   //    gradient for both products, activations for dW, weights for dX (convolution weights
@@ -119,10 +148,10 @@ int backward_common(const float* X, const float* W, const float* dY, ConvGeom g,
     q.tensor[0] = {dY, g.N, g.K, PQ,
                    RelayoutIo{pmax, nblocks, 0, st, dX ? g_npqk : nullptr, dW ? g_kpqn : nullptr, 0},
                    0.0f, nullptr, nullptr};
-    if (dW)
+    if (dW && !saved)
       q.tensor[1] = {X, g.N, g.C, HW, RelayoutIo{pmax, nblocks, 1, st, nullptr, x_chwn, 0},
                      c_x, &sc->c_x, &sc->bad_x};
-    if (dX)
+    if (dX && !saved)
       q.tensor[2] = {W, wA, wB, wL,
                      RelayoutIo{pmax, nblocks, 2, st, w_is_ck ? w_crsk : nullptr,
                                 w_is_ck ? nullptr : w_crsk, 1},
@@ -170,23 +199,36 @@ ForwardWorkspace forward_workspace(const ConvGeom& g) {
 
 int forward_common(const float* X, const float* W, ConvGeom g, bool is_linear, float c_x,
                    int x_unsigned, float c_w, int flags, float* Y, int32_t* acc_Y, int32_t* status,
-                   void* ws, size_t ws_bytes, void* stream) {
-  if (!X || !W || !Y || !ws) return LBT_ERR_NULL;
+                   void* ws, size_t ws_bytes, void* stream, void* saved = nullptr,
+                   size_t saved_bytes = 0, bool save_call = false) {
+  // save_call: the codes the backward products read are also written to `saved`; Y may then be
+  // NULL (no product, no workspace: the maxima go through the header of `saved`)
+  const bool product = Y != nullptr;
+  if (!X || !W) return LBT_ERR_NULL;
+  if (!save_call && (!Y || !ws)) return LBT_ERR_NULL;
+  if (save_call && (!saved || (product && !ws) || (!product && (acc_Y || status)))) return LBT_ERR_NULL;
   int bits;
   if ((flags & ~LBT_BITS(15)) || !split_flags(flags, &bits)) return LBT_ERR_UNSUPPORTED;
   if (x_unsigned && bits == 8) return LBT_ERR_UNSUPPORTED;
   g.bits = bits;
-  if (!aligned(X, 16) || !aligned(W, 16) || !aligned(Y, 16) || !aligned(ws, 256) ||
-      (acc_Y && !aligned(acc_Y, 16)) || (status && !aligned(status, 4)))
+  if (!aligned(X, 16) || !aligned(W, 16) || (Y && !aligned(Y, 16)) || (ws && !aligned(ws, 256)) ||
+      (acc_Y && !aligned(acc_Y, 16)) || (status && !aligned(status, 4)) ||
+      (saved && !aligned(saved, 256)))
     return LBT_ERR_ALIGN;
   const ForwardWorkspace lay = forward_workspace(g);
-  if (ws_bytes < lay.total) return LBT_ERR_WORKSPACE;
+  if (product && ws_bytes < lay.total) return LBT_ERR_WORKSPACE;
+  const SavedLayout kept = saved_layout(g);
+  if (saved && saved_bytes < kept.total) return LBT_ERR_WORKSPACE;
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-  uint8_t* base = static_cast<uint8_t*>(ws);
-  OperandScalars* sc = reinterpret_cast<OperandScalars*>(base);
-  uint32_t* pmax = reinterpret_cast<uint32_t*>(base + kWsScalarsBytes);
-  uint8_t* x_codes = base + lay.off_x;
-  uint8_t* w_codes = base + lay.off_w;
+  // scalars and partial maxima: in the header of `saved` when there is one (the backward call
+  // reads the clip values there), else in the workspace
+  uint8_t* head = saved ? static_cast<uint8_t*>(saved) : static_cast<uint8_t*>(ws);
+  OperandScalars* sc = reinterpret_cast<OperandScalars*>(head);
+  uint32_t* pmax = reinterpret_cast<uint32_t*>(head + kWsScalarsBytes);
+  uint8_t* x_codes = product ? static_cast<uint8_t*>(ws) + lay.off_x : nullptr;
+  uint8_t* w_codes = product ? static_cast<uint8_t*>(ws) + lay.off_w : nullptr;
+  uint8_t* x_kept = saved ? static_cast<uint8_t*>(saved) + kept.off_x : nullptr;   // [C][Np/16][HW][16]
+  uint8_t* w_kept = saved ? static_cast<uint8_t*>(saved) + kept.off_w : nullptr;   // [C][RS][Kp/16][16]
   const int64_t HW = (int64_t)g.H * g.W, RS = (int64_t)g.R * g.S;
   const int64_t n_x = (int64_t)g.N * g.C * HW, n_w = (int64_t)g.K * g.C * RS;
   int rc, nblocks = 0;
@@ -197,15 +239,18 @@ int forward_common(const float* X, const float* W, ConvGeom g, bool is_linear, f
   q.rounding = LBT_ROUND_NEAREST;
   q.x_unsigned = x_unsigned;
   q.bits = bits;
-  q.tensor[1] = {X, g.N, g.C, HW, RelayoutIo{pmax, nblocks, 1, nullptr, x_codes, nullptr, 0, 0},
+  q.tensor[1] = {X, g.N, g.C, HW, RelayoutIo{pmax, nblocks, 1, nullptr, x_codes, x_kept, 0, 0},
                  c_x, &sc->c_x, &sc->bad_x};
-  if (is_linear)   // W[K_in][N_out]: rows of W^T, sixteen consecutive k_in per granule
-    q.tensor[2] = {W, g.C, g.K, 1, RelayoutIo{pmax, nblocks, 2, nullptr, nullptr, w_codes, 0, 0},
+  if (is_linear)   // W[K_in][N_out]: rows of W^T, sixteen consecutive k_in per granule;
+                   // kept for dX as rows of W, sixteen consecutive n_out per granule
+    q.tensor[2] = {W, g.C, g.K, 1, RelayoutIo{pmax, nblocks, 2, nullptr, w_kept, w_codes, 0, 0},
                    c_w, &sc->c_w, &sc->bad_w};
-  else             // W[K][C][R*S]: tap-major rows, sixteen consecutive c per granule
-    q.tensor[2] = {W, g.K, g.C, RS, RelayoutIo{pmax, nblocks, 2, nullptr, w_codes, nullptr, 0, 1},
+  else             // W[K][C][R*S]: tap-major rows, sixteen consecutive c per granule;
+                   // kept for dX tap-major with sixteen consecutive k per granule
+    q.tensor[2] = {W, g.K, g.C, RS, RelayoutIo{pmax, nblocks, 2, nullptr, w_codes, w_kept, 1, 1},
                    c_w, &sc->c_w, &sc->bad_w};
   if ((rc = launch_quantize_layer(q, s))) return rc;
+  if (!product) return LBT_OK;
   return is_linear ? launch_linear_fwd(g.N, g.C, g.K, bits, x_codes, w_codes, sc, x_unsigned, Y, acc_Y,
                                        status, s)
                    : launch_conv_fwd(g, w_codes, x_codes, sc, x_unsigned, Y, acc_Y, status, s);
@@ -364,6 +409,67 @@ int lbt_forward_linear(const float* X, const float* W, int64_t M, int64_t K_in, 
   if (rc) return rc;
   return forward_common(X, W, g, true, c_x, x_unsigned, c_w, flags, Y, acc_Y, status, ws, ws_bytes,
                         stream);
+}
+
+size_t lbt_saved_bytes_conv2d(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R,
+                              int64_t S, int64_t stride, int64_t pad) {
+  ConvGeom g;
+  if (make_geom(N, C, H, Wd, K, R, S, stride, pad, &g) != LBT_OK) return 0;
+  return saved_layout(g).total;
+}
+
+size_t lbt_saved_bytes_linear(int64_t M, int64_t K_in, int64_t N_out) {
+  ConvGeom g;
+  if (make_geom(M, K_in, 1, 1, N_out, 1, 1, 1, 0, &g) != LBT_OK) return 0;
+  return saved_layout(g).total;
+}
+
+int lbt_forward_conv2d_save(const float* X, const float* W, int64_t N, int64_t C, int64_t H,
+                            int64_t Wd, int64_t K, int64_t R, int64_t S, int64_t stride, int64_t pad,
+                            float c_x, int x_unsigned, float c_w, int flags, float* Y, int32_t* acc_Y,
+                            int32_t* status, void* saved, size_t saved_bytes, void* ws,
+                            size_t ws_bytes, void* stream) {
+  ConvGeom g;
+  const int rc = make_geom(N, C, H, Wd, K, R, S, stride, pad, &g);
+  if (rc) return rc;
+  return forward_common(X, W, g, false, c_x, x_unsigned, c_w, flags, Y, acc_Y, status, ws, ws_bytes,
+                        stream, saved, saved_bytes, true);
+}
+
+int lbt_forward_linear_save(const float* X, const float* W, int64_t M, int64_t K_in, int64_t N_out,
+                            float c_x, int x_unsigned, float c_w, int flags, float* Y, int32_t* acc_Y,
+                            int32_t* status, void* saved, size_t saved_bytes, void* ws,
+                            size_t ws_bytes, void* stream) {
+  ConvGeom g;
+  const int rc = make_geom(M, K_in, 1, 1, N_out, 1, 1, 1, 0, &g);
+  if (rc) return rc;
+  return forward_common(X, W, g, true, c_x, x_unsigned, c_w, flags, Y, acc_Y, status, ws, ws_bytes,
+                        stream, saved, saved_bytes, true);
+}
+
+int lbt_backward_conv2d_saved(const void* saved, size_t saved_bytes, const float* dY, int64_t N,
+                              int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S,
+                              int64_t stride, int64_t pad, int x_unsigned, lbt_grad_state* st,
+                              uint64_t seed, int rounding, float* dX, float* dW, int32_t* acc_dX,
+                              int32_t* acc_dW, void* ws, size_t ws_bytes, void* stream) {
+  if (!saved) return LBT_ERR_NULL;
+  ConvGeom g;
+  int rc = make_geom(N, C, H, Wd, K, R, S, stride, pad, &g);
+  if (rc) return rc;
+  return backward_common(nullptr, nullptr, dY, g, false, 0.0f, x_unsigned, 0.0f, st, seed, rounding,
+                         dX, dW, acc_dX, acc_dW, ws, ws_bytes, stream, saved, saved_bytes);
+}
+
+int lbt_backward_linear_saved(const void* saved, size_t saved_bytes, const float* dY, int64_t M,
+                              int64_t K_in, int64_t N_out, int x_unsigned, lbt_grad_state* st,
+                              uint64_t seed, int rounding, float* dX, float* dW, int32_t* acc_dX,
+                              int32_t* acc_dW, void* ws, size_t ws_bytes, void* stream) {
+  if (!saved) return LBT_ERR_NULL;
+  ConvGeom g;
+  int rc = make_geom(M, K_in, 1, 1, N_out, 1, 1, 1, 0, &g);
+  if (rc) return rc;
+  return backward_common(nullptr, nullptr, dY, g, true, 0.0f, x_unsigned, 0.0f, st, seed, rounding,
+                         dX, dW, acc_dX, acc_dW, ws, ws_bytes, stream, saved, saved_bytes);
 }
 
 int lbt_backward_conv2d_acc(const float* X, const float* W, const float* dY, int64_t N, int64_t C,

@@ -97,7 +97,8 @@ constexpr size_t kWsHeaderBytes = kWsScalarsBytes + (size_t)kMaxPartialBlocks * 
 // state the kernel is launched even when every tensor is absent.
 int launch_absmax3(const float* p0, int64_t n0, int abs0, const float* p1, int64_t n1, int abs1,
                    const float* p2, int64_t n2, int abs2, uint32_t* pmax, int* nblocks_out,
-                   lbt_grad_state* st, hipStream_t s);
+                   lbt_grad_state* st, hipStream_t s, const OperandScalars* kept = nullptr,
+                   int kept_mask = 0);
 int launch_quantize_flat_grad(const float* g, int64_t n, const uint32_t* pmax, int nblocks,
                               lbt_grad_state* st, uint64_t seed, int rounding, int hindsight,
                               int fused_update, int bits, uint8_t* codes, hipStream_t s);

@@ -314,11 +314,17 @@ struct MaxSeg {
 // the few cache hits it had (+0.1 ms per step against -0.16 ms here), at every tensor size.
 __global__ __launch_bounds__(kThreads) void k_absmax3(MaxSeg s0, MaxSeg s1, MaxSeg s2,
                                                        long long per_block, uint32_t* pmax,
-                                                       lbt_grad_state* st) {
+                                                       lbt_grad_state* st,
+                                                       const OperandScalars* kept, int kept_mask) {
   const int blk = blockIdx.x;
-  // every quantizer launch that follows reports into a fresh status and fresh counters
+  // every quantizer launch that follows reports into a fresh status and fresh counters;
+  // operands quantized by an earlier call (kept: bit 0 of the mask X, bit 1 W) bring the
+  // non-finite flag of that call with them
   if (blk == 0) {
-    if (st && threadIdx.x == 0) st->status = LBT_STATUS_OK;
+    if (st && threadIdx.x == 0) {
+      const bool bad = kept && (((kept_mask & 1) && kept->bad_x) || ((kept_mask & 2) && kept->bad_w));
+      st->status = bad ? LBT_STATUS_NONFINITE : LBT_STATUS_OK;
+    }
     if (threadIdx.x < kTicketSlots) {
       unsigned long long* slots = ticket_slots(pmax);
       slots[threadIdx.x] = 0ull;
@@ -983,7 +989,7 @@ size_t plan_segment(Segment& sg) {
 
 int launch_absmax3(const float* p0, int64_t n0, int abs0, const float* p1, int64_t n1, int abs1,
                    const float* p2, int64_t n2, int abs2, uint32_t* pmax, int* nblocks_out,
-                   lbt_grad_state* st, hipStream_t s) {
+                   lbt_grad_state* st, hipStream_t s, const OperandScalars* kept, int kept_mask) {
   if (!p0) n0 = 0;
   if (!p1) n1 = 0;
   if (!p2) n2 = 0;
@@ -1001,7 +1007,8 @@ int launch_absmax3(const float* p0, int64_t n0, int abs0, const float* p1, int64
   *nblocks_out = (int)nb;
   if (nb > kMaxPartialBlocks) return LBT_ERR_UNSUPPORTED;
   MaxSeg s0{p0, n0, abs0, 0}, s1{p1, n1, abs1, (int)nb0}, s2{p2, n2, abs2, (int)(nb0 + nb1)};
-  LBT_LAUNCH(k_absmax3, dim3((unsigned)nb), dim3(kThreads), 0, s, s0, s1, s2, per, pmax, st);
+  LBT_LAUNCH(k_absmax3, dim3((unsigned)nb), dim3(kThreads), 0, s, s0, s1, s2, per, pmax, st, kept,
+             kept_mask);
   LBT_LAUNCH_CHECK();
   return LBT_OK;
 }

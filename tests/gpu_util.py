@@ -135,3 +135,78 @@ def assert_state_equal(h, o):
 def assert_outputs_close(got, want):
     """fp32 outputs: 1e-5 relative (the accumulators themselves are compared exactly)."""
     np.testing.assert_allclose(got, want, rtol=1e-5, atol=0)
+
+
+def save_conv2d(X, W, stride, pad, c_x=0.0, x_unsigned=True, c_w=0.0, flags=0, product=True):
+    """lbt_forward_conv2d_save: the forward result (when product) and the saved-codes buffer."""
+    N, Cc, H, Wd = X.shape
+    K, _, R, S = W.shape
+    P, Q = (H + 2 * pad - R) // stride + 1, (Wd + 2 * pad - S) // stride + 1
+    saved = torch.full((lbt.lbt_saved_bytes_conv2d(N, Cc, H, Wd, K, R, S, stride, pad),), 0xEE,
+                       dtype=torch.uint8, device=DEV)
+    r = Result()
+    if product:
+        ws = torch.zeros(lbt.lbt_workspace_bytes_forward_conv2d(N, Cc, H, Wd, K, R, S, stride, pad),
+                         dtype=torch.uint8, device=DEV)
+        Y = torch.full((N, K, P, Q), float("nan"), device=DEV)
+        acc = torch.full((N, K, P, Q), -1, dtype=torch.int32, device=DEV)
+        status = torch.full((1,), -1, dtype=torch.int32, device=DEV)
+    else:
+        ws = Y = acc = status = None
+    lbt.lbt_forward_conv2d_save(dev(X), dev(W), N, Cc, H, Wd, K, R, S, stride, pad, c_x, x_unsigned,
+                                c_w, flags, Y, acc, status, saved, ws)
+    if product:
+        r.Y, r.acc, r.status = Y.cpu().numpy(), acc.cpu().numpy(), int(status.item())
+    return r, saved
+
+
+def save_linear(X, W, c_x=0.0, x_unsigned=False, c_w=0.0, flags=0, product=True):
+    M, K = X.shape
+    N = W.shape[1]
+    saved = torch.full((lbt.lbt_saved_bytes_linear(M, K, N),), 0xEE, dtype=torch.uint8, device=DEV)
+    r = Result()
+    if product:
+        ws = torch.zeros(lbt.lbt_workspace_bytes_forward_linear(M, K, N), dtype=torch.uint8, device=DEV)
+        Y = torch.full((M, N), float("nan"), device=DEV)
+        acc = torch.full((M, N), -1, dtype=torch.int32, device=DEV)
+        status = torch.full((1,), -1, dtype=torch.int32, device=DEV)
+    else:
+        ws = Y = acc = status = None
+    lbt.lbt_forward_linear_save(dev(X), dev(W), M, K, N, c_x, x_unsigned, c_w, flags, Y, acc, status,
+                                saved, ws)
+    if product:
+        r.Y, r.acc, r.status = Y.cpu().numpy(), acc.cpu().numpy(), int(status.item())
+    return r, saved
+
+
+def backward_conv2d_saved(saved, x_shape, w_shape, dY, stride, pad, st, x_unsigned=True, seed=0,
+                          rounding=0, want_dx=True, want_dw=True):
+    N, Cc, H, Wd = x_shape
+    K, _, R, S = w_shape
+    ws = torch.zeros(lbt.lbt_workspace_bytes_conv2d(N, Cc, H, Wd, K, R, S, stride, pad),
+                     dtype=torch.uint8, device=DEV)
+    r = Result()
+    dX = torch.full(x_shape, float("nan"), device=DEV) if want_dx else None
+    dW = torch.full(w_shape, float("nan"), device=DEV) if want_dw else None
+    aX = torch.full(x_shape, -1, dtype=torch.int32, device=DEV) if want_dx else None
+    aW = torch.full(w_shape, -1, dtype=torch.int32, device=DEV) if want_dw else None
+    lbt.lbt_backward_conv2d_saved(saved, dev(dY), N, Cc, H, Wd, K, R, S, stride, pad, x_unsigned, st,
+                                  seed, rounding, dX, dW, aX, aW, ws)
+    r.dX, r.dW, r.acc_dx, r.acc_dw = [None if t is None else t.cpu().numpy()
+                                      for t in (dX, dW, aX, aW)]
+    return r
+
+
+def backward_linear_saved(saved, M, K, N, dY, st, x_unsigned=False, seed=0, rounding=0,
+                          want_dx=True, want_dw=True):
+    ws = torch.zeros(lbt.lbt_workspace_bytes_linear(M, K, N), dtype=torch.uint8, device=DEV)
+    r = Result()
+    dX = torch.full((M, K), float("nan"), device=DEV) if want_dx else None
+    dW = torch.full((K, N), float("nan"), device=DEV) if want_dw else None
+    aX = torch.full((M, K), -1, dtype=torch.int32, device=DEV) if want_dx else None
+    aW = torch.full((K, N), -1, dtype=torch.int32, device=DEV) if want_dw else None
+    lbt.lbt_backward_linear_saved(saved, dev(dY), M, K, N, x_unsigned, st, seed, rounding, dX, dW,
+                                  aX, aW, ws)
+    r.dX, r.dW, r.acc_dx, r.acc_dw = [None if t is None else t.cpu().numpy()
+                                      for t in (dX, dW, aX, aW)]
+    return r

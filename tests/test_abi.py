@@ -110,3 +110,41 @@ def test_sizes_beyond_the_documented_limits_are_refused(lib):
     assert lib.lbt_forward_conv2d(p, p, 0, 1, 4, 4, 1, 1, 1, 1, 0, 0.0, 1, 0.0, 0, p, None, None, p,
                                   1 << 40, None) == -2
     assert lib.lbt_forward_linear(p, p, 4, 4, 4, 0.0, 1, 0.0, 1, p, None, None, p, 1 << 40, None) == -3
+
+
+def test_saved_codes_calls_check_their_arguments(lib):
+    """Host-side checks of the forward call that keeps the operand codes and of the backward
+    call that reads them (no kernel is launched by any of these)."""
+    N, Cc, H, W, K, R, S, st, pad = 4, 16, 12, 12, 32, 3, 3, 1, 1
+    pad256 = lambda b: (b + 255) // 256 * 256
+    need = lib.lbt_saved_bytes_conv2d(N, Cc, H, W, K, R, S, st, pad)
+    # header, X as [C][N/16][H*W][16], W as [C][R*S][K/16][16]
+    assert need == 256 + 2048 * 16 + pad256(Cc * H * W * 16) + pad256(Cc * R * S * K)
+    assert lib.lbt_saved_bytes_linear(256, 512, 512) == 256 + 2048 * 16 + 512 * 256 + 512 * 512
+    assert lib.lbt_saved_bytes_conv2d(0, 1, 4, 4, 1, 1, 1, 1, 0) == 0
+    p = C.c_void_p(4096)
+    geom = (N, Cc, H, W, K, R, S, st, pad)
+    big = 1 << 40
+    # no saved buffer / too small / misaligned
+    assert lib.lbt_forward_conv2d_save(p, p, *geom, 0.0, 1, 0.0, 0, None, None, None, None, 0, None, 0,
+                                       None) == -1
+    assert lib.lbt_forward_conv2d_save(p, p, *geom, 0.0, 1, 0.0, 0, None, None, None, p, need - 1,
+                                       None, 0, None) == -4
+    assert lib.lbt_forward_conv2d_save(p, p, *geom, 0.0, 1, 0.0, 0, None, None, None,
+                                       C.c_void_p(4100), need, None, 0, None) == -7
+    # a product needs a workspace; no product, no status
+    assert lib.lbt_forward_conv2d_save(p, p, *geom, 0.0, 1, 0.0, 0, p, None, None, p, need, None, 0,
+                                       None) == -1
+    assert lib.lbt_forward_conv2d_save(p, p, *geom, 0.0, 1, 0.0, 0, None, None, p, p, need, None, 0,
+                                       None) == -1
+    assert lib.lbt_forward_linear_save(p, p, 4, 4, 4, 0.0, 1, 0.0, 8 << 8, None, None, None, p, big,
+                                       None, 0, None) == -3          # unsigned 8-bit activations
+    ws = lib.lbt_workspace_bytes_conv2d(*geom)
+    assert lib.lbt_backward_conv2d_saved(None, need, p, *geom, 1, p, 0, 0, p, p, None, None, p, ws,
+                                         None) == -1
+    assert lib.lbt_backward_conv2d_saved(p, need - 1, p, *geom, 1, p, 0, 0, p, p, None, None, p, ws,
+                                         None) == -4
+    assert lib.lbt_backward_conv2d_saved(p, need, p, *geom, 1, p, 0, 0, p, p, None, None, p, ws - 1,
+                                         None) == -4
+    assert lib.lbt_backward_linear_saved(p, big, p, 4, 4, 4, 0, p, 0, 8, p, p, None, None, p, big,
+                                         None) == -3                 # unknown rounding bit

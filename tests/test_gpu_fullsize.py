@@ -71,6 +71,17 @@ def test_full_size_layer(idx):
     assert (h2.gamma, h2.step, h2.n_out, h2.status) == (h_after.gamma, h_after.step, h_after.n_out,
                                                         h_after.status)
     assert np.array_equal(res2.dX, res.dX) and np.array_equal(res2.dW, res.dW)
+    # and the call that reads the operand codes a forward call kept (bench.py --saved-codes):
+    # the same bits as the call checked against the oracle below
+    _, saved = gu.save_conv2d(X, W, L.stride, L.pad, x_unsigned=True, product=False)
+    st3 = lbt.new_state(gamma0=gamma0)
+    res3 = gu.backward_conv2d_saved(saved, L.x_shape, L.w_shape, dY, L.stride, L.pad, st3,
+                                    x_unsigned=True, seed=seed, rounding=rounding | lbt.FUSED_UPDATE)
+    h3 = lbt.lbt_state_read(st3)
+    assert (h3.gamma, h3.step, h3.n_out, h3.status) == (h2.gamma, h2.step, h2.n_out, h2.status)
+    assert np.array_equal(res3.acc_dx, res.acc_dx) and np.array_equal(res3.acc_dw, res.acc_dw)
+    assert np.array_equal(res3.dX, res.dX) and np.array_equal(res3.dW, res.dW)
+    del saved, res3
 
     # --- oracle: quantizers in full ---------------------------------------------------------
     ost = oracle.GradState(gamma=gamma0)
