@@ -483,3 +483,42 @@ def forward_conv2d(X, W, stride: int, pad: int, c_x: float = 0.0, x_unsigned: bo
         return ForwardResult(qX, qW, s_x, s_w, status, None, None)
     acc = conv2d_fwd(qX, qW, stride, pad)
     return ForwardResult(qX, qW, s_x, s_w, status, acc, dequant(acc, s_x, s_w))
+
+
+# ----------------------------------------------------------------------------
+# learned clip values of the weight / activation quantizers (Sec. 3.1)
+# ----------------------------------------------------------------------------
+def ste_backward(x, c, is_unsigned: bool, bits: int, grad_q):
+    """Gradient of a loss through the quantizer of Eq. (1)-(4), w.r.t. the input x and w.r.t.
+    the clip value c, given grad_q = dL/dQ(x).
+
+    Sec. 3.1 learns c for weights and activations end to end, following the learned-step-size
+    and clipping-activation quantizers it cites, and prints no formula of its own.  The reading
+    taken here is the derivative of Eq. (1)-(4) with the rounding passed straight through
+    (d round(u)/du = 1), Q = s round(u), u = clip(x, c)/s, s = c/q:
+        dQ/dx = 1 for lo < x < c, else 0                        (lo = -c signed, 0 unsigned)
+        dQ/dc = (round(u) - u)/q inside;  +1 for x >= c;  -1 for x <= -c (signed);
+                0 for x <= 0 (unsigned)
+    which is the step-size gradient of the learned-step-size quantizer divided by q.
+    round(u) is taken as the operand quantizer takes it (u as one fp32 multiply by q/c);
+    everything after that decision is fp64.  Returns (grad_x fp32 shaped like x, grad_c as a
+    Python float, sum of |grad_q * dQ/dc| as a Python float: the scale of grad_c's error)."""
+    x = _f32(x)
+    g = _f32(grad_q)
+    assert x.shape == g.shape
+    c = np.float32(c)
+    assert c > 0
+    q = levels(bits, is_unsigned)
+    inv_s = np.float32(np.float64(q) / np.float64(c))
+    lo = np.float32(0.0) if is_unsigned else np.float32(-c)
+    inside = (x > lo) & (x < c)
+    with np.errstate(invalid="ignore"):
+        xc = np.minimum(np.maximum(x, lo), c)
+        u = (xc * inv_s).astype(np.float32)
+        r = np.rint(u)
+    below = np.float64(0.0 if is_unsigned else -1.0)
+    d_c = np.where(inside, (r.astype(np.float64) - u.astype(np.float64)) / np.float64(q),
+                   np.where(x >= c, 1.0, np.where(x <= lo, below, 0.0)))
+    prod = g.astype(np.float64) * d_c
+    grad_x = np.where(inside, g, np.float32(0.0)).astype(np.float32)
+    return grad_x, float(np.sum(prod)), float(np.sum(np.abs(prod)))
