@@ -74,6 +74,10 @@ def parse():
     ap.add_argument("--workload", choices=["resnet50", "vit-l"], default="resnet50",
                     help="resnet50: the headline sweep (default); vit-l: the linear layers of one "
                          "ViT-L encoder block at batch 64 x 197 tokens (signed activations)")
+    ap.add_argument("--learned-clips", action="store_true",
+                    help="clip values of X and W given, and after every backward call the "
+                         "gradient through the two operand quantizers (lbt_ste_backward on dW "
+                         "with W and on dX with X, in place, with the gradients of c_w and c_x)")
     ap.add_argument("--saved-codes", action="store_true",
                     help="the backward calls read the operand codes a forward call kept "
                          "(lbt_forward_*_save before the timed region, lbt_backward_*_saved in it): "
@@ -124,6 +128,7 @@ class LayerRun:
         self.c_x = self.c_w = 0.0            # <= 0: the call takes the tensor's maximum
         self.fan_in = fan_in
         self.saved = None
+        self.grad_c = None                   # gradients of (c_w, c_x) when the clips are learned
 
     def keep_codes(self, torch, lbt, flags):
         """What the forward pass of the layer leaves behind: the codes of X and W in the layouts
@@ -188,6 +193,11 @@ class LayerRun:
                                     self.seed, rounding, self.dX, self.dW, ws)
         if not rounding & lbt.FUSED_UPDATE:
             lbt.lbt_update_interval(self.state)
+        if self.grad_c is not None:
+            bits = ((rounding >> 8) & 15) or 4
+            lbt.lbt_ste_backward(self.W, self.c_w, False, bits, self.dW, self.dW, self.grad_c[0:1], ws)
+            lbt.lbt_ste_backward(self.X, self.c_x, self.x_unsigned, bits, self.dX, self.dX,
+                                 self.grad_c[1:2], ws)
 
 
 def cpu_baseline(layers, rounding, bits=4):
@@ -402,8 +412,10 @@ def main():
                                    x_unsigned=not vit and args.bits < 8, dense=args.dense_codes))
     for L in layers:
         L.state = lbt.new_state(gamma0=args.gamma0, bits=args.bits)
-        if args.given_clips:
+        if args.given_clips or args.learned_clips:
             L.use_given_clips()
+        if args.learned_clips:
+            L.grad_c = torch.zeros(2, device="cuda")
         if args.saved_codes and not args.forward:
             L.keep_codes(torch, lbt, lbt.BITS(args.bits))
     ws = torch.zeros(max(L.ws_bytes(lbt, args.forward) for L in layers), dtype=torch.uint8,
@@ -487,6 +499,9 @@ def main():
                                "value": gemm_ops / dt3 / 1e12, "unit": "TOPS"}
         del overlapped
         step = make_step(1)
+    if args.learned_clips:
+        out["config"]["workload"] += (", clip values of X and W given, gradient through both "
+                                      "operand quantizers after every layer")
     if args.saved_codes:
         out["config"]["workload"] += (", X and W codes kept by the forward pass (not quantized "
                                       "again in the backward calls)")
@@ -527,6 +542,8 @@ def main():
                  "avg_us": ms / launches * 1e3, "avg_us_with_markers": ms_raw / launches * 1e3}
             if "gemm" in name:
                 k["TOPS"] = work / (ms * 1e-3) / 1e12
+            elif "ste" in name:
+                k["GBps"] = work * 12.0 / (ms * 1e-3) / 1e9     # x and grad read, grad written
             elif "quantize" in name or "absmax" in name:
                 # the quantizer's algorithmic 4.5 B/element covers both sweeps of the tensor
                 # (maximum, then quantize); the maximum pass alone is rated at 4 B/element
@@ -597,7 +614,7 @@ def main():
                                    "ms_per_step": t_ms, "roofline_ms_per_step": t_roof * 1e3,
                                    "frac_of_layer_rooflines": t_roof * 1e3 / t_ms}
 
-    if not (args.no_cpu_baseline or args.single_sweep or args.forward or args.given_clips or args.saved_codes):   # the oracle is timed on the paper's mode
+    if not (args.no_cpu_baseline or args.single_sweep or args.forward or args.given_clips or args.saved_codes or args.learned_clips):   # the oracle is timed on the paper's mode
         out["cpu_baseline"] = cpu_baseline(layers, rounding & lbt.ROUND_STOCHASTIC, args.bits)
 
     print(json.dumps(out))

@@ -158,6 +158,26 @@ int lbt_quantize_operand(const float* x, int64_t n, float c, int is_unsigned, in
                          void* stream);
 
 /*
+ * Gradient of a loss through the operand quantizer, for callers that learn the clip values of
+ * weights and activations (Sec. 3.1 learns them end to end and gives no formula; this is the
+ * derivative of Eq. 1-4 with the rounding passed straight through, i.e. the step-size gradient
+ * of the learned-step-size quantizers the section cites, over q).  With grad_q = dL/dQ(x) (for
+ * weights the dW of lbt_backward_*, for activations the dX of the layer above):
+ *   grad_x[i] = grad_q[i] if lo < x[i] < c, else 0            (lo = -c signed, 0 unsigned)
+ *   grad_c    = sum_i grad_q[i] * d_i,   d_i = (round(u_i) - u_i) / q inside the interval,
+ *               +1 for x[i] >= c, -1 for x[i] <= -c (signed), 0 for x[i] <= 0 (unsigned),
+ *               u_i = clip(x[i], c) / s as the quantizer computes it, q = c / s
+ * x, grad_q, grad_x: device, n floats, 16-byte aligned; grad_x may be NULL and may be grad_q
+ * (in place).  grad_c: device, one float, may be NULL; products and the sum are taken in fp64
+ * in a fixed order (the same inputs give the same bits).  c must be > 0 and finite
+ * (LBT_ERR_UNSUPPORTED otherwise: an interval taken from the tensor's maximum has no learned
+ * parameter).  ws: lbt_workspace_bytes_quantize(n).
+ */
+int lbt_ste_backward(const float* x, int64_t n, float c, int is_unsigned, int bits,
+                     const float* grad_q, float* grad_x, float* grad_c, void* ws, size_t ws_bytes,
+                     void* stream);
+
+/*
  * Backward pass of a linear layer Y = X W with row-major X[M,K_in],
  * W[K_in,N_out], dY[M,N_out]:
  *   dX = Q(dY) . Q(W)^T   [M,K_in]      dW = Q(X)^T . Q(dY)   [K_in,N_out]

@@ -364,6 +364,23 @@ int lbt_quantize_operand(const float* x, int64_t n, float c, int is_unsigned, in
                                       clip_scale_out, s);
 }
 
+int lbt_ste_backward(const float* x, int64_t n, float c, int is_unsigned, int bits,
+                     const float* grad_q, float* grad_x, float* grad_c, void* ws, size_t ws_bytes,
+                     void* stream) {
+  if (!x || !grad_q || !ws) return LBT_ERR_NULL;
+  if (n <= 0) return LBT_ERR_SHAPE;
+  if (bits < 2 || bits > 8 || !(c > 0.0f) || !(c < INFINITY)) return LBT_ERR_UNSUPPORTED;
+  if (!aligned(x, 16) || !aligned(grad_q, 16) || (grad_x && !aligned(grad_x, 16)) ||
+      (grad_c && !aligned(grad_c, 4)) || !aligned(ws, 256))
+    return LBT_ERR_ALIGN;
+  if (ws_bytes < lbt_workspace_bytes_quantize(n)) return LBT_ERR_WORKSPACE;
+  static_assert((size_t)kStePartials * sizeof(double) <= kWsHeaderBytes - kWsScalarsBytes,
+                "partial sums must fit the header");
+  double* partial = reinterpret_cast<double*>(static_cast<uint8_t*>(ws) + kWsScalarsBytes);
+  return launch_ste_backward(x, grad_q, n, c, is_unsigned, bits, grad_x, grad_c, partial,
+                             reinterpret_cast<hipStream_t>(stream));
+}
+
 size_t lbt_workspace_bytes_conv2d(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R,
                                   int64_t S, int64_t stride, int64_t pad) {
   ConvGeom g;

@@ -59,7 +59,7 @@ __device__ __forceinline__ void interval_update(lbt_grad_state* st) {
 enum KernelId {
   KID_ABSMAX = 0, KID_FLAT_GRAD, KID_FLAT_OPERAND, KID_QUANTIZE_LAYER, KID_GEMM_DX,
   KID_GEMM_DW, KID_GEMM_FWD,
-  KID_FINALIZE, KID_UPDATE, KID_STATE, KID_COUNT
+  KID_FINALIZE, KID_UPDATE, KID_STATE, KID_STE, KID_COUNT
 };
 // Records a start event now and a stop event when it goes out of scope (after the
 // launch it brackets).  `work` is the algorithmic work of the launch: elements for
@@ -138,6 +138,11 @@ struct LayerTensors {
   int bits;       // b for all three tensors
 };
 int launch_quantize_layer(const LayerTensors& q, hipStream_t s);
+// Gradient through an operand quantizer; partial: kStePartials doubles of scratch (the
+// partial-maxima area of a workspace header is large enough).
+constexpr int kStePartials = 2048;
+int launch_ste_backward(const float* x, const float* grad_q, int64_t n, float c, int is_unsigned,
+                        int bits, float* grad_x, float* grad_c, double* partial, hipStream_t s);
 int launch_update_interval(lbt_grad_state* st, hipStream_t s);
 int launch_state_init(lbt_grad_state* st, const lbt_grad_state& v, hipStream_t s);
 

@@ -28,7 +28,8 @@ const char* const kNames[KID_COUNT] = {
     "k_absmax3",           "k_quantize_flat(grad)", "k_quantize_flat(operand)",
     "k_quantize_layer",      "k_implicit_gemm(dX)",   "k_implicit_gemm(dW)",
     "k_implicit_gemm(fwd)",
-    "k_splitk_reduce",     "k_update_interval",     "k_state_set"};
+    "k_splitk_reduce",     "k_update_interval",     "k_state_set",
+    "k_ste_backward"};
 
 hipEvent_t take_event() {
   if (!g_pool.empty()) {

@@ -373,6 +373,89 @@ __global__ __launch_bounds__(kThreads) void k_absmax3(MaxSeg s0, MaxSeg s1, MaxS
   if (threadIdx.x < 4) pmax[blk * 4 + threadIdx.x] = ((int)threadIdx.x == t) ? m : 0u;
 }
 
+// ---------------------------------------------------------------------------
+// Gradient through an operand quantizer (Sec. 3.1 learns the clip values of weights and
+// activations; Eq. 1-4 with the rounding passed straight through):
+//   grad_x = grad_q inside the interval (lo < x < c), 0 outside;
+//   grad_c = sum grad_q * d,  d = (round(u) - u) / q inside, +1 for x >= c, -1 for x <= -c
+//            (signed), 0 for x <= 0 (unsigned);  u = clip(x) * (q / c) as the quantizer takes it.
+// Products and sums in fp64; one partial sum per workgroup, added in a fixed order by
+// k_ste_finish, so the result does not depend on how the workgroups were scheduled.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ double wave_sum_f64(double v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+
+__device__ __forceinline__ double block_sum_f64(double v) {
+  __shared__ double part[16];
+  const int nw = blockDim.x >> 6;
+  v = wave_sum_f64(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = v;
+  __syncthreads();
+  double t = 0.0;
+  for (int i = 0; i < nw; ++i) t += part[i];
+  return t;
+}
+
+__device__ __forceinline__ float ste_one(float v, float g, const QConst& k, double below, double& acc) {
+  const bool inside = v > k.lo && v < k.c;
+  const float u = normalised(v, k);
+  const float r = rintf(u);
+  const double d = inside ? ((double)r - (double)u) / (double)k.q
+                          : (v >= k.c ? 1.0 : (v <= k.lo ? below : 0.0));
+  acc += (double)g * d;
+  return inside ? g : 0.0f;
+}
+
+// grad_x may be null, and may be grad_q itself (every element is read before it is written).
+__global__ __launch_bounds__(kThreads) void k_ste_backward(const float* x, const float* grad_q,
+                                                            long long n, float c, int is_unsigned,
+                                                            int bits, float* grad_x, double* partial) {
+  const QConst k = make_qconst(c, is_unsigned != 0, bits);
+  const double below = is_unsigned ? 0.0 : -1.0;
+  const float4* x4 = reinterpret_cast<const float4*>(x);
+  const float4* g4 = reinterpret_cast<const float4*>(grad_q);
+  float4* o4 = reinterpret_cast<float4*>(grad_x);
+  const long long n4 = n >> 2, stride = (long long)gridDim.x * kThreads;
+  double acc = 0.0;
+  long long i = (long long)blockIdx.x * kThreads + threadIdx.x;
+  // two float4 pairs per thread in flight
+  for (; i + stride < n4; i += 2 * stride) {
+    const float4 xa = x4[i], ga = g4[i], xb = x4[i + stride], gb = g4[i + stride];
+    float4 oa, ob;
+    oa.x = ste_one(xa.x, ga.x, k, below, acc); oa.y = ste_one(xa.y, ga.y, k, below, acc);
+    oa.z = ste_one(xa.z, ga.z, k, below, acc); oa.w = ste_one(xa.w, ga.w, k, below, acc);
+    ob.x = ste_one(xb.x, gb.x, k, below, acc); ob.y = ste_one(xb.y, gb.y, k, below, acc);
+    ob.z = ste_one(xb.z, gb.z, k, below, acc); ob.w = ste_one(xb.w, gb.w, k, below, acc);
+    if (grad_x) { o4[i] = oa; o4[i + stride] = ob; }
+  }
+  if (i < n4) {
+    const float4 xa = x4[i], ga = g4[i];
+    float4 oa;
+    oa.x = ste_one(xa.x, ga.x, k, below, acc); oa.y = ste_one(xa.y, ga.y, k, below, acc);
+    oa.z = ste_one(xa.z, ga.z, k, below, acc); oa.w = ste_one(xa.w, ga.w, k, below, acc);
+    if (grad_x) o4[i] = oa;
+  }
+  if (blockIdx.x == 0 && (long long)threadIdx.x < n - n4 * 4) {   // the last n % 4 elements
+    const long long e = n4 * 4 + threadIdx.x;
+    const float o = ste_one(x[e], grad_q[e], k, below, acc);
+    if (grad_x) grad_x[e] = o;
+  }
+  const double tot = block_sum_f64(acc);
+  if (partial && threadIdx.x == 0) partial[blockIdx.x] = tot;
+}
+
+__global__ __launch_bounds__(kThreads) void k_ste_finish(const double* partial, int nblocks,
+                                                          float* grad_c) {
+  double acc = 0.0;
+  for (int i = threadIdx.x; i < nblocks; i += kThreads) acc += partial[i];
+  const double tot = block_sum_f64(acc);
+  if (threadIdx.x == 0) *grad_c = (float)tot;
+}
+
 // Largest |v| of eight values as an fp32 bit pattern (NaN/Inf sort on top).
 __device__ __forceinline__ uint32_t max_abs_bits8(const float v[8]) {
   uint32_t m = 0;
@@ -1010,6 +1093,22 @@ int launch_absmax3(const float* p0, int64_t n0, int abs0, const float* p1, int64
   LBT_LAUNCH(k_absmax3, dim3((unsigned)nb), dim3(kThreads), 0, s, s0, s1, s2, per, pmax, st, kept,
              kept_mask);
   LBT_LAUNCH_CHECK();
+  return LBT_OK;
+}
+
+int launch_ste_backward(const float* x, const float* grad_q, int64_t n, float c, int is_unsigned,
+                        int bits, float* grad_x, float* grad_c, double* partial, hipStream_t s) {
+  ProfScope prof(KID_STE, (double)n, s);
+  long long blocks = ((n >> 2) + 2 * kThreads - 1) / (2 * kThreads);
+  if (blocks > kStePartials) blocks = kStePartials;
+  if (blocks < 1) blocks = 1;
+  LBT_LAUNCH(k_ste_backward, dim3((unsigned)blocks), dim3(kThreads), 0, s, x, grad_q, (long long)n, c,
+             is_unsigned, bits, grad_x, grad_c ? partial : (double*)nullptr);
+  LBT_LAUNCH_CHECK();
+  if (grad_c) {
+    LBT_LAUNCH(k_ste_finish, dim3(1), dim3(kThreads), 0, s, (const double*)partial, (int)blocks, grad_c);
+    LBT_LAUNCH_CHECK();
+  }
   return LBT_OK;
 }
 
