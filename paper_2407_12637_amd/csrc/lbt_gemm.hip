@@ -37,6 +37,8 @@
 // over workgroups, each writes its partial tile with plain stores, and a second
 // kernel sums the partials and applies the scale (no atomics: the result does not
 // depend on data sparsity or arrival order).
+#include <atomic>
+
 #include "lbt_internal.h"
 #include <type_traits>
 
@@ -526,20 +528,25 @@ void fill_geom(GemmArgs& g, const ConvGeom& c) {
 }
 
 constexpr size_t kMaxDynLds = 128 * 1024;
+constexpr int kMaxDevices = 64;
 
 template <int BM, int BN, int MODE, int STAGES, bool STREAM>
 int launch_one(const GemmArgs& g, unsigned grid, size_t tap_bytes, hipStream_t s) {
   void (*kernel)(const GemmArgs) = &k_implicit_gemm<BM, BN, MODE, STAGES, STREAM>;
   const size_t dyn = (size_t)STAGES * (BM + BN) * ROWB + tap_bytes;
   if (dyn > kMaxDynLds) return LBT_ERR_UNSUPPORTED;
-  // more than 64 KiB of dynamic LDS has to be allowed once per kernel
-  static bool raised = false;
-  if (!raised) {
+  // more than 64 KiB of dynamic LDS has to be allowed once per kernel and device (callers on
+  // several threads may arrive here together: setting the attribute twice is harmless)
+  static std::atomic<bool> raised[kMaxDevices];
+  int device = 0;
+  if (hipGetDevice(&device) != hipSuccess) return LBT_ERR_HIP;
+  const bool tracked = device >= 0 && device < kMaxDevices;
+  if (!tracked || !raised[device].load(std::memory_order_acquire)) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                             hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)kMaxDynLds) != hipSuccess)
       return LBT_ERR_HIP;
-    raised = true;
+    if (tracked) raised[device].store(true, std::memory_order_release);
   }
   LBT_LAUNCH(kernel, dim3(grid), dim3(kThreads), dyn, s, g);
   return LBT_OK;
