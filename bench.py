@@ -163,7 +163,15 @@ class LayerRun:
 
     def run_forward(self, lbt, ws, flags):
         s = self.spec
-        if self.is_linear:
+        if self.saved is not None:      # the forward product that also keeps the codes
+            if self.is_linear:
+                lbt.lbt_forward_linear_save(self.X, self.W, s.M, s.K, s.N, self.c_x, self.x_unsigned,
+                                            self.c_w, flags, self.Y, None, None, self.saved, ws)
+            else:
+                lbt.lbt_forward_conv2d_save(self.X, self.W, s.N, s.C, s.H, s.W, s.K, s.R, s.S,
+                                            s.stride, s.pad, self.c_x, self.x_unsigned, self.c_w,
+                                            flags, self.Y, None, None, self.saved, ws)
+        elif self.is_linear:
             lbt.lbt_forward_linear(self.X, self.W, s.M, s.K, s.N, self.c_x, self.x_unsigned,
                                    self.c_w, flags, self.Y, None, None, ws)
         else:
@@ -416,7 +424,7 @@ def main():
             L.use_given_clips()
         if args.learned_clips:
             L.grad_c = torch.zeros(2, device="cuda")
-        if args.saved_codes and not args.forward:
+        if args.saved_codes:
             L.keep_codes(torch, lbt, lbt.BITS(args.bits))
     ws = torch.zeros(max(L.ws_bytes(lbt, args.forward) for L in layers), dtype=torch.uint8,
                      device="cuda")
