@@ -88,6 +88,9 @@ def parse():
     ap.add_argument("--per-layer", action="store_true",
                     help="print a table: every layer shape of the sweep run on its own, "
                          "kernel times against the layer's own rooflines; then exit")
+    ap.add_argument("--with-oracle", action="store_true",
+                    help="with --per-layer: also time the CPU oracle's full backward of every layer "
+                         "shape (one repetition, all host cores)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="only run three plain 256 MiB device copies (calibrates the HBM byte "
                          "counters of a rocprofv3 --pmc run) and exit")
@@ -277,6 +280,9 @@ def per_layer_report(args, torch, lbt, synth, rounding, gen, vit):
     head = ("%-24s %2s %7s | %7s %6s %5s | %7s %6s %5s %5s %1s | %7s %6s %5s %5s %1s"
             % ("layer", "x", "n_dY(M)", "quant", "GB/s", "%HBM", "dX us", "TOPS", "%MFMA", "%roof",
                "b", "dW us", "TOPS", "%MFMA", "%roof", "b"))
+    if args.with_oracle:
+        import oracle
+        head += " | %9s" % "oracle ms"
     print(head)
     print("-" * len(head))
     tot = {"q_t": 0.0, "q_b": 0.0, "c_ops": 0.0, "c_t": 0.0, "all_ops": 0.0, "all_t": 0.0,
@@ -331,16 +337,31 @@ def per_layer_report(args, torch, lbt, synth, rounding, gen, vit):
         tot["q_t"] += t_q * spec.count
         tot["q_b"] += q_bytes * spec.count
         gbps = q_bytes / (t_q * 1e-6) / 1e9
-        print("%-24s %2d %7.2f | %7.1f %6.0f %5.1f | %7.1f %6.0f %5.1f %5.1f %1s | %7.1f %6.0f %5.1f %5.1f %1s"
-              % (spec.name, spec.count, ng / 1e6, t_q, gbps, 100 * gbps / PEAK_HBM_GBPS, *cols),
-              flush=True)
+        line = ("%-24s %2d %7.2f | %7.1f %6.0f %5.1f | %7.1f %6.0f %5.1f %5.1f %1s | %7.1f %6.0f %5.1f %5.1f %1s"
+                % (spec.name, spec.count, ng / 1e6, t_q, gbps, 100 * gbps / PEAK_HBM_GBPS, *cols))
+        if args.with_oracle:
+            X, W, dY = (t.cpu().numpy() for t in (probe.X, probe.W, probe.dY))
+            ost = oracle.GradState(gamma=args.gamma0, bits=args.bits)
+            t0 = time.perf_counter()
+            if is_lin:
+                oracle.backward_linear(X, W, dY, ost, x_unsigned=probe.x_unsigned, seed=probe.seed,
+                                       rounding=rounding & lbt.ROUND_STOCHASTIC)
+            else:
+                oracle.backward_conv2d(X, W, dY, spec.stride, spec.pad, ost, x_unsigned=probe.x_unsigned,
+                                       seed=probe.seed, rounding=rounding & lbt.ROUND_STOCHASTIC)
+            oracle.update_interval(ost)
+            line += " | %9.0f" % ((time.perf_counter() - t0) * 1e3)
+            del X, W, dY
+        print(line, flush=True)
         del Ls, probe, ws
         torch.cuda.empty_cache()
     print("-" * len(head))
     print("x = occurrences in the network; quant = maximum + quantize launches of dY, X and W, rated at "
           "4.5 B per element; %%roof = the layer's own roofline time max(ops / 5.0 POP/s, algorithmic "
           "bytes / 8 TB/s) over the measured time; b = which of the two binds (C compute, M memory); "
-          "dW includes its split reduce.  Event-bracket overhead removed per launch: %.2f us." % ov)
+          "dW includes its split reduce.  Event-bracket overhead removed per launch: %.2f us." % ov
+          + ("  oracle ms = the CPU oracle's whole backward of the layer (quantizers, both products, "
+             "update), one repetition on %d threads." % oracle.num_threads() if args.with_oracle else ""))
     summary = {
         "quantize_pass_GBps": tot["q_b"] / (tot["q_t"] * 1e-6) / 1e9,
         "products_TOPS": tot["all_ops"] / (tot["all_t"] * 1e-6) / 1e12,
