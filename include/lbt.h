@@ -7,12 +7,15 @@
  * the clipping-factor update of Sec. 3.3 (Eq. 15-16, Alg. 1), then the two
  * integer contractions of the backward pass on the 4-bit codes and the
  * denormalisation of Eq. (4).  Also: the quantized forward product of the same
- * layers (Sec. 3.1), bit-widths 2..8 (Sec. 4.2 uses 4, 5, 6 and 8), and two options of
- * the backward calls (interval update inside the call; single-sweep quantizer).
+ * layers (Sec. 3.1), bit-widths 2..8 (Sec. 4.2 uses 4, 5, 6 and 8), two options of
+ * the backward calls (interval update inside the call; single-sweep quantizer), a forward
+ * call that keeps the quantized operands for a backward call that reads them, and the
+ * gradient through the weight / activation quantizers for learned clip values.
  *
  * A layer's calls may be issued on any stream; calls that share a workspace or a state must
  * be ordered (same stream, or the caller's events).  Calls on different streams with
- * workspaces and states of their own may overlap.
+ * workspaces and states of their own may overlap.  A buffer of kept operand codes is written
+ * by the forward call and only read by backward calls, which must be ordered after it.
  *
  * Conventions for every entry point
  *   - Returns LBT_OK (0) or a negative LBT_ERR_* code.  Nothing throws.
