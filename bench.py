@@ -75,9 +75,12 @@ def parse():
                     help="resnet50: the headline sweep (default); vit-l: the linear layers of one "
                          "ViT-L encoder block at batch 64 x 197 tokens (signed activations)")
     ap.add_argument("--learned-clips", action="store_true",
-                    help="clip values of X and W given, and after every backward call the "
-                         "gradient through the two operand quantizers (lbt_ste_backward on dW "
-                         "with W and on dX with X, in place, with the gradients of c_w and c_x)")
+                    help="clip values of X and W given and learned: lbt_backward_*_learned (the "
+                         "backward pass, dW and dX masked with the quantizers' intervals, the "
+                         "gradients of c_w and c_x)")
+    ap.add_argument("--unfused-ste", action="store_true",
+                    help="with --learned-clips: lbt_backward_* followed by two lbt_ste_backward "
+                         "calls instead of the one call lbt_backward_*_learned (same kernels)")
     ap.add_argument("--saved-codes", action="store_true",
                     help="the backward calls read the operand codes a forward call kept "
                          "(lbt_forward_*_save before the timed region, lbt_backward_*_saved in it): "
@@ -132,6 +135,7 @@ class LayerRun:
         self.fan_in = fan_in
         self.saved = None
         self.grad_c = None                   # gradients of (c_w, c_x) when the clips are learned
+        self.unfused_ste = False
 
     def keep_codes(self, torch, lbt, flags):
         """What the forward pass of the layer leaves behind: the codes of X and W in the layouts
@@ -195,6 +199,31 @@ class LayerRun:
                 lbt.lbt_backward_conv2d_saved(self.saved, self.dY, s.N, s.C, s.H, s.W, s.K, s.R, s.S,
                                               s.stride, s.pad, self.x_unsigned, self.state,
                                               self.seed, rounding, self.dX, self.dW, None, None, ws)
+        elif self.grad_c is not None and self.unfused_ste:
+            # the same result from separate calls: the backward pass, then the gradient through
+            # each operand quantizer as a pass of its own
+            bits = ((rounding >> 8) & 15) or 4
+            if self.is_linear:
+                lbt.lbt_backward_linear(self.X, self.W, self.dY, s.M, s.K, s.N, self.c_x,
+                                        self.x_unsigned, self.c_w, self.state, self.seed, rounding,
+                                        self.dX, self.dW, ws)
+            else:
+                lbt.lbt_backward_conv2d(self.X, self.W, self.dY, s.N, s.C, s.H, s.W, s.K, s.R, s.S,
+                                        s.stride, s.pad, self.c_x, self.x_unsigned, self.c_w,
+                                        self.state, self.seed, rounding, self.dX, self.dW, ws)
+            lbt.lbt_ste_backward(self.W, self.c_w, False, bits, self.dW, self.dW, self.grad_c[0:1], ws)
+            lbt.lbt_ste_backward(self.X, self.c_x, self.x_unsigned, bits, self.dX, self.dX,
+                                 self.grad_c[1:2], ws)
+        elif self.grad_c is not None:
+            if self.is_linear:
+                lbt.lbt_backward_linear_learned(self.X, self.W, self.dY, s.M, s.K, s.N, self.c_x,
+                                                self.x_unsigned, self.c_w, self.state, self.seed,
+                                                rounding, self.dX, self.dW, self.grad_c, ws)
+            else:
+                lbt.lbt_backward_conv2d_learned(self.X, self.W, self.dY, s.N, s.C, s.H, s.W, s.K,
+                                                s.R, s.S, s.stride, s.pad, self.c_x, self.x_unsigned,
+                                                self.c_w, self.state, self.seed, rounding, self.dX,
+                                                self.dW, self.grad_c, ws)
         elif self.is_linear:
             lbt.lbt_backward_linear(self.X, self.W, self.dY, s.M, s.K, s.N, self.c_x, self.x_unsigned,
                                     self.c_w, self.state, self.seed, rounding, self.dX, self.dW, ws)
@@ -204,11 +233,6 @@ class LayerRun:
                                     self.seed, rounding, self.dX, self.dW, ws)
         if not rounding & lbt.FUSED_UPDATE:
             lbt.lbt_update_interval(self.state)
-        if self.grad_c is not None:
-            bits = ((rounding >> 8) & 15) or 4
-            lbt.lbt_ste_backward(self.W, self.c_w, False, bits, self.dW, self.dW, self.grad_c[0:1], ws)
-            lbt.lbt_ste_backward(self.X, self.c_x, self.x_unsigned, bits, self.dX, self.dX,
-                                 self.grad_c[1:2], ws)
 
 
 def cpu_baseline(layers, rounding, bits=4):
@@ -445,6 +469,7 @@ def main():
             L.use_given_clips()
         if args.learned_clips:
             L.grad_c = torch.zeros(2, device="cuda")
+            L.unfused_ste = args.unfused_ste
         if args.saved_codes:
             L.keep_codes(torch, lbt, lbt.BITS(args.bits))
     ws = torch.zeros(max(L.ws_bytes(lbt, args.forward) for L in layers), dtype=torch.uint8,

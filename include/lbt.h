@@ -285,7 +285,26 @@ int lbt_backward_conv2d_saved(const void* saved, size_t saved_bytes, const float
                               int32_t* acc_dW, void* ws, size_t ws_bytes, void* stream);
 
 /*
- * The same two calls with the raw int32 accumulators also written out
+ * Backward pass of a layer whose clip values c_x, c_w are learned (both > 0 and finite where
+ * their product is asked for: LBT_ERR_UNSUPPORTED otherwise): lbt_backward_linear /
+ * lbt_backward_conv2d followed by lbt_ste_backward on (W, dW) and on (X, dX) in one call, on
+ * the call's own workspace.  dW and dX come out masked; grad_c (device, 2 floats) receives dL/dc_w in [0] (when dW is
+ * asked for) and dL/dc_x in [1] (when dX is).
+ */
+int lbt_backward_linear_learned(const float* X, const float* W, const float* dY, int64_t M,
+                                int64_t K_in, int64_t N_out, float c_x, int x_unsigned,
+                                float c_w, lbt_grad_state* st, uint64_t seed, int rounding,
+                                float* dX, float* dW, float* grad_c, void* ws, size_t ws_bytes,
+                                void* stream);
+int lbt_backward_conv2d_learned(const float* X, const float* W, const float* dY, int64_t N,
+                                int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R,
+                                int64_t S, int64_t stride, int64_t pad, float c_x,
+                                int x_unsigned, float c_w, lbt_grad_state* st, uint64_t seed,
+                                int rounding, float* dX, float* dW, float* grad_c, void* ws,
+                                size_t ws_bytes, void* stream);
+
+/*
+ * lbt_backward_linear and lbt_backward_conv2d with the raw int32 accumulators also written out
  * (acc_dX shaped like dX, acc_dW like dW; either may be NULL).  For checking
  * the integer sums bit for bit.  LBT_ERR_OVERFLOW if the worst case of a whole sum (not
  * only of a slice) does not fit 32 bits.

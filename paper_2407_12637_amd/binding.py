@@ -64,6 +64,10 @@ SIGNATURES = {
     "lbt_quantize_grad": (_int, [_p, _i64, _p, _u64, _int, _p, _p, _sz, _p]),
     "lbt_workspace_bytes_quantize": (_sz, [_i64]),
     "lbt_quantize_operand": (_int, [_p, _i64, _f32, _int, _int, _p, _p, _p, _sz, _p]),
+    "lbt_backward_linear_learned": (_int, [_p, _p, _p, _i64, _i64, _i64, _f32, _int, _f32, _p, _u64,
+                                           _int, _p, _p, _p, _p, _sz, _p]),
+    "lbt_backward_conv2d_learned": (_int, [_p, _p, _p] + [_i64] * 9 + [_f32, _int, _f32, _p, _u64,
+                                                                       _int, _p, _p, _p, _p, _sz, _p]),
     "lbt_ste_backward": (_int, [_p, _i64, _f32, _int, _int, _p, _p, _p, _p, _sz, _p]),
     "lbt_backward_linear": (_int, [_p, _p, _p, _i64, _i64, _i64, _f32, _int, _f32, _p, _u64, _int,
                                    _p, _p, _p, _sz, _p]),
@@ -261,6 +265,24 @@ def lbt_ste_backward(x, c, is_unsigned, bits, grad_q, grad_x, grad_c, ws):
     wp, wb = _ws_args(ws)
     _check(load().lbt_ste_backward(_dp(x), x.numel(), c, int(is_unsigned), bits, _dp(grad_q),
                                    _dp(grad_x), _dp(grad_c), wp, wb, _stream()), "lbt_ste_backward")
+
+
+def lbt_backward_linear_learned(X, W, dY, M, K_in, N_out, c_x, x_unsigned, c_w, st, seed, rounding,
+                                dX, dW, grad_c, ws):
+    wp, wb = _ws_args(ws)
+    _check(load().lbt_backward_linear_learned(_dp(X), _dp(W), _dp(dY), M, K_in, N_out, c_x,
+                                              int(x_unsigned), c_w, _dp(st), seed, rounding,
+                                              _dp(dX), _dp(dW), _dp(grad_c), wp, wb, _stream()),
+           "lbt_backward_linear_learned")
+
+
+def lbt_backward_conv2d_learned(X, W, dY, N, Cc, H, Wd, K, R, S, stride, pad, c_x, x_unsigned, c_w,
+                                st, seed, rounding, dX, dW, grad_c, ws):
+    wp, wb = _ws_args(ws)
+    _check(load().lbt_backward_conv2d_learned(_dp(X), _dp(W), _dp(dY), N, Cc, H, Wd, K, R, S,
+                                              stride, pad, c_x, int(x_unsigned), c_w, _dp(st), seed,
+                                              rounding, _dp(dX), _dp(dW), _dp(grad_c), wp, wb,
+                                              _stream()), "lbt_backward_conv2d_learned")
 
 
 def lbt_saved_bytes_linear(M, K_in, N_out) -> int:

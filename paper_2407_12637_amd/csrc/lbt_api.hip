@@ -84,7 +84,15 @@ int backward_common(const float* X, const float* W, const float* dY, ConvGeom g,
                     bool w_is_ck, float c_x, int x_unsigned, float c_w, lbt_grad_state* st,
                     uint64_t seed, int rounding, float* dX, float* dW, int32_t* acc_dX,
                     int32_t* acc_dW, void* ws, size_t ws_bytes, void* stream,
-                    const void* saved = nullptr, size_t saved_bytes = 0) {
+                    const void* saved = nullptr, size_t saved_bytes = 0, float* grad_c = nullptr) {
+  // grad_c (2 floats, may be null): the clip values are learned - dW and dX are masked with the
+  // intervals of the weight / activation quantizers and grad_c receives dL/dc_w, dL/dc_x
+  if (grad_c) {
+    if (saved || !X || !W) return LBT_ERR_NULL;
+    if (!aligned(grad_c, 4)) return LBT_ERR_ALIGN;
+    if ((dW && !(c_w > 0.0f && c_w < INFINITY)) || (dX && !(c_x > 0.0f && c_x < INFINITY)))
+      return LBT_ERR_UNSUPPORTED;
+  }
   // saved: X and W were quantized by a forward call (lbt_forward_*_save); X, W, c_x, c_w unused
   if (!dY || !st || !ws) return LBT_ERR_NULL;
   if (!saved && (!W || (dW && !X))) return LBT_ERR_NULL;
@@ -168,11 +176,21 @@ int backward_common(const float* X, const float* W, const float* dY, ConvGeom g,
     rc = w_is_ck ? launch_linear_dw(g, g_kpqn, x_chwn, st, sc, x_unsigned, dW, acc_dW, partial, u, s)
                  : launch_conv_dw(g, g_kpqn, x_chwn, st, sc, x_unsigned, dW, acc_dW, partial, u, s);
     if (rc) return rc;
+    // dW is dL/dQ(W) and has W's layout: its mask and dL/dc_w (the partial-maxima area of the
+    // header is free again once the quantizers have run: scratch of the pass's partial sums)
+    if (grad_c && (rc = launch_ste_backward(W, dW, n_w, c_w, 0, bits, dW, grad_c,
+                                            reinterpret_cast<double*>(pmax), s)))
+      return rc;
   }
   if (dX) {
     rc = w_is_ck ? launch_linear_dx(g, w_crsk, g_npqk, st, sc, dX, acc_dX, upd, s)
                  : launch_conv_dx(g, w_crsk, g_npqk, st, sc, dX, acc_dX, upd, s);
     if (rc) return rc;
+    // dX is dL/dQ(X) and has X's layout.  (The mask applied in the product's epilogue instead
+    // was measured: the product then takes 1.5 ms more per ResNet-50 step, this pass 1.3 ms.)
+    if (grad_c && (rc = launch_ste_backward(X, dX, n_x, c_x, x_unsigned, bits, dX, grad_c + 1,
+                                            reinterpret_cast<double*>(pmax), s)))
+      return rc;
   }
   if (upd && !dX && !dW && (rc = launch_update_interval(st, s))) return rc;
   return LBT_OK;
@@ -487,6 +505,31 @@ int lbt_backward_linear_saved(const void* saved, size_t saved_bytes, const float
   if (rc) return rc;
   return backward_common(nullptr, nullptr, dY, g, true, 0.0f, x_unsigned, 0.0f, st, seed, rounding,
                          dX, dW, acc_dX, acc_dW, ws, ws_bytes, stream, saved, saved_bytes);
+}
+
+int lbt_backward_conv2d_learned(const float* X, const float* W, const float* dY, int64_t N,
+                                int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S,
+                                int64_t stride, int64_t pad, float c_x, int x_unsigned, float c_w,
+                                lbt_grad_state* st, uint64_t seed, int rounding, float* dX,
+                                float* dW, float* grad_c, void* ws, size_t ws_bytes, void* stream) {
+  if (!grad_c) return LBT_ERR_NULL;
+  ConvGeom g;
+  int rc = make_geom(N, C, H, Wd, K, R, S, stride, pad, &g);
+  if (rc) return rc;
+  return backward_common(X, W, dY, g, false, c_x, x_unsigned, c_w, st, seed, rounding, dX, dW,
+                         nullptr, nullptr, ws, ws_bytes, stream, nullptr, 0, grad_c);
+}
+
+int lbt_backward_linear_learned(const float* X, const float* W, const float* dY, int64_t M,
+                                int64_t K_in, int64_t N_out, float c_x, int x_unsigned, float c_w,
+                                lbt_grad_state* st, uint64_t seed, int rounding, float* dX,
+                                float* dW, float* grad_c, void* ws, size_t ws_bytes, void* stream) {
+  if (!grad_c) return LBT_ERR_NULL;
+  ConvGeom g;
+  int rc = make_geom(M, K_in, 1, 1, N_out, 1, 1, 1, 0, &g);
+  if (rc) return rc;
+  return backward_common(X, W, dY, g, true, c_x, x_unsigned, c_w, st, seed, rounding, dX, dW,
+                         nullptr, nullptr, ws, ws_bytes, stream, nullptr, 0, grad_c);
 }
 
 int lbt_backward_conv2d_acc(const float* X, const float* W, const float* dY, int64_t N, int64_t C,

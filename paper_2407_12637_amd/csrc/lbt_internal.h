@@ -55,6 +55,62 @@ __device__ __forceinline__ void interval_update(lbt_grad_state* st) {
   interval_update_with(st, st->n_out, st->n_total);
 }
 
+
+// ---- device helpers shared by the element-wise kernels and the products' epilogues -------
+// Per-call quantizer constants, uniform across the grid.
+struct QConst {
+  float c;       // clip value; <= 0 means "all codes zero"
+  float lo;      // lower clip bound: -c or 0
+  float inv_s;   // q / c
+  int q;         // largest code
+  int kmin;      // smallest code
+};
+
+__device__ __forceinline__ QConst make_qconst(float c, bool is_unsigned, int bits) {
+  QConst k;
+  k.c = c;
+  k.q = levels(bits, is_unsigned);
+  k.kmin = is_unsigned ? 0 : -k.q;
+  k.lo = is_unsigned ? 0.0f : -c;
+  k.inv_s = (c > 0.0f) ? (float)((double)k.q / (double)c) : 0.0f;
+  return k;
+}
+
+__device__ __forceinline__ float normalised(float v, const QConst& k) {
+  const float xc = fminf(fmaxf(v, k.lo), k.c);
+  return __fmul_rn(xc, k.inv_s);
+}
+
+__device__ __forceinline__ double wave_sum_f64(double v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+
+__device__ __forceinline__ double block_sum_f64(double v) {
+  __shared__ double part[16];
+  const int nw = blockDim.x >> 6;
+  v = wave_sum_f64(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = v;
+  __syncthreads();
+  double t = 0.0;
+  for (int i = 0; i < nw; ++i) t += part[i];
+  return t;
+}
+
+// One element of the gradient through an operand quantizer: returns the masked gradient and
+// adds g * (q * dQ/dc) to acc (the caller divides the sum by q once): q * dQ/dc is
+// round(u) - u inside the interval (exact in fp32: both are within 1/2 of each other), +q for
+// v >= c, below_q (-q signed, 0 unsigned) for v <= lo.
+__device__ __forceinline__ float ste_one(float v, float g, const QConst& k, float below_q, double& acc) {
+  const bool inside = v > k.lo && v < k.c;
+  const float u = normalised(v, k);
+  const float w = inside ? rintf(u) - u : (v >= k.c ? (float)k.q : (v <= k.lo ? below_q : 0.0f));
+  acc += (double)g * (double)w;
+  return inside ? g : 0.0f;
+}
+
 // ---- profile.hip: optional event timing of every launch ------------------------
 enum KernelId {
   KID_ABSMAX = 0, KID_FLAT_GRAD, KID_FLAT_OPERAND, KID_QUANTIZE_LAYER, KID_GEMM_DX,

@@ -66,32 +66,6 @@ __device__ __forceinline__ uint32_t r16_of(const Philox4& p, uint32_t lane) {
   return (p.w[lane >> 1] >> ((lane & 1u) * 16u)) & 0xFFFFu;
 }
 
-// ---------------------------------------------------------------------------
-// Per-call quantizer constants, uniform across the grid.
-// ---------------------------------------------------------------------------
-struct QConst {
-  float c;       // clip value; <= 0 means "all codes zero"
-  float lo;      // lower clip bound: -c or 0
-  float inv_s;   // q / c
-  int q;         // largest code
-  int kmin;      // smallest code
-};
-
-__device__ __forceinline__ QConst make_qconst(float c, bool is_unsigned, int bits) {
-  QConst k;
-  k.c = c;
-  k.q = levels(bits, is_unsigned);
-  k.kmin = is_unsigned ? 0 : -k.q;
-  k.lo = is_unsigned ? 0.0f : -c;
-  k.inv_s = (c > 0.0f) ? (float)((double)k.q / (double)c) : 0.0f;
-  return k;
-}
-
-__device__ __forceinline__ float normalised(float v, const QConst& k) {
-  const float xc = fminf(fmaxf(v, k.lo), k.c);
-  return __fmul_rn(xc, k.inv_s);
-}
-
 __device__ __forceinline__ int code_nearest(float v, const QConst& k) {
   const int r = (int)rintf(normalised(v, k));
   return min(max(r, k.kmin), k.q);
@@ -379,37 +353,10 @@ __global__ __launch_bounds__(kThreads) void k_absmax3(MaxSeg s0, MaxSeg s1, MaxS
 //   grad_x = grad_q inside the interval (lo < x < c), 0 outside;
 //   grad_c = sum grad_q * d,  d = (round(u) - u) / q inside, +1 for x >= c, -1 for x <= -c
 //            (signed), 0 for x <= 0 (unsigned);  u = clip(x) * (q / c) as the quantizer takes it.
-// Products and sums in fp64; one partial sum per workgroup, added in a fixed order by
+// Products and sums in fp64 (of grad_q * q d; one division by q per workgroup, none per
+// element); one partial sum per workgroup, added in a fixed order by
 // k_ste_finish, so the result does not depend on how the workgroups were scheduled.
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ double wave_sum_f64(double v) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-  return v;
-}
-
-__device__ __forceinline__ double block_sum_f64(double v) {
-  __shared__ double part[16];
-  const int nw = blockDim.x >> 6;
-  v = wave_sum_f64(v);
-  __syncthreads();
-  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = v;
-  __syncthreads();
-  double t = 0.0;
-  for (int i = 0; i < nw; ++i) t += part[i];
-  return t;
-}
-
-__device__ __forceinline__ float ste_one(float v, float g, const QConst& k, double below, double& acc) {
-  const bool inside = v > k.lo && v < k.c;
-  const float u = normalised(v, k);
-  const float r = rintf(u);
-  const double d = inside ? ((double)r - (double)u) / (double)k.q
-                          : (v >= k.c ? 1.0 : (v <= k.lo ? below : 0.0));
-  acc += (double)g * d;
-  return inside ? g : 0.0f;
-}
-
 // grad_x may be null, and may be grad_q itself (every element is read before it is written).
 // Streaming (non-temporal) loads and stores: nothing is read twice, and the masked gradient
 // leaves for HBM at once instead of being written back under the next kernel (measured on the
@@ -418,7 +365,7 @@ __global__ __launch_bounds__(kThreads) void k_ste_backward(const float* x, const
                                                             long long n, float c, int is_unsigned,
                                                             int bits, float* grad_x, double* partial) {
   const QConst k = make_qconst(c, is_unsigned != 0, bits);
-  const double below = is_unsigned ? 0.0 : -1.0;
+  const float below = is_unsigned ? 0.0f : -(float)k.q;
   const float4* x4 = reinterpret_cast<const float4*>(x);
   const float4* g4 = reinterpret_cast<const float4*>(grad_q);
   float4* o4 = reinterpret_cast<float4*>(grad_x);
@@ -457,7 +404,7 @@ __global__ __launch_bounds__(kThreads) void k_ste_backward(const float* x, const
     if (grad_x) grad_x[e] = o;
   }
   const double tot = block_sum_f64(acc);
-  if (partial && threadIdx.x == 0) partial[blockIdx.x] = tot;
+  if (partial && threadIdx.x == 0) partial[blockIdx.x] = tot / (double)k.q;
 }
 
 __global__ __launch_bounds__(kThreads) void k_ste_finish(const double* partial, int nblocks,
