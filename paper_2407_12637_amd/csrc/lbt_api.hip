@@ -171,6 +171,11 @@ int backward_common(const float* X, const float* W, const float* dY, ConvGeom g,
   //    with LBT_FUSED_UPDATE the last launch also applies Alg. 1 (the quantizers, all of which
   //    can change the status, have finished by then)
   lbt_grad_state* const upd = fused_update ? st : nullptr;
+  // partial sums of the two clip-value gradients: the two halves of the partial-maxima area
+  static_assert(2 * (size_t)kStePartials * sizeof(double) <= kWsHeaderBytes - kWsScalarsBytes,
+                "both passes' partial sums must fit the header");
+  double* const ste_w = reinterpret_cast<double*>(pmax);
+  double* const ste_x = ste_w + kStePartials;
   if (dW) {
     lbt_grad_state* const u = dX ? nullptr : upd;
     rc = w_is_ck ? launch_linear_dw(g, g_kpqn, x_chwn, st, sc, x_unsigned, dW, acc_dW, partial, u, s)
@@ -178,8 +183,7 @@ int backward_common(const float* X, const float* W, const float* dY, ConvGeom g,
     if (rc) return rc;
     // dW is dL/dQ(W) and has W's layout: its mask and dL/dc_w (the partial-maxima area of the
     // header is free again once the quantizers have run: scratch of the pass's partial sums)
-    if (grad_c && (rc = launch_ste_backward(W, dW, n_w, c_w, 0, bits, dW, grad_c,
-                                            reinterpret_cast<double*>(pmax), s)))
+    if (grad_c && (rc = launch_ste_backward(W, dW, n_w, c_w, 0, bits, dW, nullptr, ste_w, s, false)))
       return rc;
   }
   if (dX) {
@@ -188,10 +192,17 @@ int backward_common(const float* X, const float* W, const float* dY, ConvGeom g,
     if (rc) return rc;
     // dX is dL/dQ(X) and has X's layout.  (The mask applied in the product's epilogue instead
     // was measured: the product then takes 1.5 ms more per ResNet-50 step, this pass 1.3 ms.)
-    if (grad_c && (rc = launch_ste_backward(X, dX, n_x, c_x, x_unsigned, bits, dX, grad_c + 1,
-                                            reinterpret_cast<double*>(pmax), s)))
+    if (grad_c && (rc = launch_ste_backward(X, dX, n_x, c_x, x_unsigned, bits, dX, nullptr, ste_x, s,
+                                            false)))
       return rc;
   }
+  // the sums of both passes in one launch
+  if (grad_c && dW && dX && (rc = launch_ste_finish(ste_w, n_w, grad_c, ste_x, n_x, grad_c + 1, s)))
+    return rc;
+  if (grad_c && dW && !dX && (rc = launch_ste_finish(ste_w, n_w, grad_c, nullptr, 0, nullptr, s)))
+    return rc;
+  if (grad_c && dX && !dW && (rc = launch_ste_finish(ste_x, n_x, grad_c + 1, nullptr, 0, nullptr, s)))
+    return rc;
   if (upd && !dX && !dW && (rc = launch_update_interval(st, s))) return rc;
   return LBT_OK;
 }

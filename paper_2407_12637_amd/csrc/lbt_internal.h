@@ -198,7 +198,10 @@ int launch_quantize_layer(const LayerTensors& q, hipStream_t s);
 // partial-maxima area of a workspace header is large enough).
 constexpr int kStePartials = 2048;
 int launch_ste_backward(const float* x, const float* grad_q, int64_t n, float c, int is_unsigned,
-                        int bits, float* grad_x, float* grad_c, double* partial, hipStream_t s);
+                        int bits, float* grad_x, float* grad_c, double* partial, hipStream_t s,
+                        bool finish = true);
+int launch_ste_finish(const double* partial0, int64_t n0, float* grad_c0, const double* partial1,
+                      int64_t n1, float* grad_c1, hipStream_t s);
 int launch_update_interval(lbt_grad_state* st, hipStream_t s);
 int launch_state_init(lbt_grad_state* st, const lbt_grad_state& v, hipStream_t s);
 

@@ -407,12 +407,20 @@ __global__ __launch_bounds__(kThreads) void k_ste_backward(const float* x, const
   if (partial && threadIdx.x == 0) partial[blockIdx.x] = tot / (double)k.q;
 }
 
-__global__ __launch_bounds__(kThreads) void k_ste_finish(const double* partial, int nblocks,
-                                                          float* grad_c) {
+// Workgroup j adds the partial sums of pass j (one or two passes per launch).
+struct SteSums {
+  const double* partial[2];
+  int nblocks[2];
+  float* grad_c[2];
+};
+__global__ __launch_bounds__(kThreads) void k_ste_finish(const SteSums f) {
+  const int j = blockIdx.x;
+  const double* partial = j ? f.partial[1] : f.partial[0];
+  const int nblocks = j ? f.nblocks[1] : f.nblocks[0];
   double acc = 0.0;
   for (int i = threadIdx.x; i < nblocks; i += kThreads) acc += partial[i];
   const double tot = block_sum_f64(acc);
-  if (threadIdx.x == 0) *grad_c = (float)tot;
+  if (threadIdx.x == 0) *(j ? f.grad_c[1] : f.grad_c[0]) = (float)tot;
 }
 
 // Largest |v| of eight values as an fp32 bit pattern (NaN/Inf sort on top).
@@ -1055,19 +1063,37 @@ int launch_absmax3(const float* p0, int64_t n0, int abs0, const float* p1, int64
   return LBT_OK;
 }
 
-int launch_ste_backward(const float* x, const float* grad_q, int64_t n, float c, int is_unsigned,
-                        int bits, float* grad_x, float* grad_c, double* partial, hipStream_t s) {
-  ProfScope prof(KID_STE, (double)n, s);
+int ste_blocks(int64_t n) {
   long long blocks = ((n >> 2) + 2 * kThreads - 1) / (2 * kThreads);
   if (blocks > kStePartials) blocks = kStePartials;
-  if (blocks < 1) blocks = 1;
+  return blocks < 1 ? 1 : (int)blocks;
+}
+
+// finish = false: the partial sums stay in `partial` for a later launch_ste_finish.
+int launch_ste_backward(const float* x, const float* grad_q, int64_t n, float c, int is_unsigned,
+                        int bits, float* grad_x, float* grad_c, double* partial, hipStream_t s,
+                        bool finish) {
+  ProfScope prof(KID_STE, (double)n, s);
+  const int blocks = ste_blocks(n);
   LBT_LAUNCH(k_ste_backward, dim3((unsigned)blocks), dim3(kThreads), 0, s, x, grad_q, (long long)n, c,
-             is_unsigned, bits, grad_x, grad_c ? partial : (double*)nullptr);
+             is_unsigned, bits, grad_x, (grad_c || !finish) ? partial : (double*)nullptr);
   LBT_LAUNCH_CHECK();
-  if (grad_c) {
-    LBT_LAUNCH(k_ste_finish, dim3(1), dim3(kThreads), 0, s, (const double*)partial, (int)blocks, grad_c);
+  if (grad_c && finish) {
+    SteSums f{{partial, nullptr}, {blocks, 0}, {grad_c, nullptr}};
+    LBT_LAUNCH(k_ste_finish, dim3(1), dim3(kThreads), 0, s, f);
     LBT_LAUNCH_CHECK();
   }
+  return LBT_OK;
+}
+
+// The sums of one or two passes of n0 (and n1 > 0) elements whose partial sums were left in
+// partial0 (and partial1), in one launch.
+int launch_ste_finish(const double* partial0, int64_t n0, float* grad_c0, const double* partial1,
+                      int64_t n1, float* grad_c1, hipStream_t s) {
+  ProfScope prof(KID_STE, 0.0, s);
+  SteSums f{{partial0, partial1}, {ste_blocks(n0), n1 > 0 ? ste_blocks(n1) : 0}, {grad_c0, grad_c1}};
+  LBT_LAUNCH(k_ste_finish, dim3(n1 > 0 ? 2 : 1), dim3(kThreads), 0, s, f);
+  LBT_LAUNCH_CHECK();
   return LBT_OK;
 }
 
