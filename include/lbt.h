@@ -16,6 +16,10 @@
  * be ordered (same stream, or the caller's events).  Calls on different streams with
  * workspaces and states of their own may overlap.  A buffer of kept operand codes is written
  * by the forward call and only read by backward calls, which must be ordered after it.
+ * A call may be captured into a HIP graph and replayed (it enqueues kernels only: no
+ * allocation, no memset, no host synchronisation; the state advances on every replay); make one
+ * call of the same shape outside the capture first (the first launch of a kernel variant sets
+ * a function attribute).
  *
  * Conventions for every entry point
  *   - Returns LBT_OK (0) or a negative LBT_ERR_* code.  Nothing throws.
