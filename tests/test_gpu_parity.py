@@ -421,3 +421,60 @@ def test_calls_on_several_streams_with_their_own_workspaces():
             gu.assert_state_equal(lbt.lbt_state_read(w["st"]), w["ost"])
             gu.assert_outputs_close(w["dX"].cpu().numpy(), ref.dX)
             gu.assert_outputs_close(w["dW"].cpu().numpy(), ref.dW)
+
+
+def test_calls_from_several_host_threads():
+    """Three host threads, each with a stream, a workspace and layers of its own, call the library
+    at the same time (the library keeps no state between calls except its optional timer and
+    per-kernel attribute flags): every result equals the oracle's."""
+    import threading
+    cases = [(4, 16, 12, 12, 32, 3, 3, 1, 1), (8, 64, 14, 14, 160, 1, 1, 1, 0),
+             (3, 20, 10, 10, 24, 1, 1, 2, 0), (16, 16, 32, 32, 16, 3, 3, 1, 1),
+             (2, 24, 9, 9, 136, 3, 3, 2, 1), (5, 17, 6, 6, 33, 1, 1, 1, 0)]
+    r = synth.rng(0, 25, 0, 0)
+    work = []
+    for i, (N, Cc, H, W, K, R, S, stride, pad) in enumerate(cases):
+        P, Q = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1
+        X, Wt = synth.relu_normal(r, (N, Cc, H, W)), synth.kaiming_normal(r, (K, Cc, R, S))
+        dY = synth.dense_grad(r, (N, K, P, Q))
+        work.append(dict(case=cases[i], X=X, W=Wt, dY=dY, dev=[gu.dev(a) for a in (X, Wt, dY)],
+                         dX=torch.empty(X.shape, device=gu.DEV), dW=torch.empty(Wt.shape, device=gu.DEV),
+                         st=lbt.new_state(gamma0=0.4), ost=oracle.GradState(gamma=0.4)))
+    torch.cuda.synchronize()
+    errors = []
+
+    def run(tid):
+        try:
+            torch.cuda.set_device(0)
+            stream = torch.cuda.Stream()
+            mine = [w for i, w in enumerate(work) if i % 3 == tid]
+            ws = torch.zeros(max(lbt.lbt_workspace_bytes_conv2d(*w["case"]) for w in mine),
+                             dtype=torch.uint8, device=gu.DEV)
+            with torch.cuda.stream(stream):
+                for it in range(20):
+                    for w in mine:
+                        N, Cc, H, W, K, R, S, stride, pad = w["case"]
+                        lbt.lbt_backward_conv2d(w["dev"][0], w["dev"][1], w["dev"][2], N, Cc, H, W, K,
+                                                R, S, stride, pad, 0.0, True, 0.0, w["st"], 5,
+                                                lbt.ROUND_STOCHASTIC | lbt.FUSED_UPDATE, w["dX"],
+                                                w["dW"], ws)
+            stream.synchronize()
+        except Exception as e:      # reported by the main thread
+            errors.append((tid, repr(e)))
+
+    threads = [threading.Thread(target=run, args=(t,)) for t in range(3)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    torch.cuda.synchronize()
+    assert not errors, errors
+    for w in work:
+        N, Cc, H, W, K, R, S, stride, pad = w["case"]
+        for it in range(20):
+            ref = oracle.backward_conv2d(w["X"], w["W"], w["dY"], stride, pad, w["ost"], seed=5,
+                                         rounding=oracle.STOCHASTIC)
+            oracle.update_interval(w["ost"])
+        gu.assert_state_equal(lbt.lbt_state_read(w["st"]), w["ost"])
+        gu.assert_outputs_close(w["dX"].cpu().numpy(), ref.dX)
+        gu.assert_outputs_close(w["dW"].cpu().numpy(), ref.dW)
