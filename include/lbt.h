@@ -168,8 +168,9 @@ int lbt_quantize_operand(const float* x, int64_t n, float c, int is_unsigned, in
  * Gradient of a loss through the operand quantizer, for callers that learn the clip values of
  * weights and activations (Sec. 3.1 learns them end to end and gives no formula; this is the
  * derivative of Eq. 1-4 with the rounding passed straight through, i.e. the step-size gradient
- * of the learned-step-size quantizers the section cites, over q).  With grad_q = dL/dQ(x) (for
- * weights the dW of lbt_backward_*, for activations the dX of the layer above):
+ * of the learned-step-size quantizers the section cites, over q).  With grad_q = dL/dQ(x) (the
+ * dW, for a layer's weights, and the dX, for its input activations, that lbt_backward_* returns
+ * for that layer):
  *   grad_x[i] = grad_q[i] if lo < x[i] < c, else 0            (lo = -c signed, 0 unsigned)
  *   grad_c    = sum_i grad_q[i] * d_i,   d_i = (round(u_i) - u_i) / q inside the interval,
  *               +1 for x[i] >= c, -1 for x[i] <= -c (signed), 0 for x[i] <= 0 (unsigned),
