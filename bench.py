@@ -41,8 +41,8 @@ UPDATE_KERNEL_US = 4.1
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--rounding", choices=["stochastic", "nearest"], default="stochastic")
     ap.add_argument("--gamma0", type=float, default=1.0)
     ap.add_argument("--bits", type=int, default=4, choices=[2, 3, 4, 5, 6, 7, 8],
