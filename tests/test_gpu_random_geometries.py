@@ -82,6 +82,44 @@ def test_random_conv_geometry(idx):
     _check_backward(res, ref)
 
 
+@pytest.mark.parametrize("idx", range(0, len(GEOMS), 2))
+def test_random_conv_geometry_other_bits_and_learned_clips(idx):
+    """Every second geometry again at b = 5, 6 or 8 through lbt_backward_conv2d_learned (given clip
+    values, masks and clip-value gradients) against the oracle's backward pass and ste_backward."""
+    import torch
+    N, C, H, W, K, R, S, stride, pad = GEOMS[idx]
+    bits = (5, 6, 8)[(idx // 2) % 3]
+    x_unsigned = bits < 8 and bool(idx % 4)
+    print("random conv learned", idx, GEOMS[idx], bits, flush=True)
+    r = synth.rng(0, 103, idx, 0)
+    X = synth.relu_normal(r, (N, C, H, W)) if x_unsigned else synth.normal(r, (N, C, H, W))
+    Wt = synth.kaiming_normal(r, (K, C, R, S))
+    P, Q = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1
+    dY = synth.dense_grad(r, (N, K, P, Q))
+    c_x, c_w = 1.1, float(np.abs(Wt).max() * 0.7)
+    st = lbt.new_state(gamma0=0.6, bits=bits)
+    ost = oracle.GradState(gamma=0.6, bits=bits)
+    ref = oracle.backward_conv2d(X, Wt, dY, stride, pad, ost, c_x=c_x, x_unsigned=x_unsigned, c_w=c_w,
+                                 seed=idx, rounding=1)
+    want_dw, want_cw, mag_w = oracle.ste_backward(Wt, np.float32(c_w), False, bits, ref.dW)
+    want_dx, want_cx, mag_x = oracle.ste_backward(X, np.float32(c_x), x_unsigned, bits, ref.dX)
+    ws = torch.zeros(lbt.lbt_workspace_bytes_conv2d(N, C, H, W, K, R, S, stride, pad),
+                     dtype=torch.uint8, device=gu.DEV)
+    dX = torch.full(X.shape, float("nan"), device=gu.DEV)
+    dW = torch.full(Wt.shape, float("nan"), device=gu.DEV)
+    gc = torch.full((2,), float("nan"), device=gu.DEV)
+    lbt.lbt_backward_conv2d_learned(gu.dev(X), gu.dev(Wt), gu.dev(dY), N, C, H, W, K, R, S, stride,
+                                    pad, c_x, x_unsigned, c_w, st, idx, 1 | lbt.BITS(bits), dX, dW, gc,
+                                    ws)
+    gu.assert_state_equal(lbt.lbt_state_read(st), ost)
+    got_dx, got_dw, got_c = dX.cpu().numpy(), dW.cpu().numpy(), gc.cpu().numpy().astype(np.float64)
+    assert np.array_equal(got_dx == 0, want_dx == 0) and np.array_equal(got_dw == 0, want_dw == 0)
+    gu.assert_outputs_close(got_dx, want_dx)
+    gu.assert_outputs_close(got_dw, want_dw)
+    assert abs(got_c[0] - want_cw) <= 1e-5 * abs(want_cw) + 1e-6 * mag_w
+    assert abs(got_c[1] - want_cx) <= 1e-5 * abs(want_cx) + 1e-6 * mag_x
+
+
 def _linear_shapes(n, seed):
     r = np.random.default_rng(seed)
     return [(int(r.integers(1, 300)), int(r.integers(1, 300)), int(r.integers(1, 300)))
