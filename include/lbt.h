@@ -61,6 +61,7 @@ extern "C" {
 #define LBT_ERR_OVERFLOW (-5)    /* a contraction could exceed int32 accumulators  */
 #define LBT_ERR_HIP (-6)         /* a HIP runtime call failed                      */
 #define LBT_ERR_ALIGN (-7)       /* a pointer is not aligned as required           */
+#define LBT_ERR_TOO_LARGE (-8)   /* lbt_quantize_grad_static: n above LBT_QUANTIZE_STATIC_MAX_N */
 
 #define LBT_STATUS_OK 0
 #define LBT_STATUS_NONFINITE 1   /* NaN or Inf seen in a tensor whose maximum was taken */
@@ -151,6 +152,23 @@ int lbt_update_interval(lbt_grad_state* st, void* stream);
 int lbt_quantize_grad(const float* g, int64_t n, lbt_grad_state* st, uint64_t seed,
                       int rounding, uint8_t* codes, void* ws, size_t ws_bytes, void* stream);
 size_t lbt_workspace_bytes_quantize(int64_t n);
+
+/*
+ * lbt_quantize_grad for callers that cannot allocate device memory and have no workspace to
+ * pass (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc):
+ * same arguments, kernels and results, but the scratch (partial maxima and arrival counters,
+ * 33 024 bytes) is a static array in the library's device image, one copy per GPU, held until
+ * the process ends.  The call allocates nothing (no hipMalloc / hipFree, no allocating library
+ * routine).  n up to LBT_QUANTIZE_STATIC_MAX_N elements; above that LBT_ERR_TOO_LARGE and
+ * nothing is enqueued.  All calls on one GPU share that GPU's array: calls that overlap on one
+ * GPU (different streams or threads) race; order them.  The array needs no clearing between
+ * calls (every call resets the counters it uses before it reads them), so a call may follow
+ * one of any other size.  The first call on a device looks up the array's address; make that
+ * call outside a graph capture.
+ */
+#define LBT_QUANTIZE_STATIC_MAX_N ((int64_t)1 << 30)
+int lbt_quantize_grad_static(const float* g, int64_t n, lbt_grad_state* st, uint64_t seed,
+                             int rounding, uint8_t* codes, void* stream);
 
 /*
  * Weight / activation quantizer (Eq. 2 for zero-centred inputs, Eq. 3 for

@@ -63,6 +63,7 @@ SIGNATURES = {
     "lbt_update_interval": (_int, [_p, _p]),
     "lbt_quantize_grad": (_int, [_p, _i64, _p, _u64, _int, _p, _p, _sz, _p]),
     "lbt_workspace_bytes_quantize": (_sz, [_i64]),
+    "lbt_quantize_grad_static": (_int, [_p, _i64, _p, _u64, _int, _p, _p]),
     "lbt_quantize_operand": (_int, [_p, _i64, _f32, _int, _int, _p, _p, _p, _sz, _p]),
     "lbt_backward_linear_learned": (_int, [_p, _p, _p, _i64, _i64, _i64, _f32, _int, _f32, _p, _u64,
                                            _int, _p, _p, _p, _p, _sz, _p]),
@@ -195,6 +196,11 @@ def lbt_quantize_grad(g, st, seed, rounding, codes, ws):
     wp, wb = _ws_args(ws)
     _check(load().lbt_quantize_grad(_dp(g), g.numel(), _dp(st), seed, rounding, _dp(codes), wp, wb,
                                     _stream()), "lbt_quantize_grad")
+
+
+def lbt_quantize_grad_static(g, st, seed, rounding, codes):
+    _check(load().lbt_quantize_grad_static(_dp(g), g.numel(), _dp(st), seed, rounding, _dp(codes),
+                                           _stream()), "lbt_quantize_grad_static")
 
 
 def lbt_quantize_operand(x, c, is_unsigned, bits, codes, clip_scale_out, ws):

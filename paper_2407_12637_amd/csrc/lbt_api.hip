@@ -1,10 +1,35 @@
 // C ABI of liblbt.so: argument validation, workspace carving, kernel sequencing.
 // Every call only enqueues work on the caller's stream (lbt_state_read excepted).
+#include <mutex>
+
 #include "lbt_internal.h"
 
 using namespace lbt;
 
+// Scratch of lbt_quantize_grad_static (the partial maxima and arrival counters that the other
+// entry points keep in the caller's workspace): one copy per GPU, held until the process ends.
+// The name is only a host-side handle: host code uses the address hipGetSymbolAddress returns.
+static __device__ __align__(256) unsigned char scratch[kWsHeaderBytes];
+
 namespace {
+
+// Device address of `scratch` on the current device, looked up once per device.
+int static_scratch(void** out) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static void* ptr[kMaxDevices];
+  int device = -1;
+  if (hipGetDevice(&device) != hipSuccess) return LBT_ERR_HIP;
+  if (device < 0 || device >= kMaxDevices) return LBT_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptr[device]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return LBT_ERR_HIP;
+    ptr[device] = p;
+  }
+  *out = ptr[device];
+  return LBT_OK;
+}
 
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 inline size_t pad256(size_t b) { return (b + 255) / 256 * 256; }
@@ -301,6 +326,7 @@ const char* lbt_strerror(int code) {
     case LBT_ERR_OVERFLOW: return "contraction may overflow int32";
     case LBT_ERR_HIP: return "HIP runtime error";
     case LBT_ERR_ALIGN: return "misaligned pointer";
+    case LBT_ERR_TOO_LARGE: return "tensor larger than the static scratch serves";
     default: return "unknown error";
   }
 }
@@ -370,6 +396,20 @@ int lbt_quantize_grad(const float* g, int64_t n, lbt_grad_state* st, uint64_t se
     return rc;
   return launch_quantize_flat_grad(g, n, pmax, nblocks, st, seed, rounding, hindsight, fused_update,
                                    bits, codes, s);
+}
+
+int lbt_quantize_grad_static(const float* g, int64_t n, lbt_grad_state* st, uint64_t seed,
+                             int rounding, uint8_t* codes, void* stream) {
+  if (!g || !st || !codes) return LBT_ERR_NULL;
+  if (n <= 0) return LBT_ERR_SHAPE;
+  if (n > LBT_QUANTIZE_STATIC_MAX_N) return LBT_ERR_TOO_LARGE;
+  static_assert(sizeof(scratch) >= kWsHeaderBytes, "scratch must hold a workspace header");
+  void* ws = nullptr;
+  const int rc = static_scratch(&ws);
+  if (rc) return rc;
+  // the same kernels as lbt_quantize_grad, on this GPU's static scratch; nothing in it has to
+  // start at zero (the maximum kernel resets the counters it shares with the quantizer)
+  return lbt_quantize_grad(g, n, st, seed, rounding, codes, ws, sizeof(scratch), stream);
 }
 
 int lbt_quantize_operand(const float* x, int64_t n, float c, int is_unsigned, int bits,
