@@ -43,11 +43,11 @@ def _both(g, gamma, seed, rounding, step=0):
         codes = torch.full((n if bits > 4 else (n + 1) // 2,), 0xEE, dtype=torch.uint8, device=gu.DEV)
         if static:
             torch.cuda.synchronize()
-            before = torch.cuda.memory_allocated(), torch.cuda.mem_get_info()[0]
+            before = torch.cuda.mem_get_info()[0]       # free device memory, as the driver sees it
             lbt.lbt_quantize_grad_static(gd, st, seed, rounding, codes)
             torch.cuda.synchronize()
             if _warm[0]:
-                assert (torch.cuda.memory_allocated(), torch.cuda.mem_get_info()[0]) == before
+                assert torch.cuda.mem_get_info()[0] == before
             _warm[0] = True
         else:
             ws = torch.zeros(lbt.lbt_workspace_bytes_quantize(n), dtype=torch.uint8, device=gu.DEV)
