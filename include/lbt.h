@@ -65,7 +65,9 @@ extern "C" {
 
 #define LBT_STATUS_OK 0
 #define LBT_STATUS_NONFINITE 1   /* NaN or Inf seen in a tensor whose maximum was taken */
-#define LBT_STATUS_ZERO_GRAD 2   /* max|dY| == 0: codes 0, scale 0, gamma not updated   */
+#define LBT_STATUS_ZERO_GRAD 2   /* max|dY| == 0, or c_g so small (below about q * 2.9e-39) that q / c_g
+                                    is not a finite fp32 number: codes 0, clip 0, scale 0, gamma
+                                    not updated                                          */
 
 #define LBT_ROUND_NEAREST 0      /* round half to even                              */
 #define LBT_ROUND_STOCHASTIC 1   /* (floor(x_n*2^16) + r16) >> 16, r16 from Philox  */
@@ -177,6 +179,8 @@ int lbt_quantize_grad_static(const float* g, int64_t n, lbt_grad_state* st, uint
  * paper, Sec. 3.1); c <= 0 selects the tensor's own maximum (max|x| signed,
  * max x unsigned).  clip_scale_out (device, 2 floats, may be NULL) receives
  * the clip value and the scale s.  ws: lbt_workspace_bytes_quantize(n).
+ * A clip value so small that q / c is not a finite fp32 number (below about q * 2.9e-39) gives
+ * all-zero codes, like c = 0 (an all-zero tensor).
  */
 int lbt_quantize_operand(const float* x, int64_t n, float c, int is_unsigned, int bits,
                          uint8_t* codes, float* clip_scale_out, void* ws, size_t ws_bytes,
@@ -197,7 +201,8 @@ int lbt_quantize_operand(const float* x, int64_t n, float c, int is_unsigned, in
  * (in place).  grad_c: device, one float, may be NULL; products and the sum are taken in fp64
  * in a fixed order (the same inputs give the same bits).  c must be > 0 and finite
  * (LBT_ERR_UNSUPPORTED otherwise: an interval taken from the tensor's maximum has no learned
- * parameter).  ws: lbt_workspace_bytes_quantize(n).
+ * parameter), and large enough that q / c is a finite fp32 number.
+ * ws: lbt_workspace_bytes_quantize(n).
  */
 int lbt_ste_backward(const float* x, int64_t n, float c, int is_unsigned, int bits,
                      const float* grad_q, float* grad_x, float* grad_c, void* ws, size_t ws_bytes,

@@ -63,6 +63,8 @@ def _L():
         lib.orc_clip_value.restype = f32
         lib.orc_levels.argtypes = [i32, i32]
         lib.orc_levels.restype = i32
+        lib.orc_interval_usable.argtypes = [f32, i32, i32]
+        lib.orc_interval_usable.restype = i32
         lib.orc_scale.argtypes = [f32, i32, i32]
         lib.orc_scale.restype = f64
         lib.orc_quantize.argtypes = [p, i64, f32, i32, i32, i32, u64, u64, p, p]
@@ -130,6 +132,11 @@ def levels(bits: int, is_unsigned: bool = False) -> int:
     return int(_L().orc_levels(bits, int(is_unsigned)))
 
 
+def interval_usable(c, bits: int, is_unsigned: bool = False) -> bool:
+    """False for c <= 0 and for c so small that q / c is not a finite fp32 number."""
+    return bool(_L().orc_interval_usable(float(c), bits, int(is_unsigned)))
+
+
 def scale(c, bits: int, is_unsigned: bool = False) -> float:
     return float(_L().orc_scale(float(c), bits, int(is_unsigned)))
 
@@ -193,13 +200,15 @@ def quantize_grad(g, st: GradState, seed: int = 0, rounding: int = NEAREST,
     st.n_total = int(g.size)
     if status == NONFINITE:
         return None
-    if status == ZERO_GRAD:
-        st.gmax = np.float32(0)
+    c = clip_value(st.gamma, gmax) if status == OK else np.float32(0)
+    if status == ZERO_GRAD or not interval_usable(c, st.bits):
+        # all-zero tensor, or gradients of subnormal scale whose interval cannot be divided by
+        st.status = ZERO_GRAD
+        st.gmax = gmax
         st.clip = np.float32(0)
         st.scale = np.float32(0)
         st.n_out = 0
         return np.zeros(g.shape, dtype=np.int32)
-    c = clip_value(st.gamma, gmax)
     code, n_out = quantize(g, c, st.bits, False, rounding, seed, st.step)
     st.gmax, st.clip, st.n_out = gmax, c, n_out
     st.scale = np.float32(scale(c, st.bits, False))
@@ -210,7 +219,7 @@ def _quantize_grad_hindsight(g, st: GradState, seed: int, rounding: int):
     gmax_now, status_now = tensor_max(g, use_abs=True)
     st.n_total = int(g.size)
     prev = np.float32(st.gmax)
-    if np.isfinite(prev) and prev > 0:
+    if np.isfinite(prev) and prev > 0 and interval_usable(clip_value(st.gamma, prev), st.bits):
         c = clip_value(st.gamma, prev)
         code, n_out = quantize(g, c, st.bits, False, rounding, seed, st.step)
         status = OK
@@ -507,7 +516,7 @@ def ste_backward(x, c, is_unsigned: bool, bits: int, grad_q):
     g = _f32(grad_q)
     assert x.shape == g.shape
     c = np.float32(c)
-    assert c > 0
+    assert interval_usable(c, bits, is_unsigned)
     q = levels(bits, is_unsigned)
     inv_s = np.float32(np.float64(q) / np.float64(c))
     lo = np.float32(0.0) if is_unsigned else np.float32(-c)

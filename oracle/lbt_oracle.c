@@ -133,6 +133,16 @@ int orc_levels(int bits, int is_unsigned) {
   return is_unsigned ? ((1 << bits) - 1) : ((1 << (bits - 1)) - 1);
 }
 
+/* Eq. (1) divides by s = c / q; the code decision multiplies by fl32(q / c).  An
+ * interval so small that this factor is not a finite fp32 number (c below about
+ * q * 2.9e-39, i.e. subnormal-scale tensors) cannot be normalised by and is
+ * treated like c = 0: every code is zero. */
+int orc_interval_usable(float c, int bits, int is_unsigned) {
+  if (!(c > 0.0f)) return 0;
+  float inv_s = (float)((double)orc_levels(bits, is_unsigned) / (double)c);
+  return isfinite(inv_s) ? 1 : 0;
+}
+
 /* s = c / q (Eq. 2, 3). */
 double orc_scale(float c, int bits, int is_unsigned) {
   if (!(c > 0.0f)) return 0.0;
@@ -149,7 +159,7 @@ double orc_scale(float c, int bits, int is_unsigned) {
 void orc_quantize(const float* x, int64_t n, float c, int bits, int is_unsigned, int rounding,
                   uint64_t seed, uint64_t step, int32_t* code, uint64_t* n_out) {
   uint64_t cnt = 0;
-  if (!(c > 0.0f)) { /* degenerate interval: every code is zero */
+  if (!orc_interval_usable(c, bits, is_unsigned)) { /* degenerate interval: every code is zero */
     for (int64_t i = 0; i < n; ++i) code[i] = 0;
     if (n_out) *n_out = 0;
     return;

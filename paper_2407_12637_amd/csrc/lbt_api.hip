@@ -117,6 +117,9 @@ int backward_common(const float* X, const float* W, const float* dY, ConvGeom g,
     if (!aligned(grad_c, 4)) return LBT_ERR_ALIGN;
     if ((dW && !(c_w > 0.0f && c_w < INFINITY)) || (dX && !(c_x > 0.0f && c_x < INFINITY)))
       return LBT_ERR_UNSUPPORTED;
+    // (bit-widths 2..8: an interval usable at the largest q is usable at every q)
+    if ((dW && !interval_usable(c_w, 255)) || (dX && !interval_usable(c_x, 255)))
+      return LBT_ERR_UNSUPPORTED;
   }
   // saved: X and W were quantized by a forward call (lbt_forward_*_save); X, W, c_x, c_w unused
   if (!dY || !st || !ws) return LBT_ERR_NULL;
@@ -438,7 +441,8 @@ int lbt_ste_backward(const float* x, int64_t n, float c, int is_unsigned, int bi
                      void* stream) {
   if (!x || !grad_q || !ws) return LBT_ERR_NULL;
   if (n <= 0) return LBT_ERR_SHAPE;
-  if (bits < 2 || bits > 8 || !(c > 0.0f) || !(c < INFINITY)) return LBT_ERR_UNSUPPORTED;
+  if (bits < 2 || bits > 8 || !(c < INFINITY) || !interval_usable(c, levels(bits, is_unsigned != 0)))
+    return LBT_ERR_UNSUPPORTED;
   if (!aligned(x, 16) || !aligned(grad_q, 16) || (grad_x && !aligned(grad_x, 16)) ||
       (grad_c && !aligned(grad_c, 4)) || !aligned(ws, 256))
     return LBT_ERR_ALIGN;

@@ -64,7 +64,14 @@ struct QConst {
   float inv_s;   // q / c
   int q;         // largest code
   int kmin;      // smallest code
+  bool live;     // false: degenerate interval (c <= 0, or so small that q / c is not a finite
+                 // fp32 number): every code is 0
 };
+
+// Eq. (1) needs q / c as a finite fp32 number; below c ~ q * 2.9e-39 it is not.
+__host__ __device__ inline bool interval_usable(float c, int q) {
+  return c > 0.0f && (float)((double)q / (double)c) < INFINITY;
+}
 
 __device__ __forceinline__ QConst make_qconst(float c, bool is_unsigned, int bits) {
   QConst k;
@@ -72,7 +79,8 @@ __device__ __forceinline__ QConst make_qconst(float c, bool is_unsigned, int bit
   k.q = levels(bits, is_unsigned);
   k.kmin = is_unsigned ? 0 : -k.q;
   k.lo = is_unsigned ? 0.0f : -c;
-  k.inv_s = (c > 0.0f) ? (float)((double)k.q / (double)c) : 0.0f;
+  k.live = interval_usable(c, k.q);
+  k.inv_s = k.live ? (float)((double)k.q / (double)c) : 0.0f;
   return k;
 }
 

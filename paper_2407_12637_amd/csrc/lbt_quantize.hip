@@ -167,6 +167,11 @@ __device__ __forceinline__ GradSetup grad_setup(const lbt_grad_state* st, const 
   else {
     g.status = LBT_STATUS_OK;
     g.c = (float)__dmul_rn(st->gamma, (double)g.gmax);
+    // an interval too small to normalise by (subnormal-scale gradients) counts as all-zero
+    if (!interval_usable(g.c, levels(bits, false))) {
+      g.status = LBT_STATUS_ZERO_GRAD;
+      g.c = 0.0f;
+    }
   }
   return g;
 }
@@ -453,7 +458,7 @@ __global__ __launch_bounds__(kThreads) void k_quantize_flat(
   }
   const QConst qc = make_qconst(c, MODE == 1, bits);
   const bool bytes = bits > 4;   // one byte per code instead of one nibble
-  const bool live = c > 0.0f;
+  const bool live = qc.live;
   const unsigned long long step = (MODE == 3) ? st->step : 0ull;
   const long long groups = (n + 7) / 8;
   const long long stride = (long long)gridDim.x * kThreads;
@@ -728,7 +733,7 @@ __device__ __forceinline__ void stream_body(const TileArgs& t, int pitch, int tl
                       t.st, nullptr, bc.first, t.bits);
   }
   const QConst qc = make_qconst(c, MODE < 2 && t.is_unsigned != 0, t.bits);
-  const bool live = c > 0.0f;
+  const bool live = qc.live;
   const unsigned long long step = (MODE == 3) ? t.st->step : 0ull;
   const int l0 = bc.x * tl, b0 = bc.y * 16, a0 = bc.z * 16;
 
@@ -813,7 +818,7 @@ __device__ __forceinline__ void generic_body(const TileArgs& t, const TileCoord&
                       t.st, nullptr, bc.first, t.bits);
   }
   const QConst qc = make_qconst(c, MODE < 2 && t.is_unsigned != 0, t.bits);
-  const bool live = c > 0.0f;
+  const bool live = qc.live;
   const unsigned long long step = (MODE == 3) ? t.st->step : 0ull;
   const int l0 = bc.x * TL, b0 = bc.y * 16, a0 = bc.z * 16;
   uint32_t cnt = 0, seen_max = 0;
@@ -865,7 +870,7 @@ __device__ __forceinline__ void matrix_body(const TileArgs& t, const TileCoord& 
                       t.st, nullptr, bc.first, t.bits);
   }
   const QConst qc = make_qconst(c, MODE < 2 && t.is_unsigned != 0, t.bits);
-  const bool live = c > 0.0f;
+  const bool live = qc.live;
   const unsigned long long step = (MODE == 3) ? t.st->step : 0ull;
   uint32_t cnt = 0, seen_max = 0;
   for (unsigned tile_id = bc.id; tile_id < bc.tiles; tile_id += bc.n_blocks) {

@@ -56,6 +56,35 @@ def test_quantize_grad_degenerate():
     assert lbt.lbt_state_read(st).status == lbt.STATUS_OK
 
 
+def test_subnormal_scale_gradients():
+    # an interval too small to normalise by (fl32(q / c) overflows) is a degenerate interval on
+    # both sides: status ZERO_GRAD, codes 0, clip 0; just above that scale the codes are usual
+    r = synth.rng(0, 12, 0, synth.T_DY)
+    base = synth.dense_grad(r, (5000,))
+    for scale_to, gamma in ((2e-40, 1.0), (1e-38, 0.5), (3e-38, 1.0), (1e-37, 0.3)):
+        g = (base / np.abs(base).max() * np.float32(scale_to)).astype(np.float32)
+        for rounding in (0, 1):
+            _say("subnormal-scale gradient", scale_to, gamma, rounding)
+            ost = oracle.GradState(gamma=gamma)
+            want = oracle.quantize_grad(g, ost, seed=4, rounding=rounding)
+            st = lbt.new_state(gamma0=gamma)
+            packed = gu.quantize_grad(g, st, seed=4, rounding=rounding)
+            gu.assert_state_equal(lbt.lbt_state_read(st), ost)
+            assert np.array_equal(packed, oracle.pack_nibbles(want))
+    assert ost.status == oracle.OK and np.abs(want).max() == 7
+    # through a backward call: tiny gradient, tiny weights -> every output is exactly 0
+    X = synth.relu_normal(r, (2, 16, 6, 6))
+    W = (synth.kaiming_normal(r, (16, 16, 3, 3)) * np.float32(1e-39)).astype(np.float32)
+    dY = (synth.dense_grad(r, (2, 16, 6, 6)) * np.float32(1e-36)).astype(np.float32)
+    ost = oracle.GradState(gamma=1.0)
+    ref = oracle.backward_conv2d(X, W, dY, 1, 1, ost, x_unsigned=True, seed=1, rounding=1)
+    st = lbt.new_state(gamma0=1.0)
+    got = gu.backward_conv2d(X, W, dY, 1, 1, st, seed=1, rounding=1)
+    gu.assert_state_equal(lbt.lbt_state_read(st), ost)
+    assert np.array_equal(got.acc_dx, ref.acc_dx) and np.array_equal(got.acc_dw, ref.acc_dw)
+    assert not got.acc_dx.any() and not got.dX.any() and np.isfinite(got.dW).all()
+
+
 def test_quantize_is_deterministic():
     r = synth.rng(0, 11, 0, synth.T_DY)
     g = synth.grad_cfg4(r, (1 << 21,))
