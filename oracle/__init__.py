@@ -336,6 +336,59 @@ def conv2d_dw_at(qG, qX, w_shape, stride: int, pad: int, flat_idx):
     return acc
 
 
+# ----------------------------------------------------------------------------
+# Freivalds-style check of a WHOLE accumulator tensor handed in from elsewhere: the claimed
+# result is contracted with a random +-1 vector along one axis, and the same contraction is
+# pushed through the definition (the products are linear in each operand), which costs one
+# product with that axis collapsed to length 1.  Integer arithmetic in int64: equality is
+# exact.  A claimed tensor that is wrong at some position of the kept axes passes one
+# vector with probability <= 1/2.
+# ----------------------------------------------------------------------------
+def signs(rng: np.random.Generator, n: int) -> np.ndarray:
+    return (2 * rng.integers(0, 2, n, dtype=np.int64) - 1).astype(np.int64)
+
+
+def freivalds_conv2d_dx(acc_dx, qG, qW, stride: int, pad: int, r_c):
+    """sum_c r[c] acc_dX[n,c,h,w]  vs  dX of the one-channel filter  sum_c r[c] qW[k,c,r,s]
+    (dX is linear in W).  Returns the two [N,H,W] arrays; the caller asserts equality."""
+    acc = np.asarray(acc_dx)
+    N, Cc, H, W = acc.shape
+    r_c = np.asarray(r_c, dtype=np.int64)
+    assert r_c.shape == (Cc,)
+    got = np.tensordot(acc.astype(np.int64), r_c, axes=([1], [0]))
+    w1 = np.tensordot(np.asarray(qW, dtype=np.int64), r_c, axes=([1], [0]))[:, None, :, :]
+    want = conv2d_dx(qG, w1, (N, 1, H, W), stride, pad)[:, 0]
+    return got, want
+
+
+def freivalds_conv2d_dw(acc_dw, qG, qX, stride: int, pad: int, r_k):
+    """sum_k r[k] acc_dW[k,c,r,s]  vs  dW of the one-channel gradient  sum_k r[k] qG[n,k,p,q]
+    (dW is linear in dY).  Returns the two [C,R,S] arrays."""
+    acc = np.asarray(acc_dw)
+    K, Cc, R, S = acc.shape
+    r_k = np.asarray(r_k, dtype=np.int64)
+    assert r_k.shape == (K,)
+    got = np.tensordot(r_k, acc.astype(np.int64), axes=([0], [0]))
+    g1 = np.tensordot(np.asarray(qG, dtype=np.int64), r_k, axes=([1], [0]))[:, None, :, :]
+    want = conv2d_dw(g1, qX, (1, Cc, R, S), stride, pad)[0]
+    return got, want
+
+
+def freivalds_linear(acc_dx, acc_dw, qG, qX, qW, r_k, r_n):
+    """Linear layer: acc_dX[M,K] r_k  vs  qG (qW^T r_k);  acc_dW[K,N] r_n  vs  qX^T (qG r_n).
+    Returns ((got, want) for dX or None, (got, want) for dW or None)."""
+    qG, qW = np.asarray(qG, dtype=np.int64), np.asarray(qW, dtype=np.int64)
+    out_dx = out_dw = None
+    if acc_dx is not None:
+        r_k = np.asarray(r_k, dtype=np.int64)
+        out_dx = (np.asarray(acc_dx).astype(np.int64) @ r_k, qG @ (qW.T @ r_k))
+    if acc_dw is not None:
+        r_n = np.asarray(r_n, dtype=np.int64)
+        qX = np.asarray(qX, dtype=np.int64)
+        out_dw = (np.asarray(acc_dw).astype(np.int64) @ r_n, qX.T @ (qG @ r_n))
+    return out_dx, out_dw
+
+
 def dequant(acc, s_a: float, s_b: float) -> np.ndarray:
     acc = np.ascontiguousarray(acc, dtype=np.int64)
     out = np.empty(acc.shape, dtype=np.float32)

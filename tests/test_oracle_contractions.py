@@ -144,3 +144,54 @@ def test_zero_gradient_gives_zero_outputs():
     st = oracle.GradState(gamma=0.7)
     res = oracle.backward_linear(X, W, np.zeros((4, 5), np.float32), st)
     assert st.status == oracle.ZERO_GRAD and not res.dX.any() and not res.dW.any()
+
+
+# -- the whole-tensor check used at full size on the GPU's accumulators ------------------------
+def test_freivalds_accepts_the_definition_and_catches_a_single_wrong_sum():
+    rs = np.random.default_rng(17)
+    for (N, C, H, K, R, stride, pad) in ((2, 5, 9, 7, 3, 1, 1), (3, 4, 10, 6, 3, 2, 1),
+                                         (2, 6, 8, 5, 1, 2, 0), (1, 3, 12, 4, 5, 1, 2)):
+        P = (H + 2 * pad - R) // stride + 1
+        qG = rs.integers(-7, 8, (N, K, P, P)).astype(np.int32)
+        qW = rs.integers(-7, 8, (K, C, R, R)).astype(np.int32)
+        qX = rs.integers(0, 16, (N, C, H, H)).astype(np.int32)
+        acc_dx = oracle.conv2d_dx(qG, qW, (N, C, H, H), stride, pad)
+        acc_dw = oracle.conv2d_dw(qG, qX, (K, C, R, R), stride, pad)
+        caught_dx = caught_dw = 0
+        for trial in range(8):
+            r_c, r_k = oracle.signs(rs, C), oracle.signs(rs, K)
+            got, want = oracle.freivalds_conv2d_dx(acc_dx, qG, qW, stride, pad, r_c)
+            assert got.shape == (N, H, H) and np.array_equal(got, want)
+            got, want = oracle.freivalds_conv2d_dw(acc_dw, qG, qX, stride, pad, r_k)
+            assert got.shape == (C, R, R) and np.array_equal(got, want)
+            # one planted error anywhere in the claimed tensor is seen by every +-1 vector
+            bad = acc_dx.copy()
+            bad[tuple(rs.integers(0, d) for d in bad.shape)] += 1
+            got, want = oracle.freivalds_conv2d_dx(bad, qG, qW, stride, pad, r_c)
+            caught_dx += not np.array_equal(got, want)
+            bad = acc_dw.copy()
+            bad[tuple(rs.integers(0, d) for d in bad.shape)] -= 3
+            got, want = oracle.freivalds_conv2d_dw(bad, qG, qX, stride, pad, r_k)
+            caught_dw += not np.array_equal(got, want)
+        assert caught_dx == 8 and caught_dw == 8
+    # two errors in one (n, h, w) column of dX can cancel for half of the vectors, never for all
+    bad = acc_dx.copy()
+    bad[0, 0, 1, 1] += 5
+    bad[0, 1, 1, 1] += 5
+    seen = 0
+    for trial in range(32):
+        got, want = oracle.freivalds_conv2d_dx(bad, qG, qW, stride, pad, oracle.signs(rs, C))
+        seen += not np.array_equal(got, want)
+    assert 4 <= seen <= 28
+    # linear layer
+    M, Kin, Nout = 9, 7, 5
+    qG = rs.integers(-7, 8, (M, Nout)).astype(np.int32)
+    qW = rs.integers(-7, 8, (Kin, Nout)).astype(np.int32)
+    qX = rs.integers(-7, 8, (M, Kin)).astype(np.int32)
+    acc_dx, acc_dw = oracle.linear_dx(qG, qW), oracle.linear_dw(qX, qG)
+    (g1, w1), (g2, w2) = oracle.freivalds_linear(acc_dx, acc_dw, qG, qX, qW, oracle.signs(rs, Kin),
+                                                 oracle.signs(rs, Nout))
+    assert np.array_equal(g1, w1) and np.array_equal(g2, w2)
+    acc_dw[3, 2] += 1
+    _, (g2, w2) = oracle.freivalds_linear(None, acc_dw, qG, qX, qW, None, oracle.signs(rs, Nout))
+    assert not np.array_equal(g2, w2)
