@@ -97,6 +97,9 @@ def parse():
     ap.add_argument("--copy-probe", action="store_true",
                     help="only run three plain 256 MiB device copies (calibrates the HBM byte "
                          "counters of a rocprofv3 --pmc run) and exit")
+    ap.add_argument("--peaks", action="store_true",
+                    help="only run the stand-alone probe of the chip's ceilings (HBM read / write / "
+                         "copy, LDS reads, back-to-back int8 MFMA) and exit")
     return ap.parse_args()
 
 
@@ -418,6 +421,15 @@ def main():
         print("bench.py: this build runs on one GPU only (no collectives are part of it); "
               "use --gpus 1", file=sys.stderr)
         sys.exit(2)
+    if args.peaks:
+        # a child process of its own: this one has not touched the GPU yet
+        import subprocess
+        from paper_2407_12637_amd import build as lbt_build
+        if not os.path.exists(lbt_build.PEAKS):
+            print("bench.py: the peak probe is not built (python -c 'import __graft_entry__ as g; "
+                  "g.build()')", file=sys.stderr)
+            sys.exit(2)
+        sys.exit(subprocess.call([lbt_build.PEAKS]))
     import torch
 
     from paper_2407_12637_amd import binding as lbt

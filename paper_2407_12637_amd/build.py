@@ -8,6 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblbt.so")
+PEAKS = os.path.join(HERE, "lbt_peaks")        # stand-alone probe of the chip's ceilings
 SOURCES = ["lbt_api.hip", "lbt_quantize.hip", "lbt_gemm.hip", "lbt_profile.hip"]
 
 HIPCC_FLAGS = [
@@ -27,6 +28,8 @@ def stale() -> bool:
     if not os.path.exists(LIB):
         return True
     t = os.path.getmtime(LIB)
+    if not os.path.exists(PEAKS) or os.path.getmtime(PEAKS) < os.path.getmtime(os.path.join(CSRC, "lbt_peaks.hip")):
+        return True
     deps = sources() + [os.path.join(CSRC, "lbt_internal.h"), os.path.join(ROOT, "include", "lbt.h")]
     return any(os.path.getmtime(d) > t for d in deps)
 
@@ -41,7 +44,22 @@ def build(force: bool = True, verbose: bool = False) -> str:
         print(" ".join(cmd))
     subprocess.check_call(cmd)
     os.replace(tmp, LIB)
+    build_peaks(hipcc, verbose)
     return LIB
+
+
+def build_peaks(hipcc=None, verbose: bool = False) -> str:
+    """The peak probe `bench.py --peaks` runs (an executable beside the library)."""
+    hipcc = hipcc or os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    tmp = PEAKS + ".tmp.%d" % os.getpid()
+    cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-o", tmp, os.path.join(CSRC, "lbt_peaks.hip")]
+    if verbose:
+        print(" ".join(cmd))
+    subprocess.check_call(cmd)
+    os.replace(tmp, PEAKS)
+    return PEAKS
 
 
 if __name__ == "__main__":

@@ -156,7 +156,8 @@ int backward_common(const float* X, const float* W, const float* dY, ConvGeom g,
     w_crsk = kept_base + kept.off_w;
   }
 
-  uint32_t* pmax = reinterpret_cast<uint32_t*>(base + kWsScalarsBytes);
+  uint32_t* pmax = header_pmax(base);
+  unsigned long long* tickets = header_tickets(base);
   const int64_t n_dy = (int64_t)g.N * g.K * g.P * g.Q;
   const int64_t n_x = (int64_t)g.N * g.C * g.H * g.W;
   const int64_t n_w = (int64_t)g.K * g.C * g.R * g.S;
@@ -168,7 +169,7 @@ int backward_common(const float* X, const float* W, const float* dY, ConvGeom g,
   // 1. maxima of dY (unless the previous tensor's maximum is to be used), and of X / W where
   //    no clip value was given, in one launch
   if ((rc = launch_absmax3(hindsight ? nullptr : dY, n_dy, 1, want_cx ? X : nullptr, n_x, x_unsigned ? 0 : 1,
-                           want_cw ? W : nullptr, n_w, 1, pmax, &nblocks, st, s,
+                           want_cw ? W : nullptr, n_w, 1, pmax, tickets, &nblocks, st, s,
                            saved ? sc : nullptr, (dW ? 1 : 0) | (dX ? 2 : 0))))
     return rc;
   // 2. codes of all three tensors in the layouts the two products read, one launch:
@@ -182,14 +183,14 @@ int backward_common(const float* X, const float* W, const float* dY, ConvGeom g,
     q.bits = bits;
     q.x_unsigned = x_unsigned;
     q.tensor[0] = {dY, g.N, g.K, PQ,
-                   RelayoutIo{pmax, nblocks, 0, st, dX ? g_npqk : nullptr, dW ? g_kpqn : nullptr, 0},
+                   RelayoutIo{pmax, nblocks, 0, tickets, st, dX ? g_npqk : nullptr, dW ? g_kpqn : nullptr, 0},
                    0.0f, nullptr, nullptr};
     if (dW && !saved)
-      q.tensor[1] = {X, g.N, g.C, HW, RelayoutIo{pmax, nblocks, 1, st, nullptr, x_chwn, 0},
+      q.tensor[1] = {X, g.N, g.C, HW, RelayoutIo{pmax, nblocks, 1, tickets, st, nullptr, x_chwn, 0},
                      c_x, &sc->c_x, &sc->bad_x};
     if (dX && !saved)
       q.tensor[2] = {W, wA, wB, wL,
-                     RelayoutIo{pmax, nblocks, 2, st, w_is_ck ? w_crsk : nullptr,
+                     RelayoutIo{pmax, nblocks, 2, tickets, st, w_is_ck ? w_crsk : nullptr,
                                 w_is_ck ? nullptr : w_crsk, 1},
                      c_w, &sc->c_w, &sc->bad_w};
     if ((rc = launch_quantize_layer(q, s))) return rc;
@@ -281,7 +282,8 @@ int forward_common(const float* X, const float* W, ConvGeom g, bool is_linear, f
   // reads the clip values there), else in the workspace
   uint8_t* head = saved ? static_cast<uint8_t*>(saved) : static_cast<uint8_t*>(ws);
   OperandScalars* sc = reinterpret_cast<OperandScalars*>(head);
-  uint32_t* pmax = reinterpret_cast<uint32_t*>(head + kWsScalarsBytes);
+  uint32_t* pmax = header_pmax(head);
+  unsigned long long* tickets = header_tickets(head);
   uint8_t* x_codes = product ? static_cast<uint8_t*>(ws) + lay.off_x : nullptr;
   uint8_t* w_codes = product ? static_cast<uint8_t*>(ws) + lay.off_w : nullptr;
   uint8_t* x_kept = saved ? static_cast<uint8_t*>(saved) + kept.off_x : nullptr;   // [C][Np/16][HW][16]
@@ -290,21 +292,21 @@ int forward_common(const float* X, const float* W, ConvGeom g, bool is_linear, f
   const int64_t n_x = (int64_t)g.N * g.C * HW, n_w = (int64_t)g.K * g.C * RS;
   int rc, nblocks = 0;
   if ((rc = launch_absmax3(nullptr, 0, 0, !(c_x > 0.0f) ? X : nullptr, n_x, x_unsigned ? 0 : 1,
-                           !(c_w > 0.0f) ? W : nullptr, n_w, 1, pmax, &nblocks, nullptr, s)))
+                           !(c_w > 0.0f) ? W : nullptr, n_w, 1, pmax, tickets, &nblocks, nullptr, s)))
     return rc;
   LayerTensors q{};
   q.rounding = LBT_ROUND_NEAREST;
   q.x_unsigned = x_unsigned;
   q.bits = bits;
-  q.tensor[1] = {X, g.N, g.C, HW, RelayoutIo{pmax, nblocks, 1, nullptr, x_codes, x_kept, 0, 0},
+  q.tensor[1] = {X, g.N, g.C, HW, RelayoutIo{pmax, nblocks, 1, tickets, nullptr, x_codes, x_kept, 0, 0},
                  c_x, &sc->c_x, &sc->bad_x};
   if (is_linear)   // W[K_in][N_out]: rows of W^T, sixteen consecutive k_in per granule;
                    // kept for dX as rows of W, sixteen consecutive n_out per granule
-    q.tensor[2] = {W, g.C, g.K, 1, RelayoutIo{pmax, nblocks, 2, nullptr, w_kept, w_codes, 0, 0},
+    q.tensor[2] = {W, g.C, g.K, 1, RelayoutIo{pmax, nblocks, 2, tickets, nullptr, w_kept, w_codes, 0, 0},
                    c_w, &sc->c_w, &sc->bad_w};
   else             // W[K][C][R*S]: tap-major rows, sixteen consecutive c per granule;
                    // kept for dX tap-major with sixteen consecutive k per granule
-    q.tensor[2] = {W, g.K, g.C, RS, RelayoutIo{pmax, nblocks, 2, nullptr, w_codes, w_kept, 1, 1},
+    q.tensor[2] = {W, g.K, g.C, RS, RelayoutIo{pmax, nblocks, 2, tickets, nullptr, w_codes, w_kept, 1, 1},
                    c_w, &sc->c_w, &sc->bad_w};
   if ((rc = launch_quantize_layer(q, s))) return rc;
   if (!product) return LBT_OK;
@@ -391,13 +393,13 @@ int lbt_quantize_grad(const float* g, int64_t n, lbt_grad_state* st, uint64_t se
     return LBT_ERR_ALIGN;
   if (ws_bytes < lbt_workspace_bytes_quantize(n)) return LBT_ERR_WORKSPACE;
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-  uint32_t* pmax =
-      reinterpret_cast<uint32_t*>(static_cast<uint8_t*>(ws) + kWsScalarsBytes);
+  uint32_t* pmax = header_pmax(ws);
+  unsigned long long* tickets = header_tickets(ws);
   int rc, nblocks = 0;
-  if ((rc = launch_absmax3(hindsight ? nullptr : g, n, 1, nullptr, 0, 0, nullptr, 0, 0, pmax,
+  if ((rc = launch_absmax3(hindsight ? nullptr : g, n, 1, nullptr, 0, 0, nullptr, 0, 0, pmax, tickets,
                            &nblocks, st, s)))
     return rc;
-  return launch_quantize_flat_grad(g, n, pmax, nblocks, st, seed, rounding, hindsight, fused_update,
+  return launch_quantize_flat_grad(g, n, pmax, nblocks, tickets, st, seed, rounding, hindsight, fused_update,
                                    bits, codes, s);
 }
 
@@ -425,12 +427,11 @@ int lbt_quantize_operand(const float* x, int64_t n, float c, int is_unsigned, in
   if (ws_bytes < lbt_workspace_bytes_quantize(n)) return LBT_ERR_WORKSPACE;
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   OperandScalars* sc = static_cast<OperandScalars*>(ws);
-  uint32_t* pmax =
-      reinterpret_cast<uint32_t*>(static_cast<uint8_t*>(ws) + kWsScalarsBytes);
+  uint32_t* pmax = header_pmax(ws);
   int rc, nblocks = 0;
   if (!(c > 0.0f))
-    if ((rc = launch_absmax3(nullptr, 0, 0, x, n, is_unsigned ? 0 : 1, nullptr, 0, 0, pmax, &nblocks,
-                             nullptr, s)))
+    if ((rc = launch_absmax3(nullptr, 0, 0, x, n, is_unsigned ? 0 : 1, nullptr, 0, 0, pmax,
+                             header_tickets(ws), &nblocks, nullptr, s)))
       return rc;
   return launch_quantize_flat_operand(x, n, c, pmax, nblocks, is_unsigned, bits, codes, &sc->c_x,
                                       clip_scale_out, s);

@@ -612,7 +612,6 @@ int run_gemm(GemmArgs& g, int mode, int bm, int bn, int splits, int kid, hipStre
   }
 #undef LBT_GEMM_CASE
   if (rc) return rc;
-  LBT_LAUNCH_CHECK();
   return LBT_OK;
 }
 
@@ -688,7 +687,6 @@ int run_splitk(GemmArgs& g, bool x_unsigned, long long true_k, int32_t* acc, int
   else if (wide) LBT_REDUCE_CASE(1, true);
   else LBT_REDUCE_CASE(1, false);
 #undef LBT_REDUCE_CASE
-  LBT_LAUNCH_CHECK();
   return LBT_OK;
 }
 

@@ -3,6 +3,10 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <tuple>
+#include <type_traits>
+#include <utility>
+
 #include "lbt.h"
 
 #define LBT_HIP_CHECK(expr)                       \
@@ -11,10 +15,6 @@
     if (lbt_e_ != hipSuccess) return LBT_ERR_HIP; \
   } while (0)
 
-#define LBT_LAUNCH_CHECK()                              \
-  do {                                                  \
-    if (hipGetLastError() != hipSuccess) return LBT_ERR_HIP; \
-  } while (0)
 
 namespace lbt {
 
@@ -140,9 +140,28 @@ class ProfScope {
   hipStream_t s_;
 };
 
-// Every kernel of the library is launched through this macro.
-#define LBT_LAUNCH(kernel, grid, block, shmem, stream, ...) \
-  hipLaunchKernelGGL(kernel, grid, block, shmem, stream, __VA_ARGS__)
+// Every kernel of the library is launched through launch_kernel, which hands back the error
+// of THIS launch (the runtime's "last error" may stem from an earlier call of the caller's).
+template <typename... KArgs, size_t... I>
+inline hipError_t launch_tuple(void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t shmem,
+                               hipStream_t s, std::tuple<std::decay_t<KArgs>...>& vals,
+                               std::index_sequence<I...>) {
+  void* ptrs[] = {static_cast<void*>(&std::get<I>(vals))...};
+  return hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, ptrs, shmem, s);
+}
+template <typename... KArgs, typename... Args>
+inline hipError_t launch_kernel(void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t shmem,
+                                hipStream_t s, Args&&... args) {
+  static_assert(sizeof...(KArgs) == sizeof...(Args), "kernel argument count");
+  std::tuple<std::decay_t<KArgs>...> vals(std::forward<Args>(args)...);
+  return launch_tuple(kernel, grid, block, shmem, s, vals, std::index_sequence_for<KArgs...>{});
+}
+// Launch, and leave the enclosing function with LBT_ERR_HIP if the launch was refused.
+#define LBT_LAUNCH(kernel, grid, block, shmem, stream, ...)                                       \
+  do {                                                                                            \
+    if (lbt::launch_kernel(kernel, grid, block, shmem, stream, __VA_ARGS__) != hipSuccess)        \
+      return LBT_ERR_HIP;                                                                         \
+  } while (0)
 
 // ---- quantize.hip -------------------------------------------------------------
 constexpr int kMaxPartialBlocks = 2048;  // partial-maximum slots in the workspace header
@@ -155,16 +174,24 @@ constexpr size_t kWsTicketOffset = 64;
 constexpr int kTicketSlots = 16;
 constexpr size_t kWsHeaderBytes = kWsScalarsBytes + (size_t)kMaxPartialBlocks * 16;
 
+// Views of a workspace header.
+inline uint32_t* header_pmax(void* header) {
+  return reinterpret_cast<uint32_t*>(static_cast<uint8_t*>(header) + kWsScalarsBytes);
+}
+inline unsigned long long* header_tickets(void* header) {
+  return reinterpret_cast<unsigned long long*>(static_cast<uint8_t*>(header) + kWsTicketOffset);
+}
+
 // One launch for the maxima of up to three tensors (null pointer = absent); partial
-// maxima go to pmax[block][tensor].  *nblocks_out = number of partial rows written.
+// maxima go to pmax[block][tensor]; tickets: the header's counters, zeroed by this launch.  *nblocks_out = number of partial rows written.
 // st (may be null): its status is reset to OK for the quantizer launches that follow; with a
 // state the kernel is launched even when every tensor is absent.
 int launch_absmax3(const float* p0, int64_t n0, int abs0, const float* p1, int64_t n1, int abs1,
-                   const float* p2, int64_t n2, int abs2, uint32_t* pmax, int* nblocks_out,
-                   lbt_grad_state* st, hipStream_t s, const OperandScalars* kept = nullptr,
-                   int kept_mask = 0);
+                   const float* p2, int64_t n2, int abs2, uint32_t* pmax,
+                   unsigned long long* tickets, int* nblocks_out, lbt_grad_state* st, hipStream_t s,
+                   const OperandScalars* kept = nullptr, int kept_mask = 0);
 int launch_quantize_flat_grad(const float* g, int64_t n, const uint32_t* pmax, int nblocks,
-                              lbt_grad_state* st, uint64_t seed, int rounding, int hindsight,
+                              unsigned long long* tickets, lbt_grad_state* st, uint64_t seed, int rounding, int hindsight,
                               int fused_update, int bits, uint8_t* codes, hipStream_t s);
 int launch_quantize_flat_operand(const float* x, int64_t n, float c_given, const uint32_t* pmax,
                                  int nblocks, int is_unsigned, int bits, uint8_t* codes,
@@ -176,6 +203,7 @@ struct RelayoutIo {
   const uint32_t* pmax;
   int nblocks;
   int pmax_col;
+  unsigned long long* tickets;  // the header's arrival counters (used by the gradient tensor)
   lbt_grad_state* st;
   uint8_t* out_b;
   uint8_t* out_a;

@@ -5,6 +5,7 @@
 // packets add a fixed few microseconds to every bracket; callers calibrate that with
 // the empty kernel class (k_state_set) measured in the same way.  Disabled by default:
 // the hot path then pays one predictable branch per launch.
+#include <atomic>
 #include <mutex>
 #include <vector>
 
@@ -20,7 +21,7 @@ struct Record {
 };
 
 std::mutex g_mu;
-bool g_enabled = false;
+std::atomic<bool> g_enabled{false};   // read by every launch without the lock
 std::vector<Record> g_records;
 std::vector<hipEvent_t> g_pool;
 
@@ -45,7 +46,7 @@ hipEvent_t take_event() {
 }  // namespace
 
 ProfScope::ProfScope(int kid, double work, hipStream_t s) : idx_(-1), s_(s) {
-  if (!g_enabled) return;
+  if (!g_enabled.load(std::memory_order_acquire)) return;
   std::lock_guard<std::mutex> lk(g_mu);
   Record r{kid, work, take_event(), take_event()};
   if (!r.start || !r.stop) return;
@@ -74,7 +75,7 @@ int lbt_profile_enable(int on) {
     g_pool.push_back(r.stop);
   }
   g_records.clear();
-  g_enabled = on != 0;
+  g_enabled.store(on != 0, std::memory_order_release);
   return LBT_OK;
 }
 
