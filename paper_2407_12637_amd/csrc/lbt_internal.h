@@ -84,8 +84,10 @@ __device__ __forceinline__ QConst make_qconst(float c, bool is_unsigned, int bit
   return k;
 }
 
+// x_n of Eq. (1): clip to [lo, c] (the median of the three: one instruction), then one fp32
+// multiply by q / c.
 __device__ __forceinline__ float normalised(float v, const QConst& k) {
-  const float xc = fminf(fmaxf(v, k.lo), k.c);
+  const float xc = __builtin_amdgcn_fmed3f(v, k.lo, k.c);
   return __fmul_rn(xc, k.inv_s);
 }
 

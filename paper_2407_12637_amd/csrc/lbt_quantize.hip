@@ -40,14 +40,16 @@ __device__ __forceinline__ Philox4 philox4x32_10(uint32_t c0, uint32_t c1, uint3
                                                  uint32_t c3, uint32_t k0, uint32_t k1) {
   constexpr uint32_t kMulA = 0xD2511F53u, kMulB = 0xCD9E8D57u;
   constexpr uint32_t kWeylA = 0x9E3779B9u, kWeylB = 0xBB67AE85u;
+  // each round needs both halves of two 32 x 32 -> 64 bit products: one multiply
+  // instruction apiece when written as a 64-bit product
 #pragma unroll
   for (int r = 0; r < 10; ++r) {
-    const uint32_t a_hi = __umulhi(kMulA, c0), a_lo = kMulA * c0;
-    const uint32_t b_hi = __umulhi(kMulB, c2), b_lo = kMulB * c2;
-    c0 = b_hi ^ c1 ^ k0;
-    c1 = b_lo;
-    c2 = a_hi ^ c3 ^ k1;
-    c3 = a_lo;
+    const unsigned long long pa = (unsigned long long)kMulA * c0;
+    const unsigned long long pb = (unsigned long long)kMulB * c2;
+    c0 = (uint32_t)(pb >> 32) ^ c1 ^ k0;
+    c1 = (uint32_t)pb;
+    c2 = (uint32_t)(pa >> 32) ^ c3 ^ k1;
+    c3 = (uint32_t)pa;
     k0 += kWeylA;
     k1 += kWeylB;
   }
@@ -66,16 +68,29 @@ __device__ __forceinline__ uint32_t r16_of(const Philox4& p, uint32_t lane) {
   return (p.w[lane >> 1] >> ((lane & 1u) * 16u)) & 0xFFFFu;
 }
 
+// floor(x) as an integer in one instruction (the conversion that rounds towards minus infinity)
+__device__ __forceinline__ int floor_to_int(float x) {
+  int r;
+  asm("v_cvt_flr_i32_f32_e32 %0, %1" : "=v"(r) : "v"(x));
+  return r;
+}
+
+__device__ __forceinline__ int clamp_code(int r, const QConst& k) {
+  int m;
+  asm("v_med3_i32 %0, %1, %2, %3" : "=v"(m) : "v"(r), "v"(k.kmin), "v"(k.q));
+  return m;
+}
+
+// |x_n| <= q (1 + 2^-23) < q + 1/2, so the nearest integer is already inside [-q, q]
 __device__ __forceinline__ int code_nearest(float v, const QConst& k) {
-  const int r = (int)rintf(normalised(v, k));
-  return min(max(r, k.kmin), k.q);
+  return (int)rintf(normalised(v, k));
 }
 
 __device__ __forceinline__ int code_stochastic(float v, const QConst& k, uint32_t r16) {
-  // x_n in units of 2^-16 (exact scaling), truncated downwards, plus 16 random bits
-  const int fixed = (int)floorf(__fmul_rn(normalised(v, k), 65536.0f)) + (int)r16;
-  const int r = fixed >> 16;  // arithmetic shift: floor division
-  return min(max(r, k.kmin), k.q);
+  // x_n in units of 2^-16 (exact scaling), truncated downwards, plus 16 random bits;
+  // x_n may exceed q by an ulp and floor(-q - ulp) is -q - 1: the code is clamped
+  const int fixed = floor_to_int(__fmul_rn(normalised(v, k), 65536.0f)) + (int)r16;
+  return clamp_code(fixed >> 16, k);  // arithmetic shift: floor division
 }
 
 // MODE 0: signed nearest, 1: unsigned nearest, 2: signed nearest + count,
@@ -88,6 +103,35 @@ __device__ __forceinline__ int quantize_one(float v, const QConst& qc, const Phi
   else k = code_nearest(v, qc);
   if (MODE >= 2) cnt += (fabsf(v) > qc.c) ? 1u : 0u;
   return k;
+}
+
+// Eight consecutive elements (one generator block) -> two words of four code bytes each.
+// ok0 / ok1: whether the first / second four elements belong to the tile (a half that does
+// not gives a zero word and is not counted; its values are whatever a harmless load of valid
+// memory returned).  The clip-out count is taken per WAVE: each compare's lane mask is counted
+// by the scalar unit, so cnt_wave holds the same running total in every lane.
+template <int MODE>
+__device__ __forceinline__ void quantize8(const float v[8], bool ok0, bool ok1, const QConst& qc,
+                                          const Philox4& rnd, uint32_t& w0, uint32_t& w1,
+                                          uint32_t& cnt_wave) {
+  w0 = 0;
+  w1 = 0;
+#pragma unroll
+  for (int u = 0; u < 8; ++u) {
+    int k;
+    if (MODE == 3) k = code_stochastic(v[u], qc, r16_of(rnd, u));
+    else k = code_nearest(v[u], qc);
+    const uint32_t byte = ((uint32_t)k & 0xFFu) << (8 * (u & 3));
+    if (u < 4) w0 |= byte; else w1 |= byte;
+  }
+  w0 = ok0 ? w0 : 0u;
+  w1 = ok1 ? w1 : 0u;
+  if (MODE >= 2) {
+    const unsigned long long m0 = __ballot(ok0), m1 = __ballot(ok1);
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      cnt_wave += (uint32_t)__popcll(__ballot(fabsf(v[u]) > qc.c) & (u < 4 ? m0 : m1));
+  }
 }
 
 __device__ __forceinline__ uint32_t wave_sum(uint32_t v) {
@@ -462,7 +506,7 @@ __global__ __launch_bounds__(kThreads) void k_quantize_flat(
   const unsigned long long step = (MODE == 3) ? st->step : 0ull;
   const long long groups = (n + 7) / 8;
   const long long stride = (long long)gridDim.x * kThreads;
-  uint32_t cnt = 0, seen_max = 0;
+  uint32_t cnt_wave = 0, seen_max = 0;
   for (long long gi = (long long)blockIdx.x * kThreads + threadIdx.x; gi < groups; gi += stride) {
     const long long e0 = gi * 8;
     const int valid = (int)min(8ll, n - e0);
@@ -477,20 +521,17 @@ __global__ __launch_bounds__(kThreads) void k_quantize_flat(
       for (int j = 0; j < 8; ++j) v[j] = (j < valid) ? x[e0 + j] : 0.0f;
     }
     if (kGrad && gs.hindsight) seen_max = max(seen_max, max_abs_bits8(v));
-    uint32_t word = 0, lo = 0, hi = 0;   // nibble format; byte format (elements 0-3, 4-7)
+    // byte format: elements 0-3 in lo, 4-7 in hi; nibble format: the low nibbles of those
+    // bytes.  Elements past the end were loaded as 0.0: code 0, never counted.
+    uint32_t word = 0, lo = 0, hi = 0;
     if (live) {
       Philox4 rnd{};
       if (MODE == 3) rnd = philox_block((unsigned long long)gi, step, seed);
-#pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        uint32_t c1 = 0;
-        int k = quantize_one<MODE>(v[j], qc, rnd, j, c1);
-        if (j >= valid) { k = 0; c1 = 0; }
-        cnt += c1;
-        word |= ((uint32_t)k & 0xFu) << (4 * j);
-        if (j < 4) lo |= ((uint32_t)k & 0xFFu) << (8 * j);
-        else hi |= ((uint32_t)k & 0xFFu) << (8 * (j - 4));
-      }
+      quantize8<MODE>(v, true, true, qc, rnd, lo, hi, cnt_wave);
+      // gather the low nibble of each byte: 0x0d0c0b0a -> 0xdcba
+      const uint32_t l4 = lo & 0x0F0F0F0Fu, h4 = hi & 0x0F0F0F0Fu;
+      const uint32_t l2 = (l4 | (l4 >> 4)) & 0x00FF00FFu, h2 = (h4 | (h4 >> 4)) & 0x00FF00FFu;
+      word = ((l2 | (l2 >> 8)) & 0xFFFFu) | (((h2 | (h2 >> 8)) & 0xFFFFu) << 16);
     }
     if (bytes) {
       if (valid == 8) {
@@ -506,8 +547,8 @@ __global__ __launch_bounds__(kThreads) void k_quantize_flat(
       for (int j = 0; j < nbytes; ++j) codes[gi * 4 + j] = (uint8_t)(word >> (8 * j));
     }
   }
-  if (kGrad) grad_finish(st, gs, cnt, (unsigned long long)n, gridDim.x, blockIdx.x, tickets,
-                         seen_max);
+  if (kGrad) grad_finish(st, gs, (threadIdx.x & 63) == 0 ? cnt_wave : 0u, (unsigned long long)n, gridDim.x,
+                         blockIdx.x, tickets, seen_max);
 }
 
 // ---------------------------------------------------------------------------
@@ -738,7 +779,7 @@ __device__ __forceinline__ void stream_body(const TileArgs& t, int pitch, int tl
   const unsigned long long step = (MODE == 3) ? t.st->step : 0ull;
   const int l0 = bc.x * tl, b0 = bc.y * 16, a0 = bc.z * 16;
 
-  uint32_t cnt = 0, seen_max = 0;
+  uint32_t cnt = 0, cnt_wave = 0, seen_max = 0;
   auto quantize_item = [&](const ItemPos& p, const float v[8]) __attribute__((always_inline)) {
     // eight codes of one generator block -> LDS bytes
     Philox4 rnd{};
@@ -756,18 +797,7 @@ __device__ __forceinline__ void stream_body(const TileArgs& t, int pitch, int tl
       }
     } else {
       uint32_t w0 = 0, w1 = 0;
-      if (live) {
-        if (p.v0) {
-#pragma unroll
-          for (int u = 0; u < 4; ++u)
-            w0 |= ((uint32_t)quantize_one<MODE>(v[u], qc, rnd, u, cnt) & 0xFFu) << (8 * u);
-        }
-        if (p.v1) {
-#pragma unroll
-          for (int u = 0; u < 4; ++u)
-            w1 |= ((uint32_t)quantize_one<MODE>(v[4 + u], qc, rnd, 4 + u, cnt) & 0xFFu) << (8 * u);
-        }
-      }
+      if (live) quantize8<MODE>(v, p.v0, p.v1, qc, rnd, w0, w1, cnt_wave);
       uint8_t* dst = dyn_tile + p.row * pitch + p.off;
       if (p.v0 || p.z0) *reinterpret_cast<uint32_t*>(dst) = w0;
       if (p.v1 || p.z1) *reinterpret_cast<uint32_t*>(dst + 4) = w1;
@@ -796,8 +826,8 @@ __device__ __forceinline__ void stream_body(const TileArgs& t, int pitch, int tl
   __syncthreads();
   if (SMALL) store_granules(t, dyn_tile, pitch, t.L, a0, b0, 0);
   else store_granules_w4(t, dyn_tile, pitch, min(tl, t.L - l0), a0, b0, l0);
-  if (kGrad) grad_finish(t.st, gs, cnt, (unsigned long long)t.A * t.B * t.L, bc.n_blocks, bc.id,
-                         t.tickets, seen_max);
+  if (kGrad) grad_finish(t.st, gs, cnt + ((threadIdx.x & 63) == 0 ? cnt_wave : 0u),
+                         (unsigned long long)t.A * t.B * t.L, bc.n_blocks, bc.id, t.tickets, seen_max);
 }
 
 // ---------------------------------------------------------------------------
@@ -873,7 +903,7 @@ __device__ __forceinline__ void matrix_body(const TileArgs& t, const TileCoord& 
   const QConst qc = make_qconst(c, MODE < 2 && t.is_unsigned != 0, t.bits);
   const bool live = qc.live;
   const unsigned long long step = (MODE == 3) ? t.st->step : 0ull;
-  uint32_t cnt = 0, seen_max = 0;
+  uint32_t cnt_wave = 0, seen_max = 0;
   for (unsigned tile_id = bc.id; tile_id < bc.tiles; tile_id += bc.n_blocks) {
   const int b0 = (int)(tile_id % bc.gx) * 64, a0 = (int)(tile_id / bc.gx) * 64;
   float v[2][8];
@@ -899,13 +929,7 @@ __device__ __forceinline__ void matrix_body(const TileArgs& t, const TileCoord& 
     Philox4 rnd{};
     if (MODE == 3 && live && ok[i]) rnd = philox_block((unsigned long long)e0[i] >> 3, step, t.seed);
     uint32_t w0 = 0, w1 = 0;
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      int k = 0;
-      if (live && ok[i]) k = quantize_one<MODE>(v[i][u], qc, rnd, u, cnt);
-      const uint32_t byte = (uint32_t)k & 0xFFu;
-      if (u < 4) w0 |= byte << (8 * u); else w1 |= byte << (8 * (u - 4));
-    }
+    if (live) quantize8<MODE>(v[i], ok[i], ok[i], qc, rnd, w0, w1, cnt_wave);
     *reinterpret_cast<uint2*>(tile + row * PITCH + col) = make_uint2(w0, w1);
   }
   __syncthreads();
@@ -922,8 +946,8 @@ __device__ __forceinline__ void matrix_body(const TileArgs& t, const TileCoord& 
   }
   __syncthreads();   // the tile is free for the workgroup's next one
   }
-  if (MODE >= 2) grad_finish(t.st, gs, cnt, (unsigned long long)t.A * t.B * t.L, bc.n_blocks, bc.id,
-                             t.tickets, seen_max);
+  if (MODE >= 2) grad_finish(t.st, gs, (threadIdx.x & 63) == 0 ? cnt_wave : 0u,
+                             (unsigned long long)t.A * t.B * t.L, bc.n_blocks, bc.id, t.tickets, seen_max);
 }
 
 // ---------------------------------------------------------------------------
