@@ -205,10 +205,15 @@ int backward_common(const float* X, const float* W, const float* dY, ConvGeom g,
                 "both passes' partial sums must fit the header");
   double* const ste_w = reinterpret_cast<double*>(pmax);
   double* const ste_x = ste_w + kStePartials;
+  // dW's split-K sum is carried out by extra workgroups of the dX launch (one launch and one
+  // launch gap less per layer), unless the masked dW is needed before dX (learned clips) or
+  // no dX follows
+  PendingReduce pending{};
   if (dW) {
     lbt_grad_state* const u = dX ? nullptr : upd;
-    rc = w_is_ck ? launch_linear_dw(g, g_kpqn, x_chwn, st, sc, x_unsigned, dW, acc_dW, partial, u, s)
-                 : launch_conv_dw(g, g_kpqn, x_chwn, st, sc, x_unsigned, dW, acc_dW, partial, u, s);
+    PendingReduce* const defer = (dX && !grad_c) ? &pending : nullptr;
+    rc = w_is_ck ? launch_linear_dw(g, g_kpqn, x_chwn, st, sc, x_unsigned, dW, acc_dW, partial, u, defer, s)
+                 : launch_conv_dw(g, g_kpqn, x_chwn, st, sc, x_unsigned, dW, acc_dW, partial, u, defer, s);
     if (rc) return rc;
     // dW is dL/dQ(W) and has W's layout: its mask and dL/dc_w (the partial-maxima area of the
     // header is free again once the quantizers have run: scratch of the pass's partial sums)
@@ -216,8 +221,9 @@ int backward_common(const float* X, const float* W, const float* dY, ConvGeom g,
       return rc;
   }
   if (dX) {
-    rc = w_is_ck ? launch_linear_dx(g, w_crsk, g_npqk, st, sc, dX, acc_dX, upd, s)
-                 : launch_conv_dx(g, w_crsk, g_npqk, st, sc, dX, acc_dX, upd, s);
+    const PendingReduce* const carry = pending.blocks ? &pending : nullptr;
+    rc = w_is_ck ? launch_linear_dx(g, w_crsk, g_npqk, st, sc, dX, acc_dX, upd, carry, s)
+                 : launch_conv_dx(g, w_crsk, g_npqk, st, sc, dX, acc_dX, upd, carry, s);
     if (rc) return rc;
     // dX is dL/dQ(X) and has X's layout.  (The mask applied in the product's epilogue instead
     // was measured: the product then takes 1.5 ms more per ResNet-50 step, this pass 1.3 ms.)

@@ -43,6 +43,7 @@
 #include <type_traits>
 
 namespace lbt {
+int launch_pending_reduce(const PendingReduce& r, lbt_grad_state* update_st, hipStream_t s);
 namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
@@ -84,6 +85,11 @@ struct GemmArgs {
   float* out;
   int32_t* acc;       // optional raw accumulators (direct epilogues only)
   int32_t* partial;   // [splits][M][NJ] for epi 1
+  // A split contraction left pending by the launch before this one (dW's int32 partial tiles):
+  // workgroups gemm_grid .. gemm_grid + red.blocks - 1 of this launch add its slices and apply
+  // its scale, beside the workgroups of this launch's own product.
+  PendingReduce red;
+  unsigned gemm_grid; // workgroups of the product itself (a multiple of the die count)
 };
 
 // 16 bytes per lane from a buffer straight into LDS: lane l of the wave writes LDS byte
@@ -102,16 +108,68 @@ __device__ __forceinline__ void wait_loads() {
   asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
 }
 
-__device__ __forceinline__ float output_scale(const GemmArgs& g) {
-  const double q_signed = (double)levels(g.bits, false);
-  if (g.scale_kind >= 3)
-    return (float)(((double)g.sc->c_x / (g.scale_kind == 4 ? (double)levels(g.bits, true) : q_signed)) *
-                   ((double)g.sc->c_w / q_signed));
-  const double s_g = (double)g.st->clip / q_signed;
+__device__ __forceinline__ float output_scale(int scale_kind, int bits, const lbt_grad_state* st,
+                                              const OperandScalars* sc) {
+  const double q_signed = (double)levels(bits, false);
+  if (scale_kind >= 3)
+    return (float)(((double)sc->c_x / (scale_kind == 4 ? (double)levels(bits, true) : q_signed)) *
+                   ((double)sc->c_w / q_signed));
+  const double s_g = (double)st->clip / q_signed;
   double other;
-  if (g.scale_kind == 0) other = (double)g.sc->c_w / q_signed;
-  else other = (double)g.sc->c_x / (g.scale_kind == 2 ? (double)levels(g.bits, true) : q_signed);
+  if (scale_kind == 0) other = (double)sc->c_w / q_signed;
+  else other = (double)sc->c_x / (scale_kind == 2 ? (double)levels(bits, true) : q_signed);
   return (float)(s_g * other);
+}
+__device__ __forceinline__ float output_scale(const GemmArgs& g) {
+  return output_scale(g.scale_kind, g.bits, g.st, g.sc);
+}
+
+// Sum the split-K partial tiles and apply the scale: out = (sum_s partial[s]) * s_a * s_b.
+// A workgroup takes 256 / SL consecutive outputs at a time; SL groups of threads share the
+// slices (group w sums slices w, w + SL, ..., eight loads in flight per thread) and meet in
+// LDS.  SL = 4 for many slices of a small output, SL = 1 for few slices of a large one.
+// Integer adds: the result does not depend on how the slices are grouped.
+// WIDE: the slices are added in 64 bits (their sum may exceed 32 bits; each slice fits).
+// Workgroup `blk` of `nblk`.
+template <int SL, bool WIDE>
+__device__ __forceinline__ void reduce_slices(const PendingReduce& r, unsigned blk, unsigned nblk) {
+  constexpr int OUTS = kThreads / SL;
+  using sum_t = typename std::conditional<WIDE, long long, int>::type;
+  __shared__ sum_t red[SL][OUTS];
+  const float scale = output_scale(r.scale_kind, r.bits, r.st, r.sc);
+  const int32_t* __restrict__ partial = r.partial;
+  const long long n = r.n;
+  const int splits = r.splits;
+  const int io = threadIdx.x % OUTS, sl = threadIdx.x / OUTS;
+  for (long long base = (long long)blk * OUTS; base < n; base += (long long)nblk * OUTS) {
+    const long long i = base + io;
+    sum_t sum = 0;
+    if (i < n) {
+      for (int s0 = sl; s0 < splits; s0 += 8 * SL) {
+        int v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int sp = s0 + SL * u;
+          v[u] = sp < splits ? partial[(long long)sp * n + i] : 0;
+        }
+        sum += (((sum_t)v[0] + v[1]) + ((sum_t)v[2] + v[3])) + (((sum_t)v[4] + v[5]) + ((sum_t)v[6] + v[7]));
+      }
+    }
+    if (SL > 1) {
+      red[sl][io] = sum;
+      __syncthreads();
+      if (sl == 0) {
+        sum = 0;
+#pragma unroll
+        for (int w = 0; w < SL; ++w) sum += red[w][io];
+      }
+    }
+    if (sl == 0 && i < n) {
+      r.out[i] = (float)sum * scale;
+      if (r.acc) r.acc[i] = (int)sum;   // the host has checked that it fits
+    }
+    if (SL > 1) __syncthreads();
+  }
 }
 
 // MODE 0: B rows are input pixels (dX of a convolution)
@@ -132,13 +190,22 @@ __global__ __launch_bounds__(kThreads) void k_implicit_gemm(const GemmArgs g) {
   int* const s_tap = reinterpret_cast<int*>(lds + STAGES * STAGE);  // [BN][R*S]
   const unsigned lds_base = (unsigned)(uintptr_t)(lds_ptr_t)lds;    // LDS byte address of lds[0]
 
+  // the workgroups behind the product's own carry out a pending split-K sum (measured: placed
+  // in front of them instead, they delay the product more than they gain: 5.36 against
+  // 5.31 ms per ResNet-50 step)
+  if (blockIdx.x >= g.gemm_grid) {
+    if (g.red.many) reduce_slices<4, false>(g.red, blockIdx.x - g.gemm_grid, g.red.blocks);
+    else reduce_slices<1, false>(g.red, blockIdx.x - g.gemm_grid, g.red.blocks);
+    return;
+  }
   // workgroup id -> tile, so that the workgroups sharing a B tile run on one die
-  const int per_xcd = gridDim.x / kXcds;
-  const int lid = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
+  const unsigned bid = blockIdx.x;
+  const int per_xcd = g.gemm_grid / kXcds;
+  const int lid = (bid % kXcds) * per_xcd + bid / kXcds;
   if (lid >= g.total_blocks) return;
   // (the products read only the clip value from the state: no order to keep with this)
-  if (g.update_st && blockIdx.x == 0 && threadIdx.x == 0) interval_update(g.update_st);
-  if (g.status_out && blockIdx.x == 0 && threadIdx.x == 0)
+  if (g.update_st && bid == 0 && threadIdx.x == 0) interval_update(g.update_st);
+  if (g.status_out && bid == 0 && threadIdx.x == 0)
     *g.status_out = (g.sc->bad_x | g.sc->bad_w) ? LBT_STATUS_NONFINITE : LBT_STATUS_OK;
   const int m_tile = lid % g.tiles_m;
   const int n_tile = (lid / g.tiles_m) % g.tiles_n;
@@ -475,50 +542,11 @@ __global__ __launch_bounds__(kThreads) void k_implicit_gemm(const GemmArgs g) {
   }
 }
 
-// Sum the split-K partial tiles and apply the scale: out = (sum_s partial[s]) * s_a * s_b.
-// A workgroup takes 256 / SL consecutive outputs; SL groups of threads share the slices
-// (group w sums slices w, w + SL, ..., eight loads in flight per thread) and meet in LDS.
-// SL = 4 for many slices of a small output, SL = 1 for few slices of a large one.
-// Integer adds: the result does not depend on how the slices are grouped.
-// WIDE: the slices are added in 64 bits (their sum may exceed 32 bits; each slice fits).
+// The same sum as a launch of its own (no product launch follows that could carry it).
 template <int SL, bool WIDE>
-__global__ __launch_bounds__(kThreads) void k_splitk_reduce(const int32_t* __restrict__ partial,
-                                                             int splits, long long n, GemmArgs g) {
-  constexpr int OUTS = kThreads / SL;
-  using sum_t = typename std::conditional<WIDE, long long, int>::type;
-  __shared__ sum_t red[SL][OUTS];
-  const float scale = output_scale(g);
-  if (g.update_st && blockIdx.x == 0 && threadIdx.x == 0) interval_update(g.update_st);
-  const int io = threadIdx.x % OUTS, sl = threadIdx.x / OUTS;
-  for (long long base = (long long)blockIdx.x * OUTS; base < n; base += (long long)gridDim.x * OUTS) {
-    const long long i = base + io;
-    sum_t sum = 0;
-    if (i < n) {
-      for (int s0 = sl; s0 < splits; s0 += 8 * SL) {
-        int v[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-          const int sp = s0 + SL * u;
-          v[u] = sp < splits ? partial[(long long)sp * n + i] : 0;
-        }
-        sum += (((sum_t)v[0] + v[1]) + ((sum_t)v[2] + v[3])) + (((sum_t)v[4] + v[5]) + ((sum_t)v[6] + v[7]));
-      }
-    }
-    if (SL > 1) {
-      red[sl][io] = sum;
-      __syncthreads();
-      if (sl == 0) {
-        sum = 0;
-#pragma unroll
-        for (int w = 0; w < SL; ++w) sum += red[w][io];
-      }
-    }
-    if (sl == 0 && i < n) {
-      g.out[i] = (float)sum * scale;
-      if (g.acc) g.acc[i] = (int)sum;   // the host has checked that it fits
-    }
-    if (SL > 1) __syncthreads();
-  }
+__global__ __launch_bounds__(kThreads) void k_splitk_reduce(const PendingReduce r, lbt_grad_state* update_st) {
+  if (update_st && blockIdx.x == 0 && threadIdx.x == 0) interval_update(update_st);
+  reduce_slices<SL, WIDE>(r, blockIdx.x, gridDim.x);
 }
 
 void fill_geom(GemmArgs& g, const ConvGeom& c) {
@@ -548,7 +576,7 @@ int launch_one(const GemmArgs& g, unsigned grid, size_t tap_bytes, hipStream_t s
       return LBT_ERR_HIP;
     if (tracked) raised[device].store(true, std::memory_order_release);
   }
-  LBT_LAUNCH(kernel, dim3(grid), dim3(kThreads), dyn, s, g);
+  LBT_LAUNCH(kernel, dim3(grid + g.red.blocks), dim3(kThreads), dyn, s, g);
   return LBT_OK;
 }
 
@@ -569,6 +597,7 @@ int run_gemm(GemmArgs& g, int mode, int bm, int bn, int splits, int kid, hipStre
   if (total > (1ll << 30)) return LBT_ERR_UNSUPPORTED;
   g.total_blocks = (int)total;
   const unsigned grid = (unsigned)((total + kXcds - 1) / kXcds * kXcds);
+  g.gemm_grid = grid;
   size_t tap_bytes = 0;
   if (mode == 0) {
     if ((size_t)128 * g.R * g.S * sizeof(int) > 25 * 1024) return LBT_ERR_UNSUPPORTED;  // up to 7x7
@@ -644,8 +673,10 @@ int run_direct(GemmArgs& g, int mode, int scale_kind, int kid, hipStream_t s) {
   return run_gemm(g, mode, bm, bn, 1, kid, s);
 }
 
+// defer (may be null): where to leave the sum of the slices for the call's next product
+// launch to carry out, instead of launching it here.
 int run_splitk(GemmArgs& g, bool x_unsigned, long long true_k, int32_t* acc, int32_t* partial,
-               hipStream_t s) {
+               PendingReduce* defer, hipStream_t s) {
   g.scale_kind = x_unsigned ? 2 : 1;
   const SplitPlan plan = plan_split_k(g.M, g.NJ, g.chunks);
   // Every int32 accumulator (one slice of the contraction) must hold its exact sum; the
@@ -669,28 +700,49 @@ int run_splitk(GemmArgs& g, bool x_unsigned, long long true_k, int32_t* acc, int
   g.epi = 1;
   g.acc = nullptr;
   g.partial = partial;
-  lbt_grad_state* const update_st = g.update_st;   // left to the reduce launch
+  lbt_grad_state* const update_st = g.update_st;   // left to the launch that ends the call
   g.update_st = nullptr;
   if ((rc = run_gemm(g, 1, plan.bm, plan.bn, plan.splits, KID_GEMM_DW, s))) return rc;
   const long long n_out = (long long)g.M * g.NJ;
-  ProfScope prof(KID_FINALIZE, (double)n_out, s);
-  g.acc = acc;
-  g.update_st = update_st;
-  const bool many = plan.splits >= 8;
-  long long blocks = (n_out + (many ? 63 : 255)) / (many ? 64 : 256);
+  PendingReduce r{};
+  r.partial = partial;
+  r.splits = plan.splits;
+  r.n = n_out;
+  r.out = g.out;
+  r.acc = acc;
+  r.st = g.st;
+  r.sc = g.sc;
+  r.scale_kind = g.scale_kind;
+  r.bits = g.bits;
+  r.many = plan.splits >= 8;
+  r.wide = wide;
+  long long blocks = (n_out + (r.many ? 63 : 255)) / (r.many ? 64 : 256);
   if (blocks > 4096) blocks = 4096;
-#define LBT_REDUCE_CASE(SL_, WIDE_)                                                              \
-  LBT_LAUNCH((k_splitk_reduce<SL_, WIDE_>), dim3((unsigned)blocks), dim3(kThreads), 0, s, partial,  \
-             plan.splits, n_out, g)
-  if (many && wide) LBT_REDUCE_CASE(4, true);
-  else if (many) LBT_REDUCE_CASE(4, false);
-  else if (wide) LBT_REDUCE_CASE(1, true);
+  r.blocks = (unsigned)blocks;
+  if (defer && !wide) {
+    // a carried sum shares the chip with the product that carries it: fewer workgroups, each
+    // walking more outputs
+    if (r.blocks > 512) r.blocks = 512;
+    *defer = r;
+    return LBT_OK;
+  }
+  return launch_pending_reduce(r, update_st, s);
+}
+
+}  // namespace
+
+int launch_pending_reduce(const PendingReduce& r, lbt_grad_state* update_st, hipStream_t s) {
+  if (!r.blocks) return LBT_OK;
+  ProfScope prof(KID_FINALIZE, (double)r.n, s);
+#define LBT_REDUCE_CASE(SL_, WIDE_)                                                             \
+  LBT_LAUNCH((k_splitk_reduce<SL_, WIDE_>), dim3(r.blocks), dim3(kThreads), 0, s, r, update_st)
+  if (r.many && r.wide) LBT_REDUCE_CASE(4, true);
+  else if (r.many) LBT_REDUCE_CASE(4, false);
+  else if (r.wide) LBT_REDUCE_CASE(1, true);
   else LBT_REDUCE_CASE(1, false);
 #undef LBT_REDUCE_CASE
   return LBT_OK;
 }
-
-}  // namespace
 
 // Measured on the ResNet-50 shapes (every variant of tile and slice count per layer): a dW
 // launch costs 11 us or more whatever its size, and each slice adds its int32 tile twice to
@@ -733,8 +785,9 @@ SplitPlan plan_split_k(int M, int NJ, int chunks) {
 
 int launch_conv_dx(const ConvGeom& c, const uint8_t* w_codes, const uint8_t* g_codes,
                    const lbt_grad_state* st, const OperandScalars* sc, float* dX, int32_t* acc,
-                   lbt_grad_state* update_st, hipStream_t s) {
+                   lbt_grad_state* update_st, const PendingReduce* carry, hipStream_t s) {
   GemmArgs g{};
+  if (carry) g.red = *carry;
   fill_geom(g, c);
   g.A = w_codes;
   g.B = g_codes;
@@ -849,7 +902,8 @@ int launch_linear_fwd(int M, int K_in, int N_out, int bits, const uint8_t* x_cod
 
 int launch_conv_dw(const ConvGeom& c, const uint8_t* g_codes, const uint8_t* x_codes,
                    const lbt_grad_state* st, const OperandScalars* sc, int x_unsigned, float* dW,
-                   int32_t* acc, int32_t* partial, lbt_grad_state* update_st, hipStream_t s) {
+                   int32_t* acc, int32_t* partial, lbt_grad_state* update_st, PendingReduce* defer,
+                   hipStream_t s) {
   GemmArgs g{};
   fill_geom(g, c);
   g.A = g_codes;
@@ -869,15 +923,16 @@ int launch_conv_dw(const ConvGeom& c, const uint8_t* g_codes, const uint8_t* x_c
   g.NJ = c.C * c.R * c.S;
   g.st = st; g.sc = sc; g.update_st = update_st;
   g.out = dW;
-  return run_splitk(g, x_unsigned != 0, (long long)c.N * c.P * c.Q, acc, partial, s);
+  return run_splitk(g, x_unsigned != 0, (long long)c.N * c.P * c.Q, acc, partial, defer, s);
 }
 
 // Linear layer (1x1 image): operands swap roles so that the row-major outputs
 // dX[M][K_in] and dW[K_in][N_out] have their contiguous axis on the lanes.
 int launch_linear_dx(const ConvGeom& c, const uint8_t* w_codes, const uint8_t* g_codes,
                      const lbt_grad_state* st, const OperandScalars* sc, float* dX, int32_t* acc,
-                     lbt_grad_state* update_st, hipStream_t s) {
+                     lbt_grad_state* update_st, const PendingReduce* carry, hipStream_t s) {
   GemmArgs g{};
+  if (carry) g.red = *carry;
   fill_geom(g, c);
   g.A = g_codes;   // [N][Kp/16][16] gradient rows
   g.B = w_codes;   // [C][Kp/16][16] weight rows, read with the (c,r,s)-row gather on a 1x1 image
@@ -899,7 +954,8 @@ int launch_linear_dx(const ConvGeom& c, const uint8_t* w_codes, const uint8_t* g
 
 int launch_linear_dw(const ConvGeom& c, const uint8_t* g_codes, const uint8_t* x_codes,
                      const lbt_grad_state* st, const OperandScalars* sc, int x_unsigned, float* dW,
-                     int32_t* acc, int32_t* partial, lbt_grad_state* update_st, hipStream_t s) {
+                     int32_t* acc, int32_t* partial, lbt_grad_state* update_st, PendingReduce* defer,
+                     hipStream_t s) {
   GemmArgs g{};
   fill_geom(g, c);
   g.A = x_codes;   // [C][Np/16][16] activation rows
@@ -916,7 +972,7 @@ int launch_linear_dw(const ConvGeom& c, const uint8_t* g_codes, const uint8_t* x
   g.NJ = c.K;
   g.st = st; g.sc = sc; g.update_st = update_st;
   g.out = dW;
-  return run_splitk(g, x_unsigned != 0, (long long)c.N, acc, partial, s);
+  return run_splitk(g, x_unsigned != 0, (long long)c.N, acc, partial, defer, s);
 }
 
 }  // namespace lbt

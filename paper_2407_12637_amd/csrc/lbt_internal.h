@@ -259,14 +259,33 @@ struct SplitPlan {
 };
 SplitPlan plan_split_k(int M, int NJ, int chunks);
 
+// The sum of a split contraction's int32 slices, with its scale: left pending by a dW launch
+// (defer), carried out by extra workgroups of the call's next product launch (carry) or by a
+// launch of its own (launch_pending_reduce).  blocks == 0: nothing pending.
+struct PendingReduce {
+  const int32_t* partial;     // [splits][n]
+  int splits;
+  long long n;                // outputs
+  float* out;
+  int32_t* acc;               // optional raw sums
+  const lbt_grad_state* st;   // scale inputs, as for the products
+  const OperandScalars* sc;
+  int scale_kind, bits;
+  int many;                   // >= 8 slices: four thread groups share the slices of an output
+  int wide;                   // slices added in 64 bits (never carried)
+  unsigned blocks;            // workgroups that carry it out
+};
+int launch_pending_reduce(const PendingReduce& r, lbt_grad_state* update_st, hipStream_t s);
+
 // dX: A = W codes [C][R*S][Kp/16][16], B = dY codes [N][Kp/16][P*Q][16]; out/acc [N][C][H][W].
 int launch_conv_dx(const ConvGeom& g, const uint8_t* w_codes, const uint8_t* g_codes,
                    const lbt_grad_state* st, const OperandScalars* sc, float* dX, int32_t* acc,
-                   lbt_grad_state* update_st, hipStream_t s);
+                   lbt_grad_state* update_st, const PendingReduce* carry, hipStream_t s);
 // dW: A = dY codes [K][Np/16][P*Q][16], B = X codes [C][Np/16][H*W][16]; out/acc [K][C][R][S].
 int launch_conv_dw(const ConvGeom& g, const uint8_t* g_codes, const uint8_t* x_codes,
                    const lbt_grad_state* st, const OperandScalars* sc, int x_unsigned, float* dW,
-                   int32_t* acc, int32_t* partial, lbt_grad_state* update_st, hipStream_t s);
+                   int32_t* acc, int32_t* partial, lbt_grad_state* update_st, PendingReduce* defer,
+                   hipStream_t s);
 // Forward products Y = Q(X) . Q(W) (no gradient state: the scale comes from the operand
 // scalars; status_out, may be null, receives the operands' status).
 int launch_conv_fwd(const ConvGeom& g, const uint8_t* w_codes, const uint8_t* x_codes,
@@ -280,9 +299,10 @@ int launch_linear_fwd(int M, int K_in, int N_out, int bits, const uint8_t* x_cod
 // that state (the products read only the scale from it, so the order inside does not matter).
 int launch_linear_dx(const ConvGeom& g, const uint8_t* w_codes, const uint8_t* g_codes,
                      const lbt_grad_state* st, const OperandScalars* sc, float* dX, int32_t* acc,
-                     lbt_grad_state* update_st, hipStream_t s);
+                     lbt_grad_state* update_st, const PendingReduce* carry, hipStream_t s);
 int launch_linear_dw(const ConvGeom& g, const uint8_t* g_codes, const uint8_t* x_codes,
                      const lbt_grad_state* st, const OperandScalars* sc, int x_unsigned, float* dW,
-                     int32_t* acc, int32_t* partial, lbt_grad_state* update_st, hipStream_t s);
+                     int32_t* acc, int32_t* partial, lbt_grad_state* update_st, PendingReduce* defer,
+                     hipStream_t s);
 
 }  // namespace lbt
