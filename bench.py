@@ -97,6 +97,15 @@ def parse():
     ap.add_argument("--copy-probe", action="store_true",
                     help="only run three plain 256 MiB device copies (calibrates the HBM byte "
                          "counters of a rocprofv3 --pmc run) and exit")
+    ap.add_argument("--grad-sets", type=int, default=3,
+                    help="distinct output-gradient tensors per layer; step i quantizes set i mod N, "
+                         "so consecutive steps see fresh draws and gamma follows data that changes")
+    ap.add_argument("--repeats", type=int, default=5,
+                    help="the timed region of K steps is run this many times in all; the headline "
+                         "is the first (the contract's), the median of all is reported beside it")
+    ap.add_argument("--skeleton", action="store_true",
+                    help="with --per-layer: also time every product with its contraction loop "
+                         "skipped (launch + set-up + writing the result)")
     ap.add_argument("--peaks", action="store_true",
                     help="only run the stand-alone probe of the chip's ceilings (HBM read / write / "
                          "copy, LDS reads, back-to-back int8 MFMA) and exit")
@@ -106,7 +115,8 @@ def parse():
 class LayerRun:
     """Device tensors and state of one layer occurrence."""
 
-    def __init__(self, spec, idx, torch, lbt, gen, is_linear, x_unsigned=True, dense=False):
+    def __init__(self, spec, idx, torch, lbt, gen, is_linear, x_unsigned=True, dense=False,
+                 grad_sets=1):
         dev = "cuda"
         self.spec, self.is_linear, self.x_unsigned = spec, is_linear, x_unsigned
         f32 = torch.float32
@@ -120,16 +130,20 @@ class LayerRun:
         if x_unsigned:
             self.X.clamp_(min=0)        # post-ReLU activations, quantized with Eq. 3
         self.W = torch.randn(ws, generator=gen, device=dev, dtype=f32).mul_((2.0 / fan_in) ** 0.5)
-        if dense:
-            # control: uniform over (-1e-3, 1e-3), every code equally likely
-            self.dY = torch.rand(gs, generator=gen, device=dev, dtype=f32).mul_(2e-3).sub_(1e-3)
-        else:
-            # Student-t(nu) = Z / sqrt(chi2_nu / nu), chi2_nu = 2 * Gamma(nu / 2)
-            nu = 2.5
-            z = torch.randn(gs, generator=gen, device=dev, dtype=f32)
-            chi2 = torch._standard_gamma(torch.full(gs, nu / 2, device=dev, dtype=f32), generator=gen) * 2
-            self.dY = (z / (chi2 / nu).sqrt_()).mul_(1e-3)
-            del z, chi2
+        self.dYs = []
+        for _ in range(max(1, grad_sets)):
+            if dense:
+                # control: uniform over (-1e-3, 1e-3), every code equally likely
+                g = torch.rand(gs, generator=gen, device=dev, dtype=f32).mul_(2e-3).sub_(1e-3)
+            else:
+                # Student-t(nu) = Z / sqrt(chi2_nu / nu), chi2_nu = 2 * Gamma(nu / 2)
+                nu = 2.5
+                z = torch.randn(gs, generator=gen, device=dev, dtype=f32)
+                chi2 = torch._standard_gamma(torch.full(gs, nu / 2, device=dev, dtype=f32), generator=gen) * 2
+                g = (z / (chi2 / nu).sqrt_()).mul_(1e-3)
+                del z, chi2
+            self.dYs.append(g)
+        self.dY = self.dYs[0]
         self.dX = torch.empty(xs, device=dev, dtype=f32)
         self.dW = torch.empty(ws, device=dev, dtype=f32)
         self.state = None
@@ -139,6 +153,9 @@ class LayerRun:
         self.saved = None
         self.grad_c = None                   # gradients of (c_w, c_x) when the clips are learned
         self.unfused_ste = False
+
+    def use_grad_set(self, i):
+        self.dY = self.dYs[i % len(self.dYs)]
 
     def keep_codes(self, torch, lbt, flags):
         """What the forward pass of the layer leaves behind: the codes of X and W in the layouts
@@ -307,6 +324,8 @@ def per_layer_report(args, torch, lbt, synth, rounding, gen, vit):
     head = ("%-24s %2s %7s | %7s %6s %5s | %7s %6s %5s %5s %1s | %7s %6s %5s %5s %1s"
             % ("layer", "x", "n_dY(M)", "quant", "GB/s", "%HBM", "dX us", "TOPS", "%MFMA", "%roof",
                "b", "dW us", "TOPS", "%MFMA", "%roof", "b"))
+    if args.skeleton:
+        head += " | %7s %7s" % ("dX skel", "dW skel")
     if args.with_oracle:
         import oracle
         head += " | %9s" % "oracle ms"
@@ -343,6 +362,21 @@ def per_layer_report(args, torch, lbt, synth, rounding, gen, vit):
         prof = lbt.lbt_profile_read()
         lbt.lbt_profile_enable(False)
         us = {k: max((v[1] * 1e3 - ov * v[0]) / reps, 0.0) for k, v in prof.items()}
+        skel = None
+        if args.skeleton:
+            # the same calls with the products' contraction loops skipped
+            lbt.lbt_profile_skeleton(True)
+            lbt.lbt_profile_enable(True)
+            lbt.lbt_profile_read()
+            for r in range(reps):
+                Ls[r % n_inst].run(lbt, ws, rounding)
+            torch.cuda.synchronize()
+            prof2 = lbt.lbt_profile_read()
+            lbt.lbt_profile_enable(False)
+            lbt.lbt_profile_skeleton(False)
+            us2 = {k: max((v[1] * 1e3 - ov * v[0]) / reps, 0.0) for k, v in prof2.items()}
+            skel = (us2.get("k_implicit_gemm(dX)", 0.0),
+                    us2.get("k_implicit_gemm(dW)", 0.0) + us2.get("k_splitk_reduce", 0.0))
         ng, nx, nw = probe.dY.numel(), probe.X.numel(), probe.W.numel()
         ops = spec.gemm_ops
         t_q = us.get("k_absmax3", 0.0) + us.get("k_quantize_layer", 0.0)
@@ -366,6 +400,12 @@ def per_layer_report(args, torch, lbt, synth, rounding, gen, vit):
         gbps = q_bytes / (t_q * 1e-6) / 1e9
         line = ("%-24s %2d %7.2f | %7.1f %6.0f %5.1f | %7.1f %6.0f %5.1f %5.1f %1s | %7.1f %6.0f %5.1f %5.1f %1s"
                 % (spec.name, spec.count, ng / 1e6, t_q, gbps, 100 * gbps / PEAK_HBM_GBPS, *cols))
+        if skel:
+            line += " | %7.1f %7.1f" % skel
+            tot["skel_dx"] = tot.get("skel_dx", 0.0) + skel[0] * spec.count
+            tot["skel_dw"] = tot.get("skel_dw", 0.0) + skel[1] * spec.count
+            tot["full_dx"] = tot.get("full_dx", 0.0) + t_dx * spec.count
+            tot["full_dw"] = tot.get("full_dw", 0.0) + t_dw * spec.count
         if args.with_oracle:
             X, W, dY = (t.cpu().numpy() for t in (probe.X, probe.W, probe.dY))
             ost = oracle.GradState(gamma=args.gamma0, bits=args.bits)
@@ -386,7 +426,7 @@ def per_layer_report(args, torch, lbt, synth, rounding, gen, vit):
     print("x = occurrences in the network; quant = maximum + quantize launches of dY, X and W, rated at "
           "4.5 B per element; %%roof = the layer's own roofline time max(ops / 5.0 POP/s, algorithmic "
           "bytes / 8 TB/s) over the measured time; b = which of the two binds (C compute, M memory); "
-          "dW includes its split reduce.  Event-bracket overhead removed per launch: %.2f us." % ov
+          "dX includes the sum of dW's split contraction (carried by the dX launch).  Event-bracket overhead removed per launch: %.2f us." % ov
           + ("  oracle ms = the CPU oracle's whole backward of the layer (quantizers, both products, "
              "update), one repetition on %d threads." % oracle.num_threads() if args.with_oracle else ""))
     summary = {
@@ -397,22 +437,33 @@ def per_layer_report(args, torch, lbt, synth, rounding, gen, vit):
         "compute_bound_products_frac_of_int8_peak":
             (tot["c_ops"] / (tot["c_t"] * 1e-6) / 1e12 / PEAK_INT8_TOPS) if tot["c_t"] else None,
     }
+    if args.skeleton:
+        summary["skeleton_us_per_step"] = {k: tot[k] for k in ("full_dx", "skel_dx", "full_dw", "skel_dw")}
+        print("dX skel / dW skel = the same launches with the contraction loop skipped: launch, set-up "
+              "(tap tables, addresses), and the epilogue that writes the (all-zero) result; for dW the "
+              "partial tiles and their sum as well.")
     print("occurrence-weighted over the sweep:", json.dumps(summary))
 
 
-def measured_traffic(kernel_class):
-    """HBM bytes per launch (fetched + written) of a kernel class, from the committed summary
-    of the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this benchmark; None if absent."""
-    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles",
-                        "bench_resnet50_b64_hbm_traffic.txt")
+def measured_traffic(kernel_classes):
+    """HBM bytes per launch (fetched + written), summed over the given kernel classes, from the
+    committed summary of the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this benchmark, and
+    that summary's own statement of the commit it was measured at: (bytes or None, source)."""
+    rel = os.path.join("profiles", "bench_resnet50_b64_hbm_traffic.txt")
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), rel)
+    found, source = {}, None
     try:
         for line in open(path):
             f = line.split()
-            if len(f) == 4 and f[0] == "TRAFFIC" and f[1] == kernel_class:
-                return float(f[2].split("=")[1]) + float(f[3].split("=")[1])
+            if len(f) == 4 and f[0] == "TRAFFIC":
+                found[f[1]] = float(f[2].split("=")[1]) + float(f[3].split("=")[1])
+            elif len(f) >= 2 and f[0] == "SOURCE":
+                source = "%s (%s)" % (rel, " ".join(f[1:]))
     except OSError:
-        pass
-    return None
+        return None, None
+    if source is None or any(k not in found for k in kernel_classes):
+        return None, source
+    return sum(found[k] for k in kernel_classes), source
 
 
 def main():
@@ -474,7 +525,8 @@ def main():
         for _ in range(spec.count):
             layers.append(LayerRun(spec, len(layers), torch, lbt, gen,
                                    isinstance(spec, synth.LinearLayer),
-                                   x_unsigned=not vit and args.bits < 8, dense=args.dense_codes))
+                                   x_unsigned=not vit and args.bits < 8, dense=args.dense_codes,
+                                   grad_sets=1 if args.forward else args.grad_sets))
     for L in layers:
         L.state = lbt.new_state(gamma0=args.gamma0, bits=args.bits)
         if args.given_clips or args.learned_clips:
@@ -502,13 +554,17 @@ def main():
         else:
             L.run(lbt, space, rounding)
 
+    counter = [0]     # steps issued so far: step i takes every layer's gradient set i mod N
+
     def make_step(n):
         """One pass over the sweep, layers issued round-robin on n streams (each stream has a
         workspace of its own; n = 1: everything on the current stream)."""
         if n == 1:
             def one_stream():
                 for L in layers:
+                    L.use_grad_set(counter[0])
                     run_layer(L, ws)
+                counter[0] += 1
             return one_stream
         streams = [torch.cuda.Stream() for _ in range(n)]
         spaces = [ws] + [torch.zeros_like(ws) for _ in range(n - 1)]
@@ -518,10 +574,12 @@ def main():
             for st in streams:
                 st.wait_stream(main)
             for i, L in enumerate(layers):
+                L.use_grad_set(counter[0])
                 with torch.cuda.stream(streams[i % n]):
                     run_layer(L, spaces[i % n])
             for st in streams:
                 main.wait_stream(st)
+            counter[0] += 1
         return many_streams
 
     step = make_step(n_streams)
@@ -535,6 +593,15 @@ def main():
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
+    # the same region again (args.repeats in all): run-to-run spread and the median
+    region_ms = [ms_per_step]
+    for _ in range(max(0, args.repeats - 1)):
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        region_ms.append((time.perf_counter() - t1) / args.steps * 1e3)
 
     out = {
         "metric": METRIC, "value": gemm_ops / (dt / args.steps) / 1e12, "unit": "TOPS",
@@ -545,7 +612,10 @@ def main():
                                % ("ViT-L encoder block linear layers (197 tokens)" if vit
                                   else "ResNet-50 bottleneck sweep", len(layers), args.bits,
                                   args.rounding, args.gamma0),
-                   "gemm_GOP_per_step": gemm_ops / 1e9, "grad_elements_per_step": n_grad},
+                   "gemm_GOP_per_step": gemm_ops / 1e9, "grad_elements_per_step": n_grad,
+                   "grad_sets": 1 if args.forward else args.grad_sets},
+        "repeats": {"regions": len(region_ms), "ms_per_step_median": sorted(region_ms)[len(region_ms) // 2],
+                    "ms_per_step_min": min(region_ms), "ms_per_step_max": max(region_ms)},
     }
     if n_streams > 1:
         out["config"]["workload"] += ", layers round-robin on %d streams" % n_streams
@@ -617,8 +687,18 @@ def main():
                 k["GBps"] = work * per / (ms * 1e-3) / 1e9
             kernels[name] = k
         out["kernels"] = kernels
-        dom = max(kernels, key=lambda n: kernels[n]["ms_per_step"])
-        traffic = None if vit else measured_traffic(dom)     # counters were taken on the default sweep
+        # The dominant kernel of the step.  The quantize pass (the maximum sweep and the quantize
+        # sweep over the same tensors: two launches, one kernel in the sense of the scope table)
+        # counts as one; it is rated at the algorithmic 4.5 B per quantized element over the
+        # time of both launches.
+        q, am = kernels.get("k_quantize_layer"), kernels.get("k_absmax3")
+        groups = {n: kernels[n]["ms_per_step"] for n in kernels if n not in ("k_quantize_layer", "k_absmax3")}
+        if q and am:
+            groups["quantize pass (k_absmax3 + k_quantize_layer)"] = q["ms_per_step"] + am["ms_per_step"]
+        dom = max(groups, key=lambda n: groups[n])
+        pass_dom = dom.startswith("quantize pass")
+        traffic, traffic_source = (None, None) if vit else measured_traffic(
+            ("k_absmax3", "k_quantize_layer") if pass_dom else (dom,))   # counters: default sweep only
         if "gemm" in dom:
             # A product class is rated against whichever of its two rooflines binds over the
             # sweep: the int8 matrix cores (its operations) or HBM (its algorithmic bytes: 4-bit
@@ -645,15 +725,26 @@ def main():
                                    "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
                                    "frac": rates["frac_of_int8_peak"], "traffic": traffic}
             out["roofline"]["both_rates"] = rates
+        elif pass_dom:
+            n_all = (0 if args.forward else n_grad) + (0 if args.saved_codes else
+                                                       sum(L.X.numel() + L.W.numel() for L in layers))
+            launches = q["launches_per_step"]
+            per_launch_bytes = n_all * BYTES_PER_GRAD_ELEMENT / launches
+            per_launch_s = (q["avg_us"] + am["avg_us"]) * 1e-6
+            ach = per_launch_bytes / per_launch_s / 1e9
+            out["roofline"] = {"kernel": dom, "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBPS,
+                               "unit": "GB/s", "frac": ach / PEAK_HBM_GBPS, "traffic": traffic,
+                               "algorithmic_bytes_per_launch": per_launch_bytes,
+                               "avg_launch_us": {"k_absmax3": am["avg_us"], "k_quantize_layer": q["avg_us"]}}
         else:
             ach = kernels[dom].get("GBps", 0.0)
             out["roofline"] = {"kernel": dom, "bound": "hbm", "achieved": ach,
                                "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBPS,
                                "traffic": traffic}
+        out["roofline"]["traffic_source"] = traffic_source
         # the quantize pass = the maximum kernel + the quantize kernel (gradient, activations
         # and weights of a layer share both launches), rated at the algorithmic 4.5 B per
         # quantized element
-        q, am = kernels.get("k_quantize_layer"), kernels.get("k_absmax3")
         if q and am:
             n_all = (0 if args.forward else n_grad) + (0 if args.saved_codes else
                                                        sum(L.X.numel() + L.W.numel() for L in layers))

@@ -359,7 +359,13 @@ int lbt_backward_conv2d_acc(const float* X, const float* W, const float* dY, int
  * 2*N*P*Q*K*C*R*S per product); it then clears the records.  Host arrays of
  * `capacity` >= kernel count entries.  lbt_profile_enable also clears.
  * Process-wide; not meant for concurrent use from several threads' streams.
+ *
+ * lbt_profile_skeleton(1): a measurement aid, never for production: until switched off again the
+ * product launches (dX, dW, forward) run their launch, prologue and epilogue but skip the
+ * contraction loop, so that every output is 0 and their duration is what a product costs before
+ * its first multiply (launch, set-up, writing the result).  Process-wide.
  */
+int lbt_profile_skeleton(int on);
 int lbt_profile_enable(int on);
 int lbt_profile_kernel_count(void);
 const char* lbt_profile_kernel_name(int kernel_class);

@@ -97,6 +97,7 @@ SIGNATURES = {
     "lbt_backward_conv2d_saved": (_int, [_p, _sz, _p] + [_i64] * 9 + [_int, _p, _u64, _int,
                                                                       _p, _p, _p, _p, _p, _sz, _p]),
     "lbt_profile_enable": (_int, [_int]),
+    "lbt_profile_skeleton": (_int, [_int]),
     "lbt_profile_kernel_count": (_int, []),
     "lbt_profile_kernel_name": (C.c_char_p, [_int]),
     "lbt_profile_read": (_int, [_p, _p, _p, _int]),
@@ -341,6 +342,10 @@ def lbt_backward_conv2d_saved(saved, dY, N, Cc, H, Wd, K, R, S, stride, pad, x_u
 
 def lbt_profile_enable(on: bool):
     _check(load().lbt_profile_enable(int(on)), "lbt_profile_enable")
+
+
+def lbt_profile_skeleton(on: bool):
+    _check(load().lbt_profile_skeleton(int(on)), "lbt_profile_skeleton")
 
 
 def lbt_profile_read():

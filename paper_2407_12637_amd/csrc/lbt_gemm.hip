@@ -591,6 +591,8 @@ int run_gemm(GemmArgs& g, int mode, int bm, int bn, int splits, int kid, hipStre
   if ((unsigned long long)g.a_bytes >= (1ull << 31) || (unsigned long long)g.b_bytes >= (1ull << 31) ||
       (unsigned long long)(g.M + 128) * g.lda + g.a_bytes >= (1ull << 32))
     return LBT_ERR_UNSUPPORTED;
+  // measurement aid: launch, prologue and epilogue only (the outputs are then all zero)
+  if (profile_skeleton()) g.steps = g.steps_per_split = 0;
   g.tiles_m = (g.M + bm - 1) / bm;
   g.tiles_n = (g.NJ + bn - 1) / bn;
   const long long total = (long long)g.tiles_m * g.tiles_n * splits;

@@ -142,6 +142,9 @@ class ProfScope {
   hipStream_t s_;
 };
 
+// Measurement aid (lbt_profile_skeleton): the product launches skip their contraction loop.
+bool profile_skeleton();
+
 // Every kernel of the library is launched through launch_kernel, which hands back the error
 // of THIS launch (the runtime's "last error" may stem from an earlier call of the caller's).
 template <typename... KArgs, size_t... I>

@@ -22,6 +22,7 @@ struct Record {
 
 std::mutex g_mu;
 std::atomic<bool> g_enabled{false};   // read by every launch without the lock
+std::atomic<bool> g_skeleton{false};  // products skip their contraction loop (measurement aid)
 std::vector<Record> g_records;
 std::vector<hipEvent_t> g_pool;
 
@@ -44,6 +45,8 @@ hipEvent_t take_event() {
 }
 
 }  // namespace
+
+bool profile_skeleton() { return g_skeleton.load(std::memory_order_relaxed); }
 
 ProfScope::ProfScope(int kid, double work, hipStream_t s) : idx_(-1), s_(s) {
   if (!g_enabled.load(std::memory_order_acquire)) return;
@@ -76,6 +79,11 @@ int lbt_profile_enable(int on) {
   }
   g_records.clear();
   g_enabled.store(on != 0, std::memory_order_release);
+  return LBT_OK;
+}
+
+int lbt_profile_skeleton(int on) {
+  g_skeleton.store(on != 0, std::memory_order_relaxed);
   return LBT_OK;
 }
 

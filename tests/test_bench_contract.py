@@ -57,9 +57,12 @@ def test_vit_l_table():
 def test_committed_traffic_summary_is_readable():
     sys.path.insert(0, ROOT)
     import bench
-    t = bench.measured_traffic("k_quantize_layer")
-    assert t is not None and 5e7 < t < 5e8
-    assert bench.measured_traffic("no_such_kernel") is None
+    t, source = bench.measured_traffic(("k_absmax3", "k_quantize_layer"))
+    assert t is not None and 1e8 < t < 6e8       # one layer's pass: both sweeps plus the codes
+    assert source and "commit=" in source          # the summary says what it was measured at
+    one, _ = bench.measured_traffic(("k_quantize_layer",))
+    assert one is not None and one < t
+    assert bench.measured_traffic(("no_such_kernel",))[0] is None
 
 
 def test_seeded_generators_are_reproducible():
