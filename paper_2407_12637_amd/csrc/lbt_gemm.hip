@@ -23,7 +23,7 @@
 // are masked).  A wave's load lands as 1 KiB of consecutive LDS bytes in lane order, so
 // the lane -> (row, chunk) assignment fixes the tile layout:
 //   dense rows (A; B of dW): [row][8 chunks], eight lanes read 128 consecutive bytes of
-//       one row; chunk c of row r sits in slot c ^ (r & 7) so that the 32 rows a
+//       one row; chunk c of row r sits in slot c ^ ((r >> 1) & 7) so that the 32 rows a
 //       fragment read touches fall into different banks;
 //   gathered pixels (B of dX): [chunk][row], 64 lanes read the granules of 64
 //       consecutive pixels (consecutive in memory) and a fragment read is contiguous.
@@ -228,8 +228,13 @@ __global__ __launch_bounds__(kThreads) void k_implicit_gemm(const GemmArgs g) {
 
   // ---- dense-row staging ([row][slot] tiles): load i of a wave covers tile rows
   // (4 i + wave) * 8 .. + 8; lane -> row (lane / 8) of them and slot (lane % 8), which
-  // holds chunk slot ^ (row & 7).  The chunk is the same for all loads of a thread.
-  const int col = (lane & 7) ^ (lane >> 3);
+  // holds chunk slot ^ ((row >> 1) & 7): sixteen consecutive rows of one chunk then fall into
+  // sixteen different 16-byte bank groups (a row is 128 bytes = 8 groups, so rows r and r + 1
+  // differ by 8 groups and the slot permutation has to change every second row; with
+  // slot ^ (row & 7) fragment reads met two-way conflicts: measured, up to one conflict cycle
+  // per active LDS cycle).  The chunk is the same for all loads of a thread:
+  // row = (4 i + wave) * 8 + lane / 8, so (row >> 1) & 7 = 4 (wave & 1) + lane / 16.
+  const int col = (lane & 7) ^ ((4 * (wave & 1) + (lane >> 4)) & 7);
   const int sub = lane >> 3;
   unsigned a_row[NA];
 #pragma unroll
@@ -424,13 +429,13 @@ __global__ __launch_bounds__(kThreads) void k_implicit_gemm(const GemmArgs g) {
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
       const int r = wm + i * 32 + (lane & 31);
-      fa_off[kk][i] = (unsigned)(r * ROWB + ((c ^ (r & 7)) * 16));
+      fa_off[kk][i] = (unsigned)(r * ROWB + ((c ^ ((r >> 1) & 7)) * 16));
     }
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
       const int r = wn + j * 32 + (lane & 31);
       fb_off[kk][j] = (unsigned)(BM * ROWB) +
-                      (MODE == 1 ? (unsigned)(r * ROWB + ((c ^ (r & 7)) * 16)) : (unsigned)((c * BN + r) * 16));
+                      (MODE == 1 ? (unsigned)(r * ROWB + ((c ^ ((r >> 1) & 7)) * 16)) : (unsigned)((c * BN + r) * 16));
     }
   }
 
