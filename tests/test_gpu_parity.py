@@ -130,6 +130,32 @@ def test_interval_converges_like_oracle_and_resumes():
         gu.assert_state_equal(lbt.lbt_state_read(st), ost)
 
 
+def test_state_write_clears_the_internal_words():
+    # a copy of the state taken at any time, even with the internal ticket words set, must
+    # restore to a state the quantizers can use: lbt_state_write zeroes sync_word / sync_max
+    r = synth.rng(0, 12, 1, synth.T_DY)
+    g = synth.grad_cfg4(r, (70000,))
+    st = lbt.new_state(gamma0=0.1)
+    h = lbt.lbt_state_read(st)
+    h.sync_word = 0x0000_0300_0000_0007     # a stale ticket and count
+    h.sync_max = 0x7F800000                  # a stale "non-finite" running maximum
+    h.step = 4
+    lbt.lbt_state_write(st, h)
+    back = lbt.lbt_state_read(st)
+    assert back.sync_word == 0 and back.sync_max == 0 and back.step == 4
+    for flags in (1, 1 | lbt.HINDSIGHT_MAX):
+        ost = oracle.GradState(gamma=0.1, step=4)
+        st2 = lbt.new_state(gamma0=0.1)
+        lbt.lbt_state_write(st2, h)
+        if flags & lbt.HINDSIGHT_MAX:      # one ordinary call first: records a maximum
+            oracle.quantize_grad(g, ost, 3, 1)
+            gu.quantize_grad(g, st2, 3, 1)
+        want = oracle.quantize_grad(g, ost, 3, 1, hindsight=bool(flags & lbt.HINDSIGHT_MAX))
+        packed = gu.quantize_grad(g, st2, 3, flags)
+        gu.assert_state_equal(lbt.lbt_state_read(st2), ost)
+        assert np.array_equal(packed, oracle.pack_nibbles(want))
+
+
 # -- operand quantizer ----------------------------------------------------------------
 @pytest.mark.parametrize("unsigned", [False, True])
 @pytest.mark.parametrize("c", [0.0, 0.7])
